@@ -1,0 +1,180 @@
+/*
+ * rsh_spmm.h -- C ABI of the row-structured hybrid SpMM library for MI355X (gfx950).
+ *
+ * Computes C = A x B (paper, Section 2.2) with A sparse (CSR on entry), B dense
+ * row-major with N columns, binary16 operands, fp32 accumulation and fp32 C
+ * (paper, Section 4.1, Problem Configuration).
+ *
+ * The work is split as in the paper's overview (Section 3.1): a host planning
+ * stage turns the CSR matrix into the RS-Tile representation (Section 3.2) --
+ * row windows packed into bitmap-compressed dense fragments plus a residual
+ * list of irregular rows -- and two device kernels execute the two parts on
+ * disjoint output rows: a dense-fragment kernel on fp16 MFMA (the counterpart
+ * of the pipelined Tensor-Core kernel, Section 3.3.2 / Algorithm 2) and a
+ * wavefront-cooperative kernel for the residual rows (the "CUDA path" of
+ * Section 3.3.2), with long rows and oversized windows split into bounded work
+ * items (Section 3.3.3) whose partial results are summed by a deterministic,
+ * atomic-free combine pass.
+ *
+ * All functions return an int status (RSH_OK == 0).  No exception crosses the
+ * boundary.  Pointers are HOST pointers unless the name ends in _dev.
+ */
+#ifndef RSH_SPMM_H
+#define RSH_SPMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    RSH_OK = 0,
+    RSH_ERR_NULL = 1,          /* a required pointer argument is NULL                          */
+    RSH_ERR_INVALID_CSR = 2,   /* row_ptr not monotone / columns unsorted, duplicated, out of range */
+    RSH_ERR_UNSUPPORTED_N = 3, /* N must be a positive multiple of 16 and at most 4096          */
+    RSH_ERR_BAD_OPTION = 4,    /* an option value is outside its documented range               */
+    RSH_ERR_OOM = 5,           /* host or device allocation failed                              */
+    RSH_ERR_HIP = 6,           /* a HIP runtime call failed (see rsh_last_hip_error)            */
+    RSH_ERR_NOT_UPLOADED = 7,  /* rsh_spmm on a plan created with upload == 0                   */
+    RSH_ERR_TOO_LARGE = 8      /* a 32-bit plan index would overflow (see rsh_plan_create)      */
+};
+
+typedef struct rsh_plan rsh_plan_t; /* opaque */
+
+/* CSR input, host memory, borrowed for the duration of the call only. */
+typedef struct {
+    int64_t n_rows, n_cols, nnz;
+    const int64_t *row_ptr;  /* [n_rows+1], row_ptr[0]==0, non-decreasing, row_ptr[n_rows]==nnz */
+    const int32_t *col_idx;  /* [nnz], strictly increasing inside a row, 0 <= c < n_cols        */
+    const uint16_t *val_f16; /* [nnz], IEEE binary16 bit patterns; stored zeros stay entries    */
+} rsh_csr_t;
+
+/* Planning options.  Obtain defaults with rsh_plan_opts_default, then override. */
+typedef struct {
+    int32_t window_rows;  /* W of Algorithm 1; 16 (one MFMA N-extent) is the only supported value */
+    int32_t tile_k;       /* condensed columns per fragment; 16 is the only supported value     */
+    int32_t tau_nnz;      /* Algorithm 1 row-length threshold; -1 = estimate from the matrix     */
+    int32_t tau_inc;      /* Algorithm 1 column-gain threshold; -1 = estimate                    */
+    int32_t partition;    /* 0 = Algorithm 1 exactly as printed (contiguous windows, head-row test);
+                             1 = cost-guided (default): short low-overlap rows and long rows leave
+                                 first, the rest is grouped W eligible rows at a time, and a window
+                                 whose column reuse nnz/|U| is below min_reuse is dissolved        */
+    int32_t reorder;      /* 0 = keep the given row order, 1 = locality-aware reordering (Section 3.4) */
+    int32_t knn_k;        /* neighbours kept per row in the kNN graph (Algorithm 3, step II)     */
+    float alpha;          /* exponent of the column weight w_j = d_j^-alpha (Section 3.4)        */
+    int32_t max_tiles_per_item; /* bound on fragments per tile work item; 0 = auto              */
+    int32_t max_nnz_per_slice;  /* bound on stored entries per wave slice of a long row; 0 = auto */
+    int32_t force_path;   /* 0 = hybrid, 1 = every row on the irregular path, 2 = every non-empty
+                             row in a window (tests compare the three)                          */
+    float min_reuse;      /* partition == 1: dissolve windows with nnz/|U| below this           */
+    int32_t long_row_nnz; /* partition == 1: rows longer than this go to the irregular path; 0 = auto */
+    int32_t upload;       /* 1 = copy the plan to the current HIP device; 0 = host-only plan    */
+    int32_t threads;      /* host threads used for planning; 0 = all available                  */
+} rsh_plan_opts_t;
+
+/* What the planner built (host side, for tests, logs and the benchmark). */
+typedef struct {
+    int64_t n_rows, n_cols, nnz;
+    int32_t N;
+    int64_t n_windows, n_tiles, nnz_tile;      /* dense-fragment part                            */
+    int64_t n_irregular_rows, nnz_irregular;   /* residual part                                  */
+    int64_t n_empty_rows;
+    int64_t n_tile_items, n_split_windows;     /* tile work items; windows cut into > 1 item     */
+    int64_t n_segments, n_irregular_waves, n_split_rows; /* team segments, waves, rows cut in > 1 slice */
+    int64_t n_combine, n_scratch_slots;        /* combine entries; fp32 rows of N in scratch     */
+    int64_t sum_window_cols;                   /* sum over windows of |U_w| (distinct columns)   */
+    int64_t plan_bytes, csr_bytes;             /* device bytes of the plan vs 6*nnz + 8*(n_rows+1) */
+    int32_t tau_nnz, tau_inc;                  /* thresholds actually used                       */
+    double ms_validate, ms_reorder, ms_partition, ms_pack, ms_worklist, ms_upload, ms_total;
+} rsh_plan_stats_t;
+
+int rsh_plan_opts_default(rsh_plan_opts_t *opts);
+
+/*
+ * Build a plan for C[n_rows][N] = A * B[n_cols][N].  The plan copies everything
+ * it needs; the CSR arrays may be freed after the call.  With opts->upload != 0
+ * the device arrays and the plan's private scratch are allocated on the current
+ * HIP device.  opts == NULL means defaults.
+ * Limits: nnz, n_rows * 1 and n_cols * (2N) must each be below 2^31.
+ */
+int rsh_plan_create(const rsh_csr_t *csr, int32_t N, const rsh_plan_opts_t *opts, rsh_plan_t **out);
+
+/*
+ * Enqueue C = A * B on hip_stream (a hipStream_t; NULL = default stream) and
+ * return without waiting.
+ *   B_dev : device, binary16 [n_cols][N] row-major, leading dimension N, 16-byte aligned.
+ *           Must be finite (padded fragment cells multiply a gathered value by 0).
+ *   C_dev : device, fp32 [n_rows][N] row-major, 16-byte aligned; every element is
+ *           overwritten (no alpha/beta); rows of A with no stored entry become 0.
+ * The library neither allocates, frees nor synchronises on B or C.  The plan owns
+ * one scratch buffer, so two rsh_spmm calls on the same plan must not overlap in
+ * time (use the same stream, or one plan per stream).  Results are bit-identical
+ * from run to run: no atomics are used.
+ */
+int rsh_spmm(const rsh_plan_t *plan, const void *B_dev, void *C_dev, void *hip_stream);
+
+int rsh_plan_destroy(rsh_plan_t *plan); /* NULL is a no-op */
+
+int rsh_plan_stats(const rsh_plan_t *plan, rsh_plan_stats_t *out);
+
+/*
+ * Reconstruct the CSR matrix from the plan's own arrays (the host mirrors of
+ * what the kernels read).  Outputs are caller-allocated: row_ptr [n_rows+1],
+ * col_idx [nnz], val_f16 [nnz], path [nnz] (0 = dense-fragment path, 1 =
+ * irregular path; may be NULL).  Fails with RSH_ERR_INVALID_CSR if some stored
+ * entry is covered zero times or more than once.
+ */
+int rsh_plan_decode(const rsh_plan_t *plan, int64_t *row_ptr, int32_t *col_idx, uint16_t *val_f16,
+                    uint8_t *path);
+
+/* The row processing order pi produced by the reordering stage: order[i] is the
+ * original id of the i-th row.  order is caller-allocated [n_rows]. */
+int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
+
+/*
+ * Read-only access to the host mirror of one plan array (exactly the bytes the
+ * device holds).  *count is the number of elements.
+ *
+ * Dense-fragment part (RS-Tile "TC block part", Section 3.2), W = 16 rows, K = 16 columns:
+ *   RSH_ARR_WIN_ROW      int32  [n_windows*16]  original row id of each window row, -1 = absent
+ *   RSH_ARR_WIN_TILE_OFF uint32 [n_windows+1]   prefix sum of fragments per window
+ *   RSH_ARR_TILE_COLID   int32  [n_tiles*16]    original column of fragment column k; padding
+ *                                               columns repeat the last valid one
+ *   RSH_ARR_TILE_MASK    uint64 [n_tiles*4]     bitmap: cell (row r, column k) is bit
+ *                                               (k/4)*16 + r of word k%4; padding cells are 0
+ *   RSH_ARR_TILE_VAL_OFF uint32 [n_tiles+1]     start of each fragment's values in TILE_VAL,
+ *                                               in elements, always a multiple of 4
+ *   RSH_ARR_TILE_VAL     uint16 []              binary16 values, per fragment ordered by
+ *                                               ((k/4)*16 + r, k%4) ascending; pad elements are 0
+ *   RSH_ARR_TILE_ITEM    uint32 [n_items*4]     {window, first tile, end tile, dst}: dst ==
+ *                                               0xffffffff -> rows of C; else first scratch slot
+ *                                               of a 16-slot partial block
+ * Irregular part (RS-Tile "residual part", Section 3.2):
+ *   RSH_ARR_IRR_COL      int32  []              column ids, CSR order inside a row
+ *   RSH_ARR_IRR_VAL      uint16 []              binary16 values, same order
+ *   RSH_ARR_SEG          uint32 [n_segments*4]  {start, len, dst, kind} per team segment;
+ *                                               kind bit0: dst is a scratch slot (else a row of C,
+ *                                               0xffffffff = nothing to write), bit1: the teams of
+ *                                               this wave hold pieces of one row slice and are summed
+ * Combine:
+ *   RSH_ARR_COMBINE      uint32 [n_combine*4]   {row, first slot, parts, slot stride}
+ */
+enum {
+    RSH_ARR_WIN_ROW = 0, RSH_ARR_WIN_TILE_OFF, RSH_ARR_TILE_COLID, RSH_ARR_TILE_MASK,
+    RSH_ARR_TILE_VAL_OFF, RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL,
+    RSH_ARR_SEG, RSH_ARR_COMBINE, RSH_ARR_COUNT
+};
+int rsh_plan_array(const rsh_plan_t *plan, int32_t which, const void **ptr, int64_t *count);
+
+/* Number of team segments one wave of the irregular kernel consumes for this plan's N. */
+int rsh_plan_teams_per_wave(const rsh_plan_t *plan, int32_t *teams);
+
+const char *rsh_status_string(int status);
+/* Text of the last HIP error seen by the calling thread inside this library ("" if none). */
+const char *rsh_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSH_SPMM_H */

@@ -1,0 +1,71 @@
+"""Independent reader of the RS-Tile plan arrays (paper, Section 3.2) --
+TEST INFRASTRUCTURE ONLY.
+
+Given the raw arrays a plan exposes (the bytes the device kernels read), rebuild
+the list of stored entries (row, column, binary16 bits, path) with plain Python /
+numpy, following only the layout documented in the public header:
+
+* window w owns fragments win_tile_off[w] .. win_tile_off[w+1]; fragment t has 16
+  column ids, a 256-bit map (four 64-bit words; cell (row r, column k) is bit
+  (k // 4) * 16 + r of word k % 4) and a run of values that starts at
+  tile_val_off[t] and is ordered by ((k // 4) * 16 + r, k % 4);
+* an irregular segment (start, len, dst, kind) holds len consecutive entries of one
+  row; the row is dst itself, or, when kind has bit 0 set, the row whose combine
+  entry (row, first slot, parts, stride) covers scratch slot dst.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def entries_from_arrays(win_row, win_tile_off, tile_colid, tile_mask, tile_val_off, tile_val,
+                        irr_col, irr_val, seg, combine, n_scratch_slots):
+    rows, cols, vals, paths = [], [], [], []
+    n_win = len(win_row) // 16
+    for w in range(n_win):
+        for t in range(int(win_tile_off[w]), int(win_tile_off[w + 1])):
+            cells = []
+            for k in range(16):
+                word = int(tile_mask[4 * t + (k % 4)])
+                for r in range(16):
+                    if (word >> ((k // 4) * 16 + r)) & 1:
+                        cells.append(((k // 4) * 16 + r, k % 4, r, k))
+            cells.sort()
+            for pos, (_, _, r, k) in enumerate(cells):
+                row = int(win_row[16 * w + r])
+                assert row >= 0, "a set bit in an absent window row"
+                rows.append(row)
+                cols.append(int(tile_colid[16 * t + k]))
+                vals.append(int(tile_val[int(tile_val_off[t]) + pos]))
+                paths.append(0)
+    slot_row = {}
+    for e in range(len(combine) // 4):
+        row, first, parts, stride = (int(x) for x in combine[4 * e:4 * e + 4])
+        for p in range(parts):
+            slot = first + p * stride
+            assert slot not in slot_row and slot < n_scratch_slots
+            slot_row[slot] = row
+    for s in range(len(seg) // 4):
+        start, length, dst, kind = (int(x) for x in seg[4 * s:4 * s + 4])
+        if length == 0:
+            continue
+        row = slot_row[dst] if (kind & 1) else dst
+        for q in range(length):
+            rows.append(row)
+            cols.append(int(irr_col[start + q]))
+            vals.append(int(irr_val[start + q]))
+            paths.append(1)
+    return (np.array(rows, dtype=np.int64), np.array(cols, dtype=np.int64),
+            np.array(vals, dtype=np.uint16), np.array(paths, dtype=np.uint8))
+
+
+def csr_from_entries(rows, cols, vals, paths, n_rows, n_cols):
+    """Sort entries into CSR; raises if an entry is covered twice."""
+    keys = rows * n_cols + cols
+    order = np.argsort(keys, kind="stable")
+    keys = keys[order]
+    if keys.size > 1 and np.any(keys[1:] == keys[:-1]):
+        raise AssertionError("a stored entry appears more than once in the plan")
+    row_ptr = np.zeros(n_rows + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows, minlength=n_rows), out=row_ptr[1:])
+    return row_ptr, cols[order].astype(np.int32), vals[order], paths[order]

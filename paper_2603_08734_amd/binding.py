@@ -1,0 +1,194 @@
+"""Thin ctypes binding of ``librsh.so`` (argument marshalling only).
+
+Names follow the C ABI declared in ``include/rsh_spmm.h``.  Every step of the
+path runs inside the library; nothing here computes.  There is no CPU
+fallback: if the library cannot be loaded the import of a symbol fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+RSH_OK = 0
+(RSH_ERR_NULL, RSH_ERR_INVALID_CSR, RSH_ERR_UNSUPPORTED_N, RSH_ERR_BAD_OPTION, RSH_ERR_OOM,
+ RSH_ERR_HIP, RSH_ERR_NOT_UPLOADED, RSH_ERR_TOO_LARGE) = range(1, 9)
+
+(RSH_ARR_WIN_ROW, RSH_ARR_WIN_TILE_OFF, RSH_ARR_TILE_COLID, RSH_ARR_TILE_MASK, RSH_ARR_TILE_VAL_OFF,
+ RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL, RSH_ARR_SEG, RSH_ARR_COMBINE,
+ RSH_ARR_COUNT) = range(12)
+
+_ARRAY_DTYPES = {
+    RSH_ARR_WIN_ROW: np.int32, RSH_ARR_WIN_TILE_OFF: np.uint32, RSH_ARR_TILE_COLID: np.int32,
+    RSH_ARR_TILE_MASK: np.uint64, RSH_ARR_TILE_VAL_OFF: np.uint32, RSH_ARR_TILE_VAL: np.uint16,
+    RSH_ARR_TILE_ITEM: np.uint32, RSH_ARR_IRR_COL: np.int32, RSH_ARR_IRR_VAL: np.uint16,
+    RSH_ARR_SEG: np.uint32, RSH_ARR_COMBINE: np.uint32,
+}
+
+EXPORTED_SYMBOLS = [
+    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_plan_destroy", "rsh_plan_stats",
+    "rsh_plan_decode", "rsh_plan_row_order", "rsh_plan_array", "rsh_plan_teams_per_wave",
+    "rsh_status_string", "rsh_last_hip_error",
+]
+
+
+class rsh_csr_t(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int64), ("n_cols", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("val_f16", ctypes.c_void_p)]
+
+
+class rsh_plan_opts_t(ctypes.Structure):
+    _fields_ = [("window_rows", ctypes.c_int32), ("tile_k", ctypes.c_int32), ("tau_nnz", ctypes.c_int32),
+                ("tau_inc", ctypes.c_int32), ("partition", ctypes.c_int32), ("reorder", ctypes.c_int32),
+                ("knn_k", ctypes.c_int32), ("alpha", ctypes.c_float), ("max_tiles_per_item", ctypes.c_int32),
+                ("max_nnz_per_slice", ctypes.c_int32), ("force_path", ctypes.c_int32),
+                ("min_reuse", ctypes.c_float), ("long_row_nnz", ctypes.c_int32), ("upload", ctypes.c_int32),
+                ("threads", ctypes.c_int32)]
+
+
+class rsh_plan_stats_t(ctypes.Structure):
+    _fields_ = ([(n, ctypes.c_int64) for n in ("n_rows", "n_cols", "nnz")] + [("N", ctypes.c_int32)] +
+                [(n, ctypes.c_int64) for n in (
+                    "n_windows", "n_tiles", "nnz_tile", "n_irregular_rows", "nnz_irregular", "n_empty_rows",
+                    "n_tile_items", "n_split_windows", "n_segments", "n_irregular_waves", "n_split_rows",
+                    "n_combine", "n_scratch_slots", "sum_window_cols", "plan_bytes", "csr_bytes")] +
+                [("tau_nnz", ctypes.c_int32), ("tau_inc", ctypes.c_int32)] +
+                [(n, ctypes.c_double) for n in ("ms_validate", "ms_reorder", "ms_partition", "ms_pack",
+                                                "ms_worklist", "ms_upload", "ms_total")])
+
+    def as_dict(self) -> dict:
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load ``librsh.so`` (building it first only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build(force=True)
+        L = ctypes.CDLL(_build.LIB)
+        vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
+        L.rsh_plan_opts_default.argtypes = [ctypes.POINTER(rsh_plan_opts_t)]
+        L.rsh_plan_create.argtypes = [ctypes.POINTER(rsh_csr_t), i32, ctypes.POINTER(rsh_plan_opts_t),
+                                      ctypes.POINTER(vp)]
+        L.rsh_spmm.argtypes = [vp, vp, vp, vp]
+        L.rsh_plan_destroy.argtypes = [vp]
+        L.rsh_plan_stats.argtypes = [vp, ctypes.POINTER(rsh_plan_stats_t)]
+        L.rsh_plan_decode.argtypes = [vp, vp, vp, vp, vp]
+        L.rsh_plan_row_order.argtypes = [vp, vp]
+        L.rsh_plan_array.argtypes = [vp, i32, ctypes.POINTER(vp), i64p]
+        L.rsh_plan_teams_per_wave.argtypes = [vp, ctypes.POINTER(i32)]
+        L.rsh_status_string.argtypes = [ctypes.c_int]
+        L.rsh_status_string.restype = ctypes.c_char_p
+        L.rsh_last_hip_error.argtypes = []
+        L.rsh_last_hip_error.restype = ctypes.c_char_p
+        for name in EXPORTED_SYMBOLS:
+            if name not in ("rsh_status_string", "rsh_last_hip_error"):
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+class RshError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        msg = lib().rsh_status_string(status).decode()
+        if status == RSH_ERR_HIP:
+            msg += ": " + lib().rsh_last_hip_error().decode()
+        super().__init__(f"rsh status {status}: {msg}")
+
+
+def _check(status: int) -> None:
+    if status != RSH_OK:
+        raise RshError(status)
+
+
+def rsh_plan_opts_default() -> rsh_plan_opts_t:
+    o = rsh_plan_opts_t()
+    _check(lib().rsh_plan_opts_default(ctypes.byref(o)))
+    return o
+
+
+class Plan:
+    """Owner of one ``rsh_plan_t`` handle."""
+
+    def __init__(self, row_ptr, col_idx, val_f16, n_cols: int, N: int, opts: rsh_plan_opts_t | None = None, **kw):
+        row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+        col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+        val = np.ascontiguousarray(val_f16)
+        if val.dtype == np.float16:
+            val = val.view(np.uint16)
+        assert val.dtype == np.uint16
+        if opts is None:
+            opts = rsh_plan_opts_default()
+        for k, v in kw.items():
+            if not hasattr(opts, k):
+                raise TypeError(f"unknown plan option {k}")
+            setattr(opts, k, v)
+        self.n_rows, self.n_cols, self.nnz, self.N = row_ptr.shape[0] - 1, int(n_cols), int(col_idx.shape[0]), int(N)
+        csr = rsh_csr_t(self.n_rows, self.n_cols, self.nnz, row_ptr.ctypes.data, col_idx.ctypes.data, val.ctypes.data)
+        self._h = ctypes.c_void_p()
+        _check(lib().rsh_plan_create(ctypes.byref(csr), N, ctypes.byref(opts), ctypes.byref(self._h)))
+
+    # --- rsh_spmm -----------------------------------------------------------
+    def spmm(self, B, C, stream=None) -> None:
+        """Enqueue C = A @ B.  B, C are device tensors (torch) or raw device addresses."""
+        b_ptr = B.data_ptr() if hasattr(B, "data_ptr") else int(B)
+        c_ptr = C.data_ptr() if hasattr(C, "data_ptr") else int(C)
+        if hasattr(B, "shape"):
+            assert tuple(B.shape) == (self.n_cols, self.N) and B.is_contiguous() and B.element_size() == 2
+            assert tuple(C.shape) == (self.n_rows, self.N) and C.is_contiguous() and C.element_size() == 4
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        _check(lib().rsh_spmm(self._h, ctypes.c_void_p(b_ptr), ctypes.c_void_p(c_ptr), ctypes.c_void_p(stream)))
+
+    # --- introspection ------------------------------------------------------
+    def stats(self) -> dict:
+        st = rsh_plan_stats_t()
+        _check(lib().rsh_plan_stats(self._h, ctypes.byref(st)))
+        return st.as_dict()
+
+    def decode(self):
+        row_ptr = np.empty(self.n_rows + 1, dtype=np.int64)
+        col_idx = np.empty(self.nnz, dtype=np.int32)
+        val = np.empty(self.nnz, dtype=np.uint16)
+        path = np.empty(self.nnz, dtype=np.uint8)
+        _check(lib().rsh_plan_decode(self._h, row_ptr.ctypes.data, col_idx.ctypes.data, val.ctypes.data, path.ctypes.data))
+        return row_ptr, col_idx, val, path
+
+    def row_order(self) -> np.ndarray:
+        order = np.empty(self.n_rows, dtype=np.int32)
+        _check(lib().rsh_plan_row_order(self._h, order.ctypes.data))
+        return order
+
+    def array(self, which: int) -> np.ndarray:
+        ptr, cnt = ctypes.c_void_p(), ctypes.c_int64()
+        _check(lib().rsh_plan_array(self._h, which, ctypes.byref(ptr), ctypes.byref(cnt)))
+        dt = np.dtype(_ARRAY_DTYPES[which])
+        if cnt.value == 0:
+            return np.empty(0, dtype=dt)
+        buf = (ctypes.c_char * (cnt.value * dt.itemsize)).from_address(ptr.value)
+        return np.frombuffer(buf, dtype=dt).copy()
+
+    def teams_per_wave(self) -> int:
+        t = ctypes.c_int32()
+        _check(lib().rsh_plan_teams_per_wave(self._h, ctypes.byref(t)))
+        return t.value
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib().rsh_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,281 @@
+// C ABI of the library: plan life cycle, upload, launch, introspection.
+#include <hip/hip_runtime_api.h>
+
+#include <chrono>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "launch.hpp"
+#include "plan.hpp"
+
+struct rsh_plan {
+    rsh::HostPlan host;
+    rsh::DevicePlan dev;
+    bool uploaded = false;
+    int device = -1;
+};
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+bool hip_ok(hipError_t e) {
+    if (e == hipSuccess) return true;
+    g_hip_error = hipGetErrorString(e);
+    (void)hipGetLastError();
+    return false;
+}
+
+double ms_since(std::chrono::steady_clock::time_point t0) {
+    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+}
+
+template <class T>
+int upload_array(const std::vector<T>& h, T** d) {
+    *d = nullptr;
+    const size_t bytes = (h.size() ? h.size() : 1) * sizeof(T);
+    if (!hip_ok(hipMalloc((void**)d, bytes))) return RSH_ERR_OOM;
+    if (!h.empty() && !hip_ok(hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice))) return RSH_ERR_HIP;
+    return RSH_OK;
+}
+
+void free_device(rsh::DevicePlan& d) {
+    void* ptrs[] = {d.win_row, d.win_tile_off, d.tile_colid, d.tile_mask, d.tile_val_off, d.tile_val,
+                    d.tile_item, d.irr_col, d.irr_val, d.seg, d.combine, d.scratch};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    d = rsh::DevicePlan{};
+}
+
+int upload_plan(rsh_plan& p) {
+    rsh::HostPlan& h = p.host;
+    rsh::DevicePlan& d = p.dev;
+    d.geo = h.geo;
+    d.n_tile_items = (int64_t)h.tile_item.size() / 4;
+    d.n_segments = (int64_t)h.seg.size() / 4;
+    d.n_combine = (int64_t)h.combine.size() / 4;
+    d.n_scratch_slots = h.n_scratch_slots;
+    int rc;
+    if ((rc = upload_array(h.win_row, &d.win_row))) return rc;
+    if ((rc = upload_array(h.win_tile_off, &d.win_tile_off))) return rc;
+    if ((rc = upload_array(h.tile_colid, &d.tile_colid))) return rc;
+    if ((rc = upload_array(h.tile_mask, &d.tile_mask))) return rc;
+    if ((rc = upload_array(h.tile_val_off, &d.tile_val_off))) return rc;
+    if ((rc = upload_array(h.tile_val, &d.tile_val))) return rc;
+    if ((rc = upload_array(h.tile_item, &d.tile_item))) return rc;
+    if ((rc = upload_array(h.irr_col, &d.irr_col))) return rc;
+    if ((rc = upload_array(h.irr_val, &d.irr_val))) return rc;
+    if ((rc = upload_array(h.seg, &d.seg))) return rc;
+    if ((rc = upload_array(h.combine, &d.combine))) return rc;
+    const size_t sbytes = (size_t)std::max<int64_t>(1, h.n_scratch_slots) * (size_t)h.geo.N * sizeof(float);
+    if (!hip_ok(hipMalloc((void**)&d.scratch, sbytes))) return RSH_ERR_OOM;
+    if (!hip_ok(hipGetDevice(&p.device))) return RSH_ERR_HIP;
+    p.uploaded = true;
+    return RSH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rsh_plan_opts_default(rsh_plan_opts_t* o) {
+    if (!o) return RSH_ERR_NULL;
+    std::memset(o, 0, sizeof(*o));
+    o->window_rows = rsh::kW;
+    o->tile_k = rsh::kK;
+    o->tau_nnz = -1;
+    o->tau_inc = -1;
+    o->partition = 1;
+    o->reorder = 0;
+    o->knn_k = 8;
+    o->alpha = 0.5f;
+    o->max_tiles_per_item = 0;
+    o->max_nnz_per_slice = 0;
+    o->force_path = 0;
+    o->min_reuse = 1.25f;
+    o->long_row_nnz = 0;
+    o->upload = 1;
+    o->threads = 0;
+    return RSH_OK;
+}
+
+int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts, rsh_plan_t** out) {
+    if (!csr || !out) return RSH_ERR_NULL;
+    *out = nullptr;
+    if (N <= 0 || N % 16 != 0 || N > 4096) return RSH_ERR_UNSUPPORTED_N;
+    rsh_plan_opts_t o;
+    rsh_plan_opts_default(&o);
+    if (opts) o = *opts;
+    if (o.window_rows != rsh::kW || o.tile_k != rsh::kK) return RSH_ERR_BAD_OPTION;
+    if (o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2) return RSH_ERR_BAD_OPTION;
+    if (o.reorder < 0 || o.reorder > 1 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
+    if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
+    if (o.threads < 0) return RSH_ERR_BAD_OPTION;
+
+    const auto t_all = std::chrono::steady_clock::now();
+    auto t0 = t_all;
+    int rc = rsh::validate_csr(*csr);
+    if (rc) return rc;
+    if (csr->nnz >= (1ll << 31) || csr->n_rows >= (1ll << 31) - 1 || csr->n_cols >= (1ll << 31) ||
+        csr->n_cols * 2 * (int64_t)N >= (1ll << 31) * 2)
+        return RSH_ERR_TOO_LARGE;
+    rsh_plan* p = new (std::nothrow) rsh_plan;
+    if (!p) return RSH_ERR_OOM;
+    try {
+        rsh::HostPlan& h = p->host;
+        const int threads = o.threads > 0 ? o.threads : rsh::hardware_threads();
+        h.n_rows = csr->n_rows;
+        h.n_cols = csr->n_cols;
+        h.nnz = csr->nnz;
+        h.geo = rsh::make_geometry(N);
+        h.opts = o;
+        std::vector<int32_t> col_deg;
+        rsh::column_degrees(*csr, col_deg, threads);
+        h.stats.ms_validate = ms_since(t0);
+
+        t0 = std::chrono::steady_clock::now();
+        if (o.reorder) {
+            rc = rsh::reorder_rows(*csr, o, col_deg, h.order, threads);
+            if (rc) throw rc;
+        } else {
+            h.order.resize((size_t)csr->n_rows);
+            for (int64_t i = 0; i < csr->n_rows; ++i) h.order[(size_t)i] = (int32_t)i;
+        }
+        const double ms_reorder = ms_since(t0);
+
+        t0 = std::chrono::steady_clock::now();
+        int32_t tau_nnz, tau_inc;
+        rsh::estimate_threshold(csr->n_rows, csr->nnz, &tau_nnz, &tau_inc);
+        if (o.tau_nnz >= 0) tau_nnz = o.tau_nnz;
+        if (o.tau_inc >= 0) tau_inc = o.tau_inc;
+        rsh::Partition part;
+        rsh::partition_rows(*csr, o, h.order, tau_nnz, tau_inc, part, threads);
+        const double ms_partition = ms_since(t0);
+
+        t0 = std::chrono::steady_clock::now();
+        rc = rsh::pack_plan(*csr, part, h, threads);
+        if (rc) throw rc;
+        const double ms_pack = ms_since(t0);
+
+        h.stats.ms_validate = h.stats.ms_validate;
+        h.stats.ms_reorder = ms_reorder;
+        h.stats.ms_partition = ms_partition;
+        h.stats.ms_pack = ms_pack;
+        h.stats.ms_worklist = 0.0;   // work lists are emitted inside the packing pass
+        h.stats.tau_nnz = tau_nnz;
+        h.stats.tau_inc = tau_inc;
+
+        t0 = std::chrono::steady_clock::now();
+        if (o.upload) {
+            rc = upload_plan(*p);
+            if (rc) throw rc;
+        }
+        h.stats.ms_upload = ms_since(t0);
+        h.stats.ms_total = ms_since(t_all);
+    } catch (int code) {
+        free_device(p->dev);
+        delete p;
+        return code;
+    } catch (const std::bad_alloc&) {
+        free_device(p->dev);
+        delete p;
+        return RSH_ERR_OOM;
+    } catch (...) {
+        free_device(p->dev);
+        delete p;
+        return RSH_ERR_OOM;
+    }
+    *out = p;
+    return RSH_OK;
+}
+
+int rsh_spmm(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_stream) {
+    if (!plan) return RSH_ERR_NULL;
+    if (!plan->uploaded) return RSH_ERR_NOT_UPLOADED;
+    if (plan->host.n_rows == 0) return RSH_OK;
+    if (!C_dev || (!B_dev && plan->host.nnz > 0)) return RSH_ERR_NULL;
+    if (((uintptr_t)B_dev & 15u) || ((uintptr_t)C_dev & 15u)) return RSH_ERR_BAD_OPTION;
+    const int rc = rsh::launch_spmm(plan->dev, B_dev, C_dev, hip_stream);
+    if (rc == RSH_ERR_HIP) g_hip_error = "kernel launch failed";
+    return rc;
+}
+
+int rsh_plan_destroy(rsh_plan_t* plan) {
+    if (!plan) return RSH_OK;
+    if (plan->uploaded) free_device(plan->dev);
+    delete plan;
+    return RSH_OK;
+}
+
+int rsh_plan_stats(const rsh_plan_t* plan, rsh_plan_stats_t* out) {
+    if (!plan || !out) return RSH_ERR_NULL;
+    *out = plan->host.stats;
+    return RSH_OK;
+}
+
+int rsh_plan_decode(const rsh_plan_t* plan, int64_t* row_ptr, int32_t* col_idx, uint16_t* val_f16, uint8_t* path) {
+    if (!plan || !row_ptr) return RSH_ERR_NULL;
+    if (plan->host.nnz > 0 && (!col_idx || !val_f16)) return RSH_ERR_NULL;
+    try {
+        return rsh::decode_plan(plan->host, row_ptr, col_idx, val_f16, path);
+    } catch (...) {
+        return RSH_ERR_OOM;
+    }
+}
+
+int rsh_plan_row_order(const rsh_plan_t* plan, int32_t* order) {
+    if (!plan || (!order && plan->host.n_rows > 0)) return RSH_ERR_NULL;
+    if (plan->host.n_rows > 0) std::memcpy(order, plan->host.order.data(), (size_t)plan->host.n_rows * sizeof(int32_t));
+    return RSH_OK;
+}
+
+int rsh_plan_array(const rsh_plan_t* plan, int32_t which, const void** ptr, int64_t* count) {
+    if (!plan || !ptr || !count) return RSH_ERR_NULL;
+    const rsh::HostPlan& h = plan->host;
+#define RSH_CASE(id, vec) \
+    case id:              \
+        *ptr = (vec).data(); \
+        *count = (int64_t)(vec).size(); \
+        return RSH_OK;
+    switch (which) {
+        RSH_CASE(RSH_ARR_WIN_ROW, h.win_row)
+        RSH_CASE(RSH_ARR_WIN_TILE_OFF, h.win_tile_off)
+        RSH_CASE(RSH_ARR_TILE_COLID, h.tile_colid)
+        RSH_CASE(RSH_ARR_TILE_MASK, h.tile_mask)
+        RSH_CASE(RSH_ARR_TILE_VAL_OFF, h.tile_val_off)
+        RSH_CASE(RSH_ARR_TILE_VAL, h.tile_val)
+        RSH_CASE(RSH_ARR_TILE_ITEM, h.tile_item)
+        RSH_CASE(RSH_ARR_IRR_COL, h.irr_col)
+        RSH_CASE(RSH_ARR_IRR_VAL, h.irr_val)
+        RSH_CASE(RSH_ARR_SEG, h.seg)
+        RSH_CASE(RSH_ARR_COMBINE, h.combine)
+        default: return RSH_ERR_BAD_OPTION;
+    }
+#undef RSH_CASE
+}
+
+int rsh_plan_teams_per_wave(const rsh_plan_t* plan, int32_t* teams) {
+    if (!plan || !teams) return RSH_ERR_NULL;
+    *teams = plan->host.geo.irr_teams;
+    return RSH_OK;
+}
+
+const char* rsh_status_string(int status) {
+    switch (status) {
+        case RSH_OK: return "ok";
+        case RSH_ERR_NULL: return "null pointer argument";
+        case RSH_ERR_INVALID_CSR: return "invalid CSR (row_ptr not monotone, or columns unsorted / duplicated / out of range)";
+        case RSH_ERR_UNSUPPORTED_N: return "unsupported N (must be a positive multiple of 16, at most 4096)";
+        case RSH_ERR_BAD_OPTION: return "option or argument out of range";
+        case RSH_ERR_OOM: return "out of memory";
+        case RSH_ERR_HIP: return "HIP runtime error";
+        case RSH_ERR_NOT_UPLOADED: return "plan was created host-only (upload == 0)";
+        case RSH_ERR_TOO_LARGE: return "matrix too large for 32-bit plan indices";
+        default: return "unknown status";
+    }
+}
+
+const char* rsh_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

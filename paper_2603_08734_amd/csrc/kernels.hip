@@ -1,0 +1,330 @@
+// Device kernels (gfx950 / CDNA4, wave64) and their launchers.
+//
+//   rsh_tile_kernel      dense-fragment path: the MFMA counterpart of the pipelined
+//                        Tensor-Core kernel (paper, Section 3.3.2, Algorithm 2)
+//   rsh_irregular_kernel residual rows (Section 3.3.2, "CUDA path"), teams of lanes own
+//                        feature columns, long rows arrive as bounded slices (Section 3.3.3)
+//   rsh_combine_kernel   fixed-order sum of the partial results of split windows / rows
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include "launch.hpp"
+
+namespace rsh {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWavesPerBlock = 4;
+
+// Workgroups are dealt to the 8 XCDs round-robin; each XCD has its own L2.  Remap the
+// block index so that one XCD walks a contiguous eighth of the work list and rows that
+// are neighbours in the plan share an L2.  `per_xcd` = gridDim.x / 8.
+__device__ __forceinline__ uint32_t xcd_contiguous_block(uint32_t b, uint32_t per_xcd) {
+    return (b & 7u) * per_xcd + (b >> 3);
+}
+
+__device__ __forceinline__ int shfl_i32(int v, int src_lane) { return __builtin_amdgcn_ds_bpermute(src_lane << 2, v); }
+__device__ __forceinline__ float shfl_f32(float v, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
+}
+
+// Number of set bits of a 64-bit wave-uniform mask below this lane.
+__device__ __forceinline__ uint32_t bits_below_lane(uint64_t m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+union Pack16 {
+    uint4 u;
+    __half h[8];
+};
+
+// ---------------------------------------------------------------------------
+// Irregular rows.  A wave is G = 64/TPR teams of TPR lanes; lane t of a team owns
+// features [8t, 8t+8) of the current panel, so a team reads one B row segment as TPR
+// coalesced 16-byte loads.  Each team walks its own segment of stored entries; the
+// (column, value) pairs of TPR consecutive entries are fetched by the team's lanes in
+// one coalesced load and handed round with a cross-lane read.  A wave whose teams
+// hold pieces of the same row slice sums them with a butterfly over the teams.
+// ---------------------------------------------------------------------------
+template <int TPR>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
+    const uint4* __restrict__ seg, uint32_t n_waves, uint32_t blocks_per_xcd,
+    const int32_t* __restrict__ irr_col, const uint16_t* __restrict__ irr_val,
+    const __half* __restrict__ B, float* __restrict__ C, float* __restrict__ scratch, int N) {
+    constexpr int G = 64 / TPR;
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(
+        xcd_contiguous_block(blockIdx.x, blocks_per_xcd) * kWavesPerBlock + (threadIdx.x >> 6));
+    if (wave >= n_waves) return;
+    const int team = lane / TPR, tl = lane % TPR, team_base = team * TPR;
+    const int feat = blockIdx.y * (TPR * 8) + tl * 8;
+
+    const uint4 s = seg[(size_t)wave * G + team];
+    const uint32_t start = s.x, len = s.y, dst = s.z, kind = s.w;
+
+    // longest segment among the teams (wave-uniform loop bound)
+    uint32_t max_len = len;
+#pragma unroll
+    for (int off = TPR; off < 64; off <<= 1) max_len = max(max_len, (uint32_t)shfl_i32((int)max_len, lane ^ off));
+    max_len = __builtin_amdgcn_readfirstlane(max_len);
+
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+
+    const __half* Bp = B + feat;
+    for (uint32_t base = 0; base < max_len; base += TPR) {
+        const uint32_t p = base + tl;
+        const bool ok = p < len;
+        const int my_col = ok ? irr_col[start + p] : 0;
+        const float my_val = ok ? __half2float(__ushort_as_half(irr_val[start + p])) : 0.f;
+        const int steps = (int)min((uint32_t)TPR, max_len - base);
+        int j = 0;
+        for (; j + 4 <= steps; j += 4) {
+            Pack16 b[4];
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = shfl_i32(my_col, team_base + j + u);
+                v[u] = shfl_f32(my_val, team_base + j + u);
+                b[u].u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = fmaf(v[u], __half2float(b[u].h[i]), acc[i]);
+        }
+        for (; j < steps; ++j) {
+            const int c = shfl_i32(my_col, team_base + j);
+            const float v = shfl_f32(my_val, team_base + j);
+            Pack16 b;
+            b.u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = fmaf(v, __half2float(b.h[i]), acc[i]);
+        }
+    }
+
+    if (kind & kSegWaveReduce) {
+#pragma unroll
+        for (int off = TPR; off < 64; off <<= 1)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += shfl_f32(acc[i], lane ^ off);
+        if (team != 0) return;
+    }
+    if (dst == kNoDst) return;
+    float* out = ((kind & kSegToScratch) ? scratch : C) + (size_t)dst * N + feat;
+    *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+}
+
+// ---------------------------------------------------------------------------
+// Dense fragments.  One wave per work item (a window or a bounded run of its
+// fragments).  Per fragment the wave gathers the 16 B rows named by the fragment's
+// column ids with coalesced 16-byte loads, stages them in LDS, expands the bitmap-
+// compressed 16x16 piece of A into an MFMA operand with popcount prefixes, and issues
+// one v_mfma_f32_16x16x16_f16 per 16-feature chunk.  The product is formed transposed
+// (features along M, window rows along N) so that a lane ends up owning 4*NCH
+// consecutive features of one output row and stores them as 16-byte vectors.
+//
+// MFMA 16x16x16 f16 operand layout (lane l, i = 0..3):
+//   A[m = l%16][k = 4*(l/16)+i]   B[k = 4*(l/16)+i][n = l%16]   D[m = 4*(l/16)+i][n = l%16]
+// Chunk c maps M index m to feature (m/4)*(4*NCH) + 4c + m%4.
+// ---------------------------------------------------------------------------
+template <int NCH>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
+    const uint4* __restrict__ items, uint32_t n_items, uint32_t blocks_per_xcd,
+    const int32_t* __restrict__ win_row, const int32_t* __restrict__ tile_colid,
+    const uint64_t* __restrict__ tile_mask, const uint32_t* __restrict__ tile_val_off,
+    const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, float* __restrict__ C,
+    float* __restrict__ scratch, int N) {
+    constexpr int P = 16 * NCH;            // features per panel
+    constexpr int TPR = P / 8;             // lanes per B row (16 bytes each)
+    constexpr int RPI = TPR >= 64 ? 1 : 64 / TPR;   // B rows per load instruction
+    constexpr int ROWS_PER_LOAD = RPI > 16 ? 16 : RPI;
+    constexpr int NLD = 16 / ROWS_PER_LOAD;
+    constexpr int LDB = P + 8;             // LDS row stride in halves (16-byte aligned, skews banks)
+    __shared__ __attribute__((aligned(16))) _Float16 lds_b[kWavesPerBlock][16 * LDB];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWavesPerBlock][256 + 8];
+
+    const int lane = threadIdx.x & 63;
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t item = xcd_contiguous_block(blockIdx.x, blocks_per_xcd) * kWavesPerBlock + wib;
+    if (item >= n_items) return;
+    const uint4 it = items[item];
+    const uint32_t win = __builtin_amdgcn_readfirstlane(it.x), t_begin = __builtin_amdgcn_readfirstlane(it.y);
+    const uint32_t t_end = __builtin_amdgcn_readfirstlane(it.z), dst = __builtin_amdgcn_readfirstlane(it.w);
+    const int panel = blockIdx.y * P;
+    _Float16* sb = lds_b[wib];
+    uint16_t* sv = lds_v[wib];
+
+    const int ld_row = lane / TPR;          // row handled inside one load instruction
+    const int ld_col = (lane % TPR) * 8;    // feature offset inside the panel
+    const bool ld_active = ld_row < 16;     // only false when TPR < 4
+    const int m = lane & 15, kg = lane >> 4;
+
+    float4_t acc[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) acc[c] = (float4_t){0.f, 0.f, 0.f, 0.f};
+
+    for (uint32_t t = t_begin; t < t_end; ++t) {
+        const int my_colid = tile_colid[(size_t)t * 16 + m];
+        uint4 breg[NLD];
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int k = j * ROWS_PER_LOAD + ld_row;
+            const int c = shfl_i32(my_colid, k & 15);
+            if (ld_active) breg[j] = *reinterpret_cast<const uint4*>(B + (size_t)c * N + panel + ld_col);
+        }
+        const uint32_t voff = tile_val_off[t];
+        const uint32_t vcnt = tile_val_off[t + 1] - voff;
+        uint2 vreg = make_uint2(0u, 0u);
+        if ((uint32_t)lane * 4u < vcnt) vreg = *reinterpret_cast<const uint2*>(tile_val + voff + lane * 4);
+        const uint64_t m0 = tile_mask[(size_t)t * 4 + 0], m1 = tile_mask[(size_t)t * 4 + 1];
+        const uint64_t m2 = tile_mask[(size_t)t * 4 + 2], m3 = tile_mask[(size_t)t * 4 + 3];
+
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int k = j * ROWS_PER_LOAD + ld_row;
+            if (ld_active) *reinterpret_cast<uint4*>(sb + k * LDB + ld_col) = breg[j];
+        }
+        *reinterpret_cast<uint2*>(sv + lane * 4) = vreg;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // expand this lane's four cells (window row m, fragment columns 4kg..4kg+3)
+        const uint32_t bit0 = (uint32_t)(m0 >> lane) & 1u, bit1 = (uint32_t)(m1 >> lane) & 1u;
+        const uint32_t bit2 = (uint32_t)(m2 >> lane) & 1u, bit3 = (uint32_t)(m3 >> lane) & 1u;
+        const uint32_t i0 = bits_below_lane(m0) + bits_below_lane(m1) + bits_below_lane(m2) + bits_below_lane(m3);
+        const uint32_t i1 = i0 + bit0, i2 = i1 + bit1, i3 = i2 + bit2;
+        half4_t a_frag;
+        a_frag[0] = bit0 ? __builtin_bit_cast(_Float16, sv[i0]) : (_Float16)0;
+        a_frag[1] = bit1 ? __builtin_bit_cast(_Float16, sv[i1]) : (_Float16)0;
+        a_frag[2] = bit2 ? __builtin_bit_cast(_Float16, sv[i2]) : (_Float16)0;
+        a_frag[3] = bit3 ? __builtin_bit_cast(_Float16, sv[i3]) : (_Float16)0;
+
+        const _Float16* brow = sb + (4 * kg) * LDB + (m >> 2) * (4 * NCH) + (m & 3);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            half4_t b_frag;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) b_frag[i] = brow[i * LDB + 4 * c];
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
+        }
+    }
+
+    // lane (q = lane/16, r = lane%16) owns features [q*4*NCH, (q+1)*4*NCH) of window row r
+    const int r = lane & 15, q = lane >> 4;
+    float* out;
+    if (dst == kNoDst) {
+        const int row = win_row[(size_t)win * 16 + r];
+        if (row < 0) return;
+        out = C + (size_t)row * N;
+    } else {
+        out = scratch + ((size_t)dst + r) * N;
+    }
+    out += panel + q * (4 * NCH);
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(out + 4 * c) = acc[c];
+}
+
+// ---------------------------------------------------------------------------
+// Combine: C[row] = sum over parts of scratch[first + p*stride], in a fixed order
+// (four interleaved running sums, then a fixed tree), one wave per entry.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_combine_kernel(
+    const uint4* __restrict__ entries, uint32_t n_entries, const float* __restrict__ scratch,
+    float* __restrict__ C, int N) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t e = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    if (e >= n_entries) return;
+    const uint4 en = entries[e];
+    const uint32_t row = en.x, first = en.y, parts = en.z, stride = en.w;
+    for (int f = lane * 4; f < N; f += 256) {
+        float4 s0 = make_float4(0, 0, 0, 0), s1 = s0, s2 = s0, s3 = s0;
+        uint32_t p = 0;
+        for (; p + 4 <= parts; p += 4) {
+            const float4 a = *reinterpret_cast<const float4*>(scratch + ((size_t)first + (size_t)(p + 0) * stride) * N + f);
+            const float4 b = *reinterpret_cast<const float4*>(scratch + ((size_t)first + (size_t)(p + 1) * stride) * N + f);
+            const float4 c = *reinterpret_cast<const float4*>(scratch + ((size_t)first + (size_t)(p + 2) * stride) * N + f);
+            const float4 d = *reinterpret_cast<const float4*>(scratch + ((size_t)first + (size_t)(p + 3) * stride) * N + f);
+            s0.x += a.x; s0.y += a.y; s0.z += a.z; s0.w += a.w;
+            s1.x += b.x; s1.y += b.y; s1.z += b.z; s1.w += b.w;
+            s2.x += c.x; s2.y += c.y; s2.z += c.z; s2.w += c.w;
+            s3.x += d.x; s3.y += d.y; s3.z += d.z; s3.w += d.w;
+        }
+        for (; p < parts; ++p) {
+            const float4 a = *reinterpret_cast<const float4*>(scratch + ((size_t)first + (size_t)p * stride) * N + f);
+            s0.x += a.x; s0.y += a.y; s0.z += a.z; s0.w += a.w;
+        }
+        float4 o;
+        o.x = (s0.x + s1.x) + (s2.x + s3.x);
+        o.y = (s0.y + s1.y) + (s2.y + s3.y);
+        o.z = (s0.z + s1.z) + (s2.z + s3.z);
+        o.w = (s0.w + s1.w) + (s2.w + s3.w);
+        *reinterpret_cast<float4*>(C + (size_t)row * N + f) = o;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+static inline uint32_t blocks_per_xcd_for(uint32_t n_waves) {
+    const uint32_t blocks = (n_waves + kWavesPerBlock - 1) / kWavesPerBlock;
+    return (blocks + 7) / 8;
+}
+
+template <int TPR>
+static void launch_irregular_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+    const uint32_t n_waves = (uint32_t)(d.n_segments / (64 / TPR));
+    const uint32_t per = blocks_per_xcd_for(n_waves);
+    dim3 grid(per * 8, (unsigned)(d.geo.N / d.geo.irr_panel));
+    hipLaunchKernelGGL(rsh_irregular_kernel<TPR>, grid, dim3(64 * kWavesPerBlock), 0, st,
+                       (const uint4*)d.seg, n_waves, per, d.irr_col, d.irr_val, (const __half*)B, (float*)C,
+                       d.scratch, d.geo.N);
+}
+
+template <int NCH>
+static void launch_tile_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+    const uint32_t n_items = (uint32_t)d.n_tile_items;
+    const uint32_t per = blocks_per_xcd_for(n_items);
+    dim3 grid(per * 8, (unsigned)(d.geo.N / d.geo.tile_panel));
+    hipLaunchKernelGGL(rsh_tile_kernel<NCH>, grid, dim3(64 * kWavesPerBlock), 0, st, (const uint4*)d.tile_item,
+                       n_items, per, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off, d.tile_val,
+                       (const __half*)B, (float*)C, d.scratch, d.geo.N);
+}
+
+int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (d.n_tile_items > 0) {
+        switch (d.geo.tile_nch) {
+            case 1: launch_tile_t<1>(d, B, C, st); break;
+            case 2: launch_tile_t<2>(d, B, C, st); break;
+            case 4: launch_tile_t<4>(d, B, C, st); break;
+            case 8: launch_tile_t<8>(d, B, C, st); break;
+            case 16: launch_tile_t<16>(d, B, C, st); break;
+            default: return RSH_ERR_UNSUPPORTED_N;
+        }
+    }
+    if (d.n_segments > 0) {
+        switch (d.geo.irr_tpr) {
+            case 2: launch_irregular_t<2>(d, B, C, st); break;
+            case 4: launch_irregular_t<4>(d, B, C, st); break;
+            case 8: launch_irregular_t<8>(d, B, C, st); break;
+            case 16: launch_irregular_t<16>(d, B, C, st); break;
+            case 32: launch_irregular_t<32>(d, B, C, st); break;
+            case 64: launch_irregular_t<64>(d, B, C, st); break;
+            default: return RSH_ERR_UNSUPPORTED_N;
+        }
+    }
+    if (d.n_combine > 0) {
+        const uint32_t n = (uint32_t)d.n_combine;
+        hipLaunchKernelGGL(rsh_combine_kernel, dim3((n + kWavesPerBlock - 1) / kWavesPerBlock), dim3(64 * kWavesPerBlock),
+                           0, st, (const uint4*)d.combine, n, d.scratch, (float*)C, d.geo.N);
+    }
+    return hipGetLastError() == hipSuccess ? RSH_OK : RSH_ERR_HIP;
+}
+
+}  // namespace rsh

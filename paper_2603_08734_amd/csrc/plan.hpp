@@ -1,0 +1,96 @@
+// Internal plan structures shared by the host planner, the C ABI and the launchers.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "../../include/rsh_spmm.h"
+
+namespace rsh {
+
+constexpr int kW = 16;  // rows per window  (MFMA N extent)
+constexpr int kK = 16;  // condensed columns per fragment (MFMA K extent)
+constexpr uint32_t kNoDst = 0xffffffffu;
+constexpr uint32_t kSegToScratch = 1u;   // segment result goes to a scratch slot
+constexpr uint32_t kSegWaveReduce = 2u;  // the teams of the wave hold pieces of one row slice
+
+// Feature-panel geometry derived from N (both kernels walk N in panels).
+struct Geometry {
+    int N = 0;
+    int irr_panel = 0;  // features per irregular-kernel panel: gcd(N, 512)
+    int irr_tpr = 0;    // lanes per B-row segment = irr_panel / 8
+    int irr_teams = 0;  // 64 / irr_tpr
+    int tile_panel = 0; // features per tile-kernel panel: gcd(N, 256)
+    int tile_nch = 0;   // 16-feature MFMA chunks per panel
+};
+Geometry make_geometry(int N);
+
+struct HostPlan {
+    int64_t n_rows = 0, n_cols = 0, nnz = 0;
+    Geometry geo;
+    rsh_plan_opts_t opts{};
+    std::vector<int32_t> order;  // pi: order[i] = original id of the i-th processed row
+
+    // dense-fragment part
+    std::vector<int32_t> win_row;
+    std::vector<uint32_t> win_tile_off;
+    std::vector<int32_t> tile_colid;
+    std::vector<uint64_t> tile_mask;
+    std::vector<uint32_t> tile_val_off;
+    std::vector<uint16_t> tile_val;
+    std::vector<uint32_t> tile_item;  // 4 per item
+    // irregular part
+    std::vector<int32_t> irr_col;
+    std::vector<uint16_t> irr_val;
+    std::vector<uint32_t> seg;  // 4 per team segment
+    // combine
+    std::vector<uint32_t> combine;  // 4 per entry
+    int64_t n_scratch_slots = 0;
+
+    rsh_plan_stats_t stats{};
+};
+
+// Row classes produced by the partitioner (Section 3.3.1).
+struct Partition {
+    std::vector<int32_t> win_row;     // kW ids per window, -1 = absent
+    std::vector<int32_t> irregular;   // non-empty rows routed to the residual path, processing order
+    std::vector<int32_t> empty;       // rows without stored entries
+};
+
+// Stages (planner.cpp / reorder.cpp).  All return an RSH_* status.
+int validate_csr(const rsh_csr_t& a);
+void column_degrees(const rsh_csr_t& a, std::vector<int32_t>& deg, int threads);
+void estimate_threshold(int64_t n_rows, int64_t nnz, int32_t* tau_nnz, int32_t* tau_inc);
+int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& col_deg,
+                 std::vector<int32_t>& order, int threads);
+void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
+                    int32_t tau_nnz, int32_t tau_inc, Partition& out, int threads);
+int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads);
+int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t* val, uint8_t* path);
+
+int hardware_threads();
+
+// Simple static-chunk parallel loop: fn(begin, end, thread_index).
+template <class F>
+void parallel_chunks(int64_t n, int threads, F fn);
+
+}  // namespace rsh
+
+#include <algorithm>
+#include <thread>
+namespace rsh {
+template <class F>
+void parallel_chunks(int64_t n, int threads, F fn) {
+    if (threads <= 1 || n < 2) {
+        fn((int64_t)0, n, 0);
+        return;
+    }
+    threads = (int)std::min<int64_t>(threads, n);
+    std::vector<std::thread> pool;
+    pool.reserve(threads);
+    for (int t = 0; t < threads; ++t) {
+        int64_t b = n * t / threads, e = n * (t + 1) / threads;
+        pool.emplace_back([=, &fn]() { fn(b, e, t); });
+    }
+    for (auto& th : pool) th.join();
+}
+}  // namespace rsh

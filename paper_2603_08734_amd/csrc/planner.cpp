@@ -1,0 +1,519 @@
+// Host planner: CSR -> RS-Tile plan.
+//
+// Stages (paper, Section 3.1 overview; Section 3.2 format; Section 3.3.1 row
+// partitioning; Section 3.3.3 load balancing):
+//   validate -> column degrees -> (reorder, reorder.cpp) -> partition rows into
+//   windows / irregular rows / empty rows -> pack windows into bitmap fragments
+//   -> pack irregular rows into team segments -> bounded work items + combine list.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <numeric>
+
+namespace rsh {
+
+int hardware_threads() {
+    unsigned n = std::thread::hardware_concurrency();
+    return n ? (int)n : 1;
+}
+
+static int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
+
+Geometry make_geometry(int N) {
+    Geometry g;
+    g.N = N;
+    g.irr_panel = gcd_int(N, 512);
+    g.irr_tpr = g.irr_panel / 8;
+    g.irr_teams = 64 / g.irr_tpr;
+    g.tile_panel = gcd_int(N, 256);
+    g.tile_nch = g.tile_panel / 16;
+    return g;
+}
+
+// ---------------------------------------------------------------------------
+// validation and column degrees (d_j of Section 3.4)
+// ---------------------------------------------------------------------------
+int validate_csr(const rsh_csr_t& a) {
+    if (a.n_rows < 0 || a.n_cols < 0 || a.nnz < 0) return RSH_ERR_INVALID_CSR;
+    if (!a.row_ptr) return RSH_ERR_NULL;
+    if (a.nnz > 0 && (!a.col_idx || !a.val_f16)) return RSH_ERR_NULL;
+    if (a.row_ptr[0] != 0 || a.row_ptr[a.n_rows] != a.nnz) return RSH_ERR_INVALID_CSR;
+    for (int64_t i = 0; i < a.n_rows; ++i) {
+        const int64_t b = a.row_ptr[i], e = a.row_ptr[i + 1];
+        if (e < b || e > a.nnz) return RSH_ERR_INVALID_CSR;
+        int64_t prev = -1;
+        for (int64_t p = b; p < e; ++p) {
+            const int64_t c = a.col_idx[p];
+            if (c <= prev || c >= a.n_cols) return RSH_ERR_INVALID_CSR;
+            prev = c;
+        }
+    }
+    return RSH_OK;
+}
+
+void column_degrees(const rsh_csr_t& a, std::vector<int32_t>& deg, int) {
+    deg.assign((size_t)a.n_cols, 0);
+    for (int64_t p = 0; p < a.nnz; ++p) ++deg[a.col_idx[p]];
+}
+
+// The paper names an estimator but does not define it; it only says the row-length
+// threshold is small, saturates around 4-6 and depends on size and sparsity
+// (Section 4.3.2).  Reading used here: a quarter of the mean row length, clamped to
+// [2, 6]; column-gain threshold 2.
+void estimate_threshold(int64_t n_rows, int64_t nnz, int32_t* tau_nnz, int32_t* tau_inc) {
+    const int64_t mean4 = n_rows > 0 ? (nnz / n_rows) / 4 : 0;
+    *tau_nnz = (int32_t)std::max<int64_t>(2, std::min<int64_t>(6, mean4));
+    *tau_inc = 2;
+}
+
+// ---------------------------------------------------------------------------
+// row partitioning
+// ---------------------------------------------------------------------------
+static inline bool row_has_col(const rsh_csr_t& a, int32_t row, int32_t col) {
+    const int32_t* b = a.col_idx + a.row_ptr[row];
+    const int32_t* e = a.col_idx + a.row_ptr[row + 1];
+    return std::binary_search(b, e, col);
+}
+
+// Number of columns of `row` found in none of the rows listed in others[0..n_others).
+static int64_t own_columns(const rsh_csr_t& a, int32_t row, const int32_t* others, int n_others) {
+    int64_t own = 0;
+    for (int64_t p = a.row_ptr[row]; p < a.row_ptr[row + 1]; ++p) {
+        const int32_t c = a.col_idx[p];
+        bool shared = false;
+        for (int q = 0; q < n_others && !shared; ++q) shared = row_has_col(a, others[q], c);
+        own += shared ? 0 : 1;
+    }
+    return own;
+}
+
+static inline int64_t row_len(const rsh_csr_t& a, int32_t r) { return a.row_ptr[r + 1] - a.row_ptr[r]; }
+
+// Distinct columns over a set of rows.
+static int64_t union_size(const rsh_csr_t& a, const int32_t* rows, int n, std::vector<int32_t>& tmp) {
+    tmp.clear();
+    for (int i = 0; i < n; ++i)
+        if (rows[i] >= 0) tmp.insert(tmp.end(), a.col_idx + a.row_ptr[rows[i]], a.col_idx + a.row_ptr[rows[i] + 1]);
+    std::sort(tmp.begin(), tmp.end());
+    return std::unique(tmp.begin(), tmp.end()) - tmp.begin();
+}
+
+void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
+                    int32_t tau_nnz, int32_t tau_inc, Partition& out, int threads) {
+    const int64_t n = a.n_rows;
+    out.win_row.clear();
+    out.irregular.clear();
+    out.empty.clear();
+
+    if (o.force_path == 1 || o.force_path == 2) {
+        std::vector<int32_t> cur;
+        for (int64_t i = 0; i < n; ++i) {
+            const int32_t r = order[i];
+            if (row_len(a, r) == 0) out.empty.push_back(r);
+            else if (o.force_path == 1) out.irregular.push_back(r);
+            else out.win_row.push_back(r);
+        }
+        while (out.win_row.size() % kW) out.win_row.push_back(-1);
+        return;
+    }
+
+    if (o.partition == 0) {
+        // Algorithm 1 as printed, applied to the row sequence `order`: only the head row
+        // of a candidate span is tested; an accepted span of W consecutive rows becomes a
+        // window whatever the other rows hold.
+        int64_t i = 0;
+        while (i < n) {
+            const int32_t r = order[i];
+            const int64_t nz = row_len(a, r);
+            if (nz == 0) {
+                out.empty.push_back(r);
+                ++i;
+                continue;
+            }
+            const int n_others = (int)std::min<int64_t>(kW - 1, n - i - 1);
+            const int64_t gain = own_columns(a, r, order.data() + i + 1, n_others);
+            if (gain < tau_inc && nz <= tau_nnz) {
+                out.irregular.push_back(r);
+                ++i;
+            } else {
+                for (int q = 0; q < kW; ++q) out.win_row.push_back(i + q < n ? order[i + q] : -1);
+                i += kW;
+            }
+        }
+        return;
+    }
+
+    // Cost-guided partition.  The paper's prose (Sections 3.2, 3.3.1, 4.3.2) removes rows
+    // that are very short *and* share few columns with the rows around them; long rows are
+    // split off as well (Section 3.3.3 treats them separately), and a window is only kept
+    // if staging its distinct columns once beats gathering per stored entry.
+    enum : uint8_t { kEmpty = 0, kIrr = 1, kWin = 2 };
+    std::vector<uint8_t> cls((size_t)n, kWin);
+    const double mean = n > 0 ? (double)a.nnz / (double)n : 0.0;
+    const int64_t long_thr = o.long_row_nnz > 0 ? o.long_row_nnz : (int64_t)std::max(4.0 * mean, 4.0 * kK);
+    parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
+        int32_t others[kW];
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = order[i];
+            const int64_t nz = row_len(a, r);
+            if (nz == 0) cls[i] = kEmpty;
+            else if (nz > long_thr) cls[i] = kIrr;
+            else if (nz <= tau_nnz) {
+                int n_others = 0;
+                for (int64_t q = i + 1; q < n && n_others < kW - 1; ++q)
+                    if (row_len(a, order[q]) > 0) others[n_others++] = order[q];
+                const int64_t shared = nz - own_columns(a, r, others, n_others);
+                if (shared < tau_inc) cls[i] = kIrr;
+            }
+        }
+    });
+    // group eligible rows kW at a time, then test each group's column reuse
+    std::vector<int64_t> win_pos;  // positions (in `order`) of eligible rows
+    win_pos.reserve((size_t)n);
+    for (int64_t i = 0; i < n; ++i)
+        if (cls[i] == kWin) win_pos.push_back(i);
+    const int64_t n_groups = ((int64_t)win_pos.size() + kW - 1) / kW;
+    std::vector<uint8_t> keep((size_t)n_groups, 1);
+    parallel_chunks(n_groups, threads, [&](int64_t b, int64_t e, int) {
+        std::vector<int32_t> tmp;
+        int32_t rows[kW];
+        for (int64_t g = b; g < e; ++g) {
+            int cnt = 0;
+            int64_t nnz_w = 0;
+            for (int64_t q = g * kW; q < std::min<int64_t>((g + 1) * kW, (int64_t)win_pos.size()); ++q) {
+                rows[cnt++] = order[win_pos[q]];
+                nnz_w += row_len(a, rows[cnt - 1]);
+            }
+            const int64_t u = union_size(a, rows, cnt, tmp);
+            keep[g] = (double)nnz_w >= (double)o.min_reuse * (double)u;
+        }
+    });
+    for (int64_t g = 0; g < n_groups; ++g)
+        if (!keep[g])
+            for (int64_t q = g * kW; q < std::min<int64_t>((g + 1) * kW, (int64_t)win_pos.size()); ++q)
+                cls[win_pos[q]] = kIrr;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        if (!keep[g]) continue;
+        for (int64_t q = g * kW; q < (g + 1) * kW; ++q)
+            out.win_row.push_back(q < (int64_t)win_pos.size() ? order[win_pos[q]] : -1);
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        if (cls[i] == kEmpty) out.empty.push_back(order[i]);
+        else if (cls[i] == kIrr) out.irregular.push_back(order[i]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// packing
+// ---------------------------------------------------------------------------
+static inline uint32_t round_up4(uint32_t x) { return (x + 3u) & ~3u; }
+
+struct WinEntry {
+    uint64_t key;  // col << 4 | window row
+    uint16_t val;
+};
+
+// Collect the stored entries of one window sorted by (column, window row).
+static void gather_window(const rsh_csr_t& a, const int32_t* rows, std::vector<WinEntry>& ent) {
+    ent.clear();
+    for (int r = 0; r < kW; ++r) {
+        if (rows[r] < 0) continue;
+        for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p)
+            ent.push_back({((uint64_t)(uint32_t)a.col_idx[p] << 4) | (uint64_t)r, a.val_f16[p]});
+    }
+    std::sort(ent.begin(), ent.end(), [](const WinEntry& x, const WinEntry& y) { return x.key < y.key; });
+}
+
+static inline int popc64(uint64_t x) { return __builtin_popcountll(x); }
+
+int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads) {
+    const Geometry& geo = plan.geo;
+    const int64_t n_win = (int64_t)part.win_row.size() / kW;
+    plan.win_row = part.win_row;
+
+    // ---- pass 1: fragments and padded value count per window ---------------------------
+    std::vector<uint32_t> win_tiles((size_t)n_win), win_vals((size_t)n_win);
+    std::vector<int64_t> win_cols((size_t)n_win);
+    parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
+        std::vector<WinEntry> ent;
+        std::vector<uint32_t> cnt;
+        for (int64_t w = b; w < e; ++w) {
+            gather_window(a, &part.win_row[w * kW], ent);
+            int64_t u = 0;
+            cnt.clear();
+            uint64_t prev_col = ~0ull;
+            for (const WinEntry& x : ent) {
+                const uint64_t c = x.key >> 4;
+                if (c != prev_col) {
+                    prev_col = c;
+                    if (u % kK == 0) cnt.push_back(0);
+                    ++u;
+                }
+                ++cnt.back();
+            }
+            uint32_t v = 0;
+            for (uint32_t c : cnt) v += round_up4(c);
+            win_tiles[w] = (uint32_t)cnt.size();
+            win_vals[w] = v;
+            win_cols[w] = u;
+        }
+    });
+    plan.win_tile_off.assign((size_t)n_win + 1, 0);
+    std::vector<uint64_t> win_val_off((size_t)n_win + 1, 0);
+    int64_t sum_cols = 0;
+    for (int64_t w = 0; w < n_win; ++w) {
+        const uint64_t t = (uint64_t)plan.win_tile_off[w] + win_tiles[w];
+        if (t >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+        plan.win_tile_off[w + 1] = (uint32_t)t;
+        win_val_off[w + 1] = win_val_off[w] + win_vals[w];
+        sum_cols += win_cols[w];
+    }
+    const int64_t n_tiles = plan.win_tile_off[n_win];
+    if (win_val_off[n_win] >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+    plan.tile_colid.assign((size_t)n_tiles * kK, 0);
+    plan.tile_mask.assign((size_t)n_tiles * 4, 0);
+    plan.tile_val_off.assign((size_t)n_tiles + 1, 0);
+    plan.tile_val.assign((size_t)win_val_off[n_win] + 8, 0);  // tail pad: kernels read 4 elements per lane
+
+    // ---- pass 2: fill -------------------------------------------------------------------
+    std::vector<int64_t> win_nnz((size_t)n_win, 0);
+    parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
+        std::vector<WinEntry> ent;
+        std::vector<uint32_t> ucol;   // condensed column index of each entry
+        for (int64_t w = b; w < e; ++w) {
+            gather_window(a, &part.win_row[w * kW], ent);
+            win_nnz[w] = (int64_t)ent.size();
+            const uint32_t t0 = plan.win_tile_off[w];
+            const uint32_t nt = plan.win_tile_off[w + 1] - t0;
+            // condensed column ids (sorted ascending) and bitmaps
+            ucol.resize(ent.size());
+            int64_t u = -1;
+            uint64_t prev_col = ~0ull;
+            for (size_t i = 0; i < ent.size(); ++i) {
+                const uint64_t c = ent[i].key >> 4;
+                if (c != prev_col) {
+                    prev_col = c;
+                    ++u;
+                    plan.tile_colid[(size_t)t0 * kK + (size_t)u] = (int32_t)c;
+                }
+                ucol[i] = (uint32_t)u;
+                const uint32_t t = (uint32_t)u / kK, k = (uint32_t)u % kK, r = (uint32_t)(ent[i].key & 15);
+                plan.tile_mask[(size_t)(t0 + t) * 4 + (k & 3)] |= 1ull << ((k >> 2) * 16 + r);
+            }
+            // padding columns of the last fragment repeat its last valid column
+            if (nt > 0) {
+                const int64_t n_u = u + 1;
+                for (int64_t k = n_u; k < (int64_t)nt * kK; ++k)
+                    plan.tile_colid[(size_t)t0 * kK + (size_t)k] = plan.tile_colid[(size_t)t0 * kK + (size_t)(n_u - 1)];
+            }
+            // value offsets
+            uint64_t off = win_val_off[w];
+            for (uint32_t t = 0; t < nt; ++t) {
+                plan.tile_val_off[t0 + t] = (uint32_t)off;
+                uint32_t c = 0;
+                for (int q = 0; q < 4; ++q) c += (uint32_t)popc64(plan.tile_mask[(size_t)(t0 + t) * 4 + q]);
+                off += round_up4(c);
+            }
+            // values: position = (entries of lower lanes) + (entries of this lane in lower words)
+            for (size_t i = 0; i < ent.size(); ++i) {
+                const uint32_t t = ucol[i] / kK, k = ucol[i] % kK, r = (uint32_t)(ent[i].key & 15);
+                const uint32_t lane = (k >> 2) * 16 + r, word = k & 3;
+                const uint64_t* m = &plan.tile_mask[(size_t)(t0 + t) * 4];
+                const uint64_t below = lane ? (~0ull >> (64 - lane)) : 0ull;
+                uint32_t pos = 0;
+                for (uint32_t q = 0; q < 4; ++q) pos += (uint32_t)popc64(m[q] & below);
+                for (uint32_t q = 0; q < word; ++q) pos += (uint32_t)((m[q] >> lane) & 1ull);
+                plan.tile_val[plan.tile_val_off[t0 + t] + pos] = ent[i].val;
+            }
+        }
+    });
+    plan.tile_val_off[n_tiles] = (uint32_t)win_val_off[n_win];
+    int64_t nnz_tile = 0;
+    for (int64_t w = 0; w < n_win; ++w) nnz_tile += win_nnz[w];
+
+    // ---- tile work items (bounded fragments per item, Section 3.3.3) --------------------
+    int64_t t_max = plan.opts.max_tiles_per_item;
+    if (t_max <= 0) {
+        int64_t per = (n_tiles + 4095) / 4096, p2 = 1;
+        while (p2 < per) p2 <<= 1;
+        t_max = std::max<int64_t>(32, std::min<int64_t>(64, p2));
+    }
+    plan.tile_item.clear();
+    plan.combine.clear();
+    int64_t slots = 0, n_split_windows = 0;
+    for (int64_t w = 0; w < n_win; ++w) {
+        const uint32_t t0 = plan.win_tile_off[w], nt = plan.win_tile_off[w + 1] - t0;
+        if (nt <= (uint32_t)t_max) {
+            // a window without fragments (only absent/empty rows) still zero-fills its rows
+            plan.tile_item.insert(plan.tile_item.end(), {(uint32_t)w, t0, t0 + nt, kNoDst});
+            continue;
+        }
+        ++n_split_windows;
+        const uint32_t parts = (uint32_t)((nt + t_max - 1) / t_max);
+        for (uint32_t p = 0; p < parts; ++p) {
+            const uint32_t b = t0 + (uint32_t)((uint64_t)nt * p / parts);
+            const uint32_t e = t0 + (uint32_t)((uint64_t)nt * (p + 1) / parts);
+            plan.tile_item.insert(plan.tile_item.end(), {(uint32_t)w, b, e, (uint32_t)(slots + (int64_t)p * kW)});
+        }
+        for (int r = 0; r < kW; ++r) {
+            const int32_t row = part.win_row[w * kW + r];
+            if (row >= 0) plan.combine.insert(plan.combine.end(), {(uint32_t)row, (uint32_t)(slots + r), parts, (uint32_t)kW});
+        }
+        slots += (int64_t)parts * kW;
+    }
+    const int64_t n_tile_combine = (int64_t)plan.combine.size() / 4;
+
+    // ---- irregular rows -> team segments ------------------------------------------------
+    const int G = geo.irr_teams, TPR = geo.irr_tpr;
+    const int64_t short_max = std::max(2 * TPR, 16);
+    const int64_t slice_max = plan.opts.max_nnz_per_slice > 0 ? plan.opts.max_nnz_per_slice : 256;
+    const int64_t n_irr = (int64_t)part.irregular.size();
+    std::vector<uint32_t> irr_start((size_t)n_irr + 1, 0);
+    for (int64_t i = 0; i < n_irr; ++i) {
+        const uint64_t s = (uint64_t)irr_start[i] + (uint64_t)row_len(a, part.irregular[i]);
+        if (s >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+        irr_start[i + 1] = (uint32_t)s;
+    }
+    const int64_t nnz_irr = irr_start[n_irr];
+    plan.irr_col.assign((size_t)nnz_irr + 64, 0);   // tail pad keeps lane-wise reads in bounds
+    plan.irr_val.assign((size_t)nnz_irr + 64, 0);
+    parallel_chunks(n_irr, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = part.irregular[i];
+            const int64_t len = row_len(a, r);
+            std::memcpy(&plan.irr_col[irr_start[i]], a.col_idx + a.row_ptr[r], (size_t)len * sizeof(int32_t));
+            std::memcpy(&plan.irr_val[irr_start[i]], a.val_f16 + a.row_ptr[r], (size_t)len * sizeof(uint16_t));
+        }
+    });
+    plan.seg.clear();
+    int64_t n_split_rows = 0;
+    // (1) rows longer than a team's share: one or more wave slices, the wave's teams each
+    //     take a contiguous piece and are summed inside the wave
+    for (int64_t i = 0; i < n_irr; ++i) {
+        const int64_t len = irr_start[i + 1] - irr_start[i];
+        if (len <= short_max) continue;
+        const int64_t n_slices = (len + slice_max - 1) / slice_max;
+        if (n_slices > 1) {
+            ++n_split_rows;
+            plan.combine.insert(plan.combine.end(), {(uint32_t)part.irregular[i], (uint32_t)slots, (uint32_t)n_slices, 1u});
+        }
+        for (int64_t s = 0; s < n_slices; ++s) {
+            const int64_t sb = len * s / n_slices, se = len * (s + 1) / n_slices;
+            const uint32_t dst = n_slices > 1 ? (uint32_t)(slots + s) : (uint32_t)part.irregular[i];
+            const uint32_t kind = kSegWaveReduce | (n_slices > 1 ? kSegToScratch : 0u);
+            for (int t = 0; t < G; ++t) {
+                const int64_t tb = sb + (se - sb) * t / G, te = sb + (se - sb) * (t + 1) / G;
+                plan.seg.insert(plan.seg.end(), {(uint32_t)(irr_start[i] + tb), (uint32_t)(te - tb), dst, kind});
+            }
+        }
+        if (n_slices > 1) slots += n_slices;
+    }
+    // (2) short rows: one team each, grouped by length class so the teams of a wave finish together
+    {
+        auto bucket_of = [](int64_t len) {
+            int b = 0;
+            while ((1ll << b) < len) ++b;   // 1 -> 0, 2 -> 1, 3-4 -> 2, 5-8 -> 3, ...
+            return b;
+        };
+        std::vector<std::vector<int64_t>> buckets(40);
+        for (int64_t i = 0; i < n_irr; ++i) {
+            const int64_t len = irr_start[i + 1] - irr_start[i];
+            if (len <= short_max) buckets[(size_t)bucket_of(len)].push_back(i);
+        }
+        for (int b = 39; b >= 0; --b)
+            for (int64_t i : buckets[(size_t)b])
+                plan.seg.insert(plan.seg.end(), {irr_start[i], (uint32_t)(irr_start[i + 1] - irr_start[i]),
+                                                 (uint32_t)part.irregular[i], 0u});
+    }
+    // (3) rows without stored entries: zero-length segments make the kernel write zeros
+    for (int32_t r : part.empty) plan.seg.insert(plan.seg.end(), {0u, 0u, (uint32_t)r, 0u});
+    while ((plan.seg.size() / 4) % (size_t)G) plan.seg.insert(plan.seg.end(), {0u, 0u, kNoDst, 0u});
+
+    plan.n_scratch_slots = slots;
+
+    // ---- statistics -----------------------------------------------------------------------
+    rsh_plan_stats_t& st = plan.stats;
+    st.n_rows = a.n_rows;
+    st.n_cols = a.n_cols;
+    st.nnz = a.nnz;
+    st.N = geo.N;
+    st.n_windows = n_win;
+    st.n_tiles = n_tiles;
+    st.nnz_tile = nnz_tile;
+    st.n_irregular_rows = n_irr;
+    st.nnz_irregular = nnz_irr;
+    st.n_empty_rows = (int64_t)part.empty.size();
+    st.n_tile_items = (int64_t)plan.tile_item.size() / 4;
+    st.n_split_windows = n_split_windows;
+    st.n_segments = (int64_t)plan.seg.size() / 4;
+    st.n_irregular_waves = st.n_segments / G;
+    st.n_split_rows = n_split_rows;
+    st.n_combine = (int64_t)plan.combine.size() / 4;
+    (void)n_tile_combine;
+    st.n_scratch_slots = slots;
+    st.sum_window_cols = sum_cols;
+    st.plan_bytes = (int64_t)(plan.win_row.size() * 4 + plan.win_tile_off.size() * 4 + plan.tile_colid.size() * 4 +
+                              plan.tile_mask.size() * 8 + plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 +
+                              plan.tile_item.size() * 4 + plan.irr_col.size() * 4 + plan.irr_val.size() * 2 +
+                              plan.seg.size() * 4 + plan.combine.size() * 4);
+    st.csr_bytes = 6 * a.nnz + 8 * (a.n_rows + 1);
+    return RSH_OK;
+}
+
+// ---------------------------------------------------------------------------
+// decode: rebuild CSR from the arrays the kernels read
+// ---------------------------------------------------------------------------
+int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t* val, uint8_t* path) {
+    struct Ent {
+        int32_t row, col;
+        uint16_t val;
+        uint8_t path;
+    };
+    std::vector<Ent> ent;
+    ent.reserve((size_t)p.nnz);
+    // dense-fragment part
+    const int64_t n_win = (int64_t)p.win_row.size() / kW;
+    for (int64_t w = 0; w < n_win; ++w) {
+        for (uint32_t t = p.win_tile_off[w]; t < p.win_tile_off[w + 1]; ++t) {
+            const uint64_t* m = &p.tile_mask[(size_t)t * 4];
+            uint32_t pos = p.tile_val_off[t];
+            for (int lane = 0; lane < 64; ++lane)
+                for (int word = 0; word < 4; ++word)
+                    if ((m[word] >> lane) & 1ull) {
+                        const int r = lane & 15, k = (lane >> 4) * 4 + word;
+                        const int32_t row = p.win_row[(size_t)w * kW + r];
+                        if (row < 0) return RSH_ERR_INVALID_CSR;
+                        ent.push_back({row, p.tile_colid[(size_t)t * kK + k], p.tile_val[pos++], 0});
+                    }
+        }
+    }
+    // irregular part: a scratch slot belongs to the row named by its combine entry
+    std::vector<int32_t> slot_row((size_t)p.n_scratch_slots, -1);
+    for (size_t c = 0; c + 3 < p.combine.size(); c += 4)
+        for (uint32_t q = 0; q < p.combine[c + 2]; ++q) slot_row[p.combine[c + 1] + (size_t)q * p.combine[c + 3]] = (int32_t)p.combine[c];
+    for (size_t s = 0; s + 3 < p.seg.size(); s += 4) {
+        const uint32_t start = p.seg[s], len = p.seg[s + 1], dst = p.seg[s + 2], kind = p.seg[s + 3];
+        if (len == 0) continue;
+        if (dst == kNoDst) return RSH_ERR_INVALID_CSR;
+        const int32_t row = (kind & kSegToScratch) ? slot_row[dst] : (int32_t)dst;
+        if (row < 0) return RSH_ERR_INVALID_CSR;
+        for (uint32_t q = 0; q < len; ++q) ent.push_back({row, p.irr_col[start + q], p.irr_val[start + q], 1});
+    }
+    if ((int64_t)ent.size() != p.nnz) return RSH_ERR_INVALID_CSR;
+    std::sort(ent.begin(), ent.end(), [](const Ent& x, const Ent& y) { return x.row != y.row ? x.row < y.row : x.col < y.col; });
+    for (int64_t i = 0; i <= p.n_rows; ++i) row_ptr[i] = 0;
+    for (size_t i = 0; i < ent.size(); ++i) {
+        if (ent[i].row < 0 || ent[i].row >= p.n_rows) return RSH_ERR_INVALID_CSR;
+        if (i && ent[i].row == ent[i - 1].row && ent[i].col == ent[i - 1].col) return RSH_ERR_INVALID_CSR;
+        ++row_ptr[ent[i].row + 1];
+        col_idx[i] = ent[i].col;
+        val[i] = ent[i].val;
+        if (path) path[i] = ent[i].path;
+    }
+    for (int64_t i = 0; i < p.n_rows; ++i) row_ptr[i + 1] += row_ptr[i];
+    return RSH_OK;
+}
+
+}  // namespace rsh

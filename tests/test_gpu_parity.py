@@ -1,0 +1,141 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle.
+
+Acceptance (elementwise): |C_gpu - C_ref| <= 1e-4 * S, S = sum_k |a_ik| |b_kj|;
+where S == 0 the GPU value must be exactly 0.
+"""
+import numpy as np
+import pytest
+
+from oracle import spmm as oracle
+from workloads import dense_B, from_coo, make_config
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def gpu_spmm(A, B_np, N, runs=1, **opts):
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, **opts)
+    B = torch.from_numpy(B_np.view(np.int16)).cuda().view(torch.float16)
+    outs = []
+    for _ in range(runs):
+        C = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+        plan.spmm(B, C)
+        torch.cuda.synchronize()
+        outs.append(C.cpu().numpy())
+    st = plan.stats()
+    plan.destroy()
+    return outs, st
+
+
+def assert_parity(C_gpu, C_ref, S, what=""):
+    assert not np.isnan(C_gpu).any(), f"{what}: unwritten or NaN outputs"
+    err = np.abs(C_gpu.astype(np.float64) - C_ref)
+    bad = err > TOL * S
+    if bad.any():
+        i, j = np.argwhere(bad)[0]
+        raise AssertionError(f"{what}: {int(bad.sum())} elements off, first at ({i},{j}): gpu={C_gpu[i, j]} "
+                             f"ref={C_ref[i, j]} S={S[i, j]}")
+    ratio = float((err / np.where(S > 0, S, 1.0)).max()) if err.size else 0.0
+    return ratio
+
+
+OPTION_SETS = {
+    "hybrid": dict(),
+    "all_irregular": dict(force_path=1),
+    "all_tile": dict(force_path=2),
+    "alg1_literal": dict(partition=0),
+    "tiny_items": dict(force_path=2, max_tiles_per_item=2),
+    "tiny_slices": dict(force_path=1, max_nnz_per_slice=24),
+}
+
+
+@pytest.mark.parametrize("mode", list(OPTION_SETS))
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_reduced_configs_all_routings(k, mode):
+    A, N, dist = make_config(k, small=True)
+    B = dense_B(A.n_cols, N, dist, seed=100 + k)
+    print(f"case config={k} small mode={mode} N={N} rows={A.n_rows} nnz={A.nnz}", flush=True)
+    (C1, C2), st = gpu_spmm(A, B, N, runs=2, **OPTION_SETS[mode])
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    ratio = assert_parity(C1, C_ref, S, f"config {k} {mode}")
+    assert np.array_equal(C1.view(np.uint32), C2.view(np.uint32)), "two runs differ bitwise"
+    print(f"  max err/S = {ratio:.2e}  windows={st['n_windows']} tiles={st['n_tiles']} irr_nnz={st['nnz_irregular']}", flush=True)
+
+
+@pytest.mark.parametrize("N", [16, 32, 48, 64, 96, 128, 256, 512, 1024])
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile"])
+def test_feature_widths(N, mode):
+    A, _, _ = make_config(3, small=True)
+    B = dense_B(A.n_cols, N, "normal", seed=N)
+    print(f"case widths N={N} mode={mode}", flush=True)
+    (C,), _ = gpu_spmm(A, B, N, **OPTION_SETS[mode])
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    assert_parity(C, C_ref, S, f"N={N} {mode}")
+
+
+def edge_matrices():
+    rng = np.random.default_rng(7)
+    out = {}
+    out["one_by_one"] = from_coo([0], [0], [1.5], 1, 1)
+    out["all_empty"] = from_coo([], [], [], 40, 40)
+    out["single_entry_last_row"] = from_coo([36], [3], [-2.0], 37, 9)
+    n = 50
+    out["identity"] = from_coo(np.arange(n), np.arange(n), np.ones(n), n, n)
+    # 15, 17 and 33 rows: windows shorter / longer than 16 by one
+    for rows in (15, 17, 33):
+        m = rng.random((rows, 40)) < 0.4
+        r, c = np.nonzero(m)
+        out[f"dense_rows_{rows}"] = from_coo(r, c, rng.standard_normal(r.size), rows, 40)
+    # one very long row among empty and short ones (split slices + combine)
+    cols = np.sort(rng.choice(5000, size=3000, replace=False))
+    r = np.concatenate([np.full(3000, 5), [0, 9, 9]])
+    c = np.concatenate([cols, [7, 1, 4999]])
+    out["hub_row"] = from_coo(r, c, rng.standard_normal(r.size), 12, 5000)
+    # a full dense block: every window cell set
+    r, c = np.nonzero(np.ones((32, 48), dtype=bool))
+    out["full_block"] = from_coo(r, c, rng.standard_normal(r.size), 32, 48)
+    # fewer columns than one fragment
+    m = rng.random((20, 5)) < 0.6
+    r, c = np.nonzero(m)
+    out["narrow"] = from_coo(r, c, rng.standard_normal(r.size), 20, 5)
+    return out
+
+
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "alg1_literal", "tiny_items", "tiny_slices"])
+@pytest.mark.parametrize("name", list(edge_matrices()))
+def test_edge_cases(name, mode):
+    A = edge_matrices()[name]
+    N = 32
+    B = dense_B(A.n_cols, N, "uniform", seed=3)
+    print(f"case edge={name} mode={mode}", flush=True)
+    (C,), _ = gpu_spmm(A, B, N, **OPTION_SETS[mode])
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    assert_parity(C, C_ref, S, f"{name} {mode}")
+    if name == "identity":
+        assert np.array_equal(C, B.astype(np.float32))
+    if name == "all_empty":
+        assert np.all(C == 0)
+
+
+def test_row_permutation_metamorphic():
+    A, N, dist = make_config(4, small=True)
+    B = dense_B(A.n_cols, N, dist, seed=8)
+    rng = np.random.default_rng(0)
+    perm = rng.permutation(A.n_rows)
+    rows = np.repeat(np.arange(A.n_rows), A.row_nnz())
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(A.n_rows)
+    Ap = from_coo(inv[rows], A.col_idx, A.val, A.n_rows, A.n_cols)   # row perm[i] of A becomes row i
+    (C,), _ = gpu_spmm(A, B, N)
+    (Cp,), _ = gpu_spmm(Ap, B, N)
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    assert_parity(Cp[inv], C_ref, S, "permuted rows")
+    assert_parity(C, C_ref, S, "original rows")

@@ -1,0 +1,277 @@
+"""Host-side planner tests (no GPU): plans are built with upload = 0."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import partition as opart
+from oracle import rstile
+from paper_2603_08734_amd import Plan, RshError, binding
+from workloads import from_coo, make_config
+
+B_ = binding
+
+MODES = {
+    "hybrid": dict(),
+    "all_irregular": dict(force_path=1),
+    "all_tile": dict(force_path=2),
+    "alg1_literal": dict(partition=0),
+    "tiny_items": dict(force_path=2, max_tiles_per_item=2),
+    "tiny_slices": dict(force_path=1, max_nnz_per_slice=24),
+}
+
+
+def host_plan(A, N, **kw):
+    return Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, upload=0, **kw)
+
+
+def arrays_of(p):
+    names = ["WIN_ROW", "WIN_TILE_OFF", "TILE_COLID", "TILE_MASK", "TILE_VAL_OFF", "TILE_VAL", "TILE_ITEM",
+             "IRR_COL", "IRR_VAL", "SEG", "COMBINE"]
+    return {n: p.array(getattr(B_, "RSH_ARR_" + n)) for n in names}
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(os.path.dirname(__file__), "..", "include", "rsh_spmm.h")).read()
+    L = binding.lib()
+    import re
+    declared = set(re.findall(r"\b(rsh_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(L, name)
+    nm = subprocess.run(["nm", "-D", "--defined-only", binding._build.LIB], capture_output=True, text=True).stdout
+    for name in declared:
+        assert f" T {name}" in nm
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_decode_is_bit_exact_and_paths_are_disjoint(k, mode):
+    A, N, _ = make_config(k, small=True)
+    p = host_plan(A, N, **MODES[mode])
+    row_ptr, col_idx, val, path = p.decode()
+    assert np.array_equal(row_ptr, A.row_ptr)
+    assert np.array_equal(col_idx, A.col_idx)
+    assert np.array_equal(val, A.val.view(np.uint16))
+    st = p.stats()
+    assert int((path == 0).sum()) == st["nnz_tile"] and int((path == 1).sum()) == st["nnz_irregular"]
+    assert st["nnz_tile"] + st["nnz_irregular"] == A.nnz
+    if mode == "all_irregular":
+        assert st["nnz_tile"] == 0
+    if mode == "all_tile":
+        assert st["nnz_irregular"] == 0
+
+
+@pytest.mark.parametrize("mode", ["hybrid", "alg1_literal", "tiny_items", "tiny_slices"])
+@pytest.mark.parametrize("k", [2, 4, 5])
+def test_independent_reader_rebuilds_A_from_raw_arrays(k, mode):
+    A, N, _ = make_config(k, small=True)
+    if k == 5:
+        A, _, _ = make_config(5, small=True)
+    p = host_plan(A, N, **MODES[mode])
+    a = arrays_of(p)
+    st = p.stats()
+    rows, cols, vals, paths = rstile.entries_from_arrays(
+        a["WIN_ROW"], a["WIN_TILE_OFF"], a["TILE_COLID"], a["TILE_MASK"], a["TILE_VAL_OFF"], a["TILE_VAL"],
+        a["IRR_COL"], a["IRR_VAL"], a["SEG"], a["COMBINE"], st["n_scratch_slots"])
+    assert rows.size == A.nnz           # every stored entry once ...
+    row_ptr, col_idx, val, _ = rstile.csr_from_entries(rows, cols, vals, paths, A.n_rows, A.n_cols)  # ... and only once
+    assert np.array_equal(row_ptr, A.row_ptr)
+    assert np.array_equal(col_idx, A.col_idx)
+    assert np.array_equal(val, A.val.view(np.uint16))
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_plan_structure_invariants(k, mode):
+    A, N, _ = make_config(k, small=True)
+    p = host_plan(A, N, **MODES[mode])
+    a, st = arrays_of(p), p.stats()
+    n_win, n_tiles = st["n_windows"], st["n_tiles"]
+    win_row = a["WIN_ROW"].reshape(n_win, 16)
+    # rows: windows + irregular + empty partition the row set
+    in_win = win_row[win_row >= 0]
+    seg = a["SEG"].reshape(-1, 4)
+    comb = a["COMBINE"].reshape(-1, 4)
+    direct = seg[((seg[:, 3] & 1) == 0) & (seg[:, 2] != 0xFFFFFFFF)]
+    seg_rows = np.unique(direct[:, 2]).astype(np.int64)
+    irr_comb_rows = comb[comb[:, 3] == 1][:, 0].astype(np.int64)
+    covered = np.concatenate([in_win.astype(np.int64), seg_rows, irr_comb_rows])
+    assert np.array_equal(np.sort(covered), np.arange(A.n_rows)), "every row is written by exactly one path"
+    # fragments: offsets, bitmap popcounts, padding
+    off = a["WIN_TILE_OFF"]
+    assert off[0] == 0 and off[-1] == n_tiles and np.all(np.diff(off.astype(np.int64)) >= 0)
+    mask = a["TILE_MASK"].reshape(n_tiles, 4)
+    pop = np.array([[bin(int(x)).count("1") for x in row] for row in mask]).sum(axis=1) if n_tiles else np.zeros(0, int)
+    voff = a["TILE_VAL_OFF"].astype(np.int64)
+    assert np.all(voff % 4 == 0)
+    assert np.all(np.diff(voff) == (pop + 3) // 4 * 4)
+    assert int(pop.sum()) == st["nnz_tile"]
+    colid = a["TILE_COLID"].reshape(n_tiles, 16)
+    assert colid.size == 0 or (colid.min() >= 0 and colid.max() < A.n_cols)
+    for w in range(n_win):
+        cols_w = colid[off[w]:off[w + 1]].reshape(-1)
+        if cols_w.size == 0:
+            continue
+        distinct = np.unique(cols_w)
+        n_u = distinct.size
+        assert np.array_equal(cols_w[:n_u], distinct), "condensed columns are ascending and distinct"
+        assert np.all(cols_w[n_u:] == distinct[-1]), "padding repeats the last valid column"
+        # padding cells carry no bits: fragment column k >= n_u - 16*(tiles-1) of the last fragment
+        last = off[w + 1] - 1
+        first_pad = n_u - 16 * (off[w + 1] - off[w] - 1)
+        for k in range(first_pad, 16):
+            word = int(mask[last, k % 4])
+            assert (word >> ((k // 4) * 16)) & 0xFFFF == 0
+        # absent rows carry no bits
+        for r in np.nonzero(win_row[w] < 0)[0]:
+            for t in range(off[w], off[w + 1]):
+                for word in mask[t]:
+                    assert all(((int(word) >> (g * 16 + int(r))) & 1) == 0 for g in range(4))
+    # tile items cover each window's fragments exactly once, in order
+    items = a["TILE_ITEM"].reshape(-1, 4)
+    assert items.shape[0] == st["n_tile_items"]
+    by_win = {}
+    for w, b, e, dst in items:
+        by_win.setdefault(int(w), []).append((int(b), int(e), int(dst)))
+    assert sorted(by_win) == list(range(n_win))
+    for w, lst in by_win.items():
+        assert lst[0][0] == off[w] and lst[-1][1] == off[w + 1]
+        assert all(lst[i][1] == lst[i + 1][0] for i in range(len(lst) - 1))
+        assert (len(lst) == 1) == (lst[0][2] == 0xFFFFFFFF)
+    # irregular segments tile the irregular stream exactly once
+    G = p.teams_per_wave()
+    assert seg.shape[0] % G == 0
+    nz = seg[seg[:, 1] > 0]
+    order = np.argsort(nz[:, 0], kind="stable")
+    starts, lens = nz[order, 0].astype(np.int64), nz[order, 1].astype(np.int64)
+    assert starts.size == 0 or (starts[0] == 0 and np.all(starts[1:] == (starts + lens)[:-1]) and
+                                starts[-1] + lens[-1] == st["nnz_irregular"])
+    # wave-reduce waves hold G pieces of one destination
+    waves = seg.reshape(-1, G, 4)
+    red = (waves[:, :, 3] & 2) != 0
+    assert np.all(red.all(axis=1) | (~red).all(axis=1))
+    rw = waves[red.all(axis=1)]
+    assert np.all(rw[:, :, 2] == rw[:, :1, 2]) and np.all(rw[:, :, 3] == rw[:, :1, 3])
+    # scratch slots: every slot is produced once and consumed once
+    produced = []
+    for w, b, e, dst in items:
+        if dst != 0xFFFFFFFF:
+            produced.extend(range(int(dst), int(dst) + 16))
+    slot_waves = waves[red.all(axis=1) & ((waves[:, 0, 3] & 1) != 0)]
+    produced.extend(int(x) for x in slot_waves[:, 0, 2])
+    consumed = []
+    for row, first, parts, stride in comb:
+        consumed.extend(int(first) + q * int(stride) for q in range(int(parts)))
+    absent_slots = 0
+    for w, lst in by_win.items():
+        if len(lst) > 1:
+            absent_slots += int((win_row[w] < 0).sum()) * len(lst)
+    assert len(produced) == len(set(produced)) == st["n_scratch_slots"]
+    assert len(consumed) == len(set(consumed)) and set(consumed) <= set(produced)
+    assert len(produced) - len(consumed) == absent_slots
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_alg1_literal_matches_the_python_oracle(k):
+    A, N, _ = make_config(k, small=True)
+    for tau_nnz, tau_inc in [(-1, -1), (0, 2), (3, 1), (6, 4)]:
+        p = host_plan(A, N, partition=0, tau_nnz=tau_nnz, tau_inc=tau_inc)
+        st = p.stats()
+        if tau_nnz < 0:
+            assert (st["tau_nnz"], st["tau_inc"]) == opart.estimate_threshold(A.n_rows, A.nnz)
+        wins, res = opart.partition_rows(A.row_ptr, A.col_idx, 16, st["tau_nnz"], st["tau_inc"])
+        win_row = p.array(B_.RSH_ARR_WIN_ROW).reshape(-1, 16)
+        assert win_row[:, 0].tolist() == wins
+        for s, rows in zip(wins, win_row):
+            want = [r if r < A.n_rows else -1 for r in range(s, s + 16)]
+            assert rows.tolist() == want
+        seg = p.array(B_.RSH_ARR_SEG).reshape(-1, 4)
+        comb = p.array(B_.RSH_ARR_COMBINE).reshape(-1, 4)
+        nonempty = seg[seg[:, 1] > 0]
+        direct = nonempty[(nonempty[:, 3] & 1) == 0][:, 2]
+        got_res = sorted(set(int(x) for x in direct) | set(int(x) for x in comb[comb[:, 3] == 1][:, 0]))
+        assert got_res == res
+
+
+def test_row_order_is_identity_without_reordering():
+    A, N, _ = make_config(2, small=True)
+    p = host_plan(A, N)
+    assert np.array_equal(p.row_order(), np.arange(A.n_rows))
+
+
+def test_plan_is_deterministic():
+    A, N, _ = make_config(2, small=True)
+    a1, a2 = arrays_of(host_plan(A, N, threads=1)), arrays_of(host_plan(A, N, threads=5))
+    for k in a1:
+        assert np.array_equal(a1[k], a2[k]), k
+
+
+def test_abi_error_codes():
+    L = binding.lib()
+    A, N, _ = make_config(1, small=True)
+    opts = binding.rsh_plan_opts_default()
+    opts.upload = 0
+    out = ctypes.c_void_p()
+
+    def create(row_ptr, col_idx, val, n_rows, n_cols, N=32, o=opts):
+        csr = binding.rsh_csr_t(n_rows, n_cols, len(col_idx), row_ptr.ctypes.data, col_idx.ctypes.data, val.ctypes.data)
+        rc = L.rsh_plan_create(ctypes.byref(csr), N, ctypes.byref(o), ctypes.byref(out))
+        if rc == 0:
+            L.rsh_plan_destroy(out)
+        return rc
+
+    rp, ci, v = A.row_ptr.copy(), A.col_idx.copy(), A.val.view(np.uint16).copy()
+    assert create(rp, ci, v, A.n_rows, A.n_cols) == B_.RSH_OK
+    assert L.rsh_plan_create(None, 32, None, ctypes.byref(out)) == B_.RSH_ERR_NULL
+    for bad_N in (0, -16, 8, 40, 8192):
+        assert create(rp, ci, v, A.n_rows, A.n_cols, N=bad_N) == B_.RSH_ERR_UNSUPPORTED_N
+    bad = ci.copy(); bad[5] = A.n_cols
+    assert create(rp, bad, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR
+    bad = ci.copy(); bad[1] = bad[0]
+    assert create(rp, bad, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR      # duplicate
+    bad = ci.copy(); bad[0], bad[1] = bad[1], bad[0]
+    assert create(rp, bad, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR      # unsorted
+    bad = ci.copy(); bad[3] = -1
+    assert create(rp, bad, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR
+    bad = rp.copy(); bad[3] = bad[4] + 1
+    assert create(bad, ci, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR      # non-monotone
+    bad = rp.copy(); bad[0] = 1
+    assert create(bad, ci, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR
+    bad = rp.copy(); bad[-1] -= 1
+    assert create(bad, ci, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR
+    o2 = binding.rsh_plan_opts_default(); o2.upload = 0; o2.window_rows = 8
+    assert create(rp, ci, v, A.n_rows, A.n_cols, o=o2) == B_.RSH_ERR_BAD_OPTION
+    o3 = binding.rsh_plan_opts_default(); o3.upload = 0; o3.alpha = 0.0
+    assert create(rp, ci, v, A.n_rows, A.n_cols, o=o3) == B_.RSH_ERR_BAD_OPTION
+    # empty matrices are legal
+    z = np.zeros(1, dtype=np.int64)
+    assert create(z, np.zeros(0, np.int32), np.zeros(0, np.uint16), 0, 0) == B_.RSH_OK
+    z = np.zeros(6, dtype=np.int64)
+    assert create(z, np.zeros(0, np.int32), np.zeros(0, np.uint16), 5, 7) == B_.RSH_OK
+    # spmm on a host-only plan is refused; destroy(NULL) is a no-op
+    p = host_plan(A, 32)
+    assert L.rsh_spmm(p._h, ctypes.c_void_p(16), ctypes.c_void_p(16), None) == B_.RSH_ERR_NOT_UPLOADED
+    assert L.rsh_spmm(None, None, None, None) == B_.RSH_ERR_NULL
+    assert L.rsh_plan_destroy(None) == B_.RSH_OK
+    assert L.rsh_status_string(B_.RSH_ERR_INVALID_CSR).decode().startswith("invalid CSR")
+    with pytest.raises(RshError):
+        Plan(rp, ci, v, A.n_cols, 24, upload=0)
+
+
+def test_long_rows_are_split_into_bounded_slices_and_windows_into_bounded_items():
+    rng = np.random.default_rng(1)
+    cols = np.sort(rng.choice(4000, size=2500, replace=False))
+    A = from_coo(np.full(2500, 3), cols, rng.standard_normal(2500), 8, 4000)
+    p = host_plan(A, 128, max_nnz_per_slice=256)
+    st = p.stats()
+    assert st["n_split_rows"] == 1 and st["n_scratch_slots"] == 10 and st["n_combine"] == 1
+    seg = p.array(B_.RSH_ARR_SEG).reshape(-1, 4)
+    G = p.teams_per_wave()
+    waves = seg.reshape(-1, G, 4)
+    assert waves[:, :, 1].sum(axis=1).max() <= 256
+    p2 = host_plan(A, 128, force_path=2, max_tiles_per_item=8)
+    items = p2.array(B_.RSH_ARR_TILE_ITEM).reshape(-1, 4)
+    assert (items[:, 2] - items[:, 1]).max() <= 8 and p2.stats()["n_split_windows"] == 1
