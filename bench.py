@@ -1,0 +1,140 @@
+#!/usr/bin/env python3
+"""Benchmark of the row-structured hybrid SpMM hot path on one MI355X.
+
+One "step" is one rsh_spmm call: tile kernel + irregular kernel + combine over the
+whole matrix, with the plan, B and C already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+# HBM bytes per rsh_spmm call measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE of the
+# dominant kernel, scaled by a copy kernel of known size); filled in from profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline R-MAT graph)")
+    ap.add_argument("--reorder", type=int, default=-1, help="override the plan's reorder option")
+    ap.add_argument("--opt", action="append", default=[], help="plan option override name=value")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2603_08734_amd import Plan
+    from workloads import dense_B, make_config
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    A, N, dist = make_config(args.config)
+    B_np = dense_B(A.n_cols, N, dist, seed=1)
+    gen_s = time.perf_counter() - t0
+
+    opts = {}
+    if args.reorder >= 0:
+        opts["reorder"] = args.reorder
+    for kv in args.opt:
+        k, v = kv.split("=")
+        opts[k] = float(v) if k in ("alpha", "min_reuse") else int(v)
+    t0 = time.perf_counter()
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, **opts)
+    plan_s = time.perf_counter() - t0
+    st = plan.stats()
+
+    B = torch.from_numpy(B_np.view(np.int16)).cuda().view(torch.float16)
+    C = torch.empty((A.n_rows, N), dtype=torch.float32, device="cuda")
+    for _ in range(args.warmup):
+        plan.spmm(B, C)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan.spmm(B, C)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    flops = 2.0 * A.nnz * N
+    gflops = flops / (ms_per_step * 1e-3) / 1e9
+
+    # per-kernel durations with HIP events on the launch stream
+    acc = {"tile": 0.0, "irregular": 0.0, "combine": 0.0}
+    n_prof = max(5, min(args.steps, 20))
+    for _ in range(n_prof):
+        t = plan.spmm_profile(B, C)
+        for k in acc:
+            acc[k] += t[k]
+    kernel_ms = {k: v / n_prof for k, v in acc.items()}
+    dominant = max(("tile", "irregular"), key=lambda k: kernel_ms[k])
+    if dominant == "irregular":
+        alg_bytes = st["irregular_part_bytes"] + 2 * N * st["cols_irregular"] + 4 * N * st["rows_irregular"]
+    else:
+        alg_bytes = st["tile_part_bytes"] + 2 * N * st["cols_tile"] + 4 * N * st["rows_tile"]
+    achieved = alg_bytes / (kernel_ms[dominant] * 1e-3) / 1e9 if kernel_ms[dominant] > 0 else 0.0
+    bytes_min = st["plan_bytes"] + 2 * N * st["cols_all"] + 4 * N * A.n_rows
+    roofline = {"bound": "hbm", "kernel": "rsh_%s_kernel" % dominant, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dominant)),
+                "algorithmic_bytes": int(alg_bytes), "kernel_ms": round(kernel_ms[dominant], 4)}
+
+    out = {
+        "metric": "SpMM GFLOP/s (2*nnz*N/t), N=%d, 1 MI355X" % N, "value": round(gflops, 1), "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16*f16+f32",
+        "data": "synthetic",
+        "config": {"workload": A.meta["name"], "rows": A.n_rows, "cols": A.n_cols, "nnz": A.nnz, "N": N,
+                   "seed": 0, "csr_checksum": A.checksum(), "plan_options": opts},
+        "roofline": roofline,
+        "hbm_useful_GBps": round(bytes_min / (ms_per_step * 1e-3) / 1e9, 1),
+        "bytes_min": int(bytes_min),
+        "kernel_ms": {k: round(v, 4) for k, v in kernel_ms.items()},
+        "plan": {"build_s": round(plan_s, 3), "stage_ms": {k[3:]: round(st[k], 1) for k in st if k.startswith("ms_")},
+                 "windows": st["n_windows"], "tiles": st["n_tiles"], "nnz_tile": st["nnz_tile"],
+                 "nnz_irregular": st["nnz_irregular"], "tile_items": st["n_tile_items"],
+                 "irregular_waves": st["n_irregular_waves"], "split_rows": st["n_split_rows"],
+                 "split_windows": st["n_split_windows"], "plan_bytes": st["plan_bytes"], "csr_bytes": st["csr_bytes"],
+                 "mean_nnz_per_tile": round(st["nnz_tile"] / max(1, st["n_tiles"]), 2),
+                 "mean_nnz_per_window": round(st["nnz_tile"] / max(1, st["n_windows"]), 1)},
+        "gen_s": round(gen_s, 2),
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on this machine's host cores, whole matrix, one run
+        from oracle import spmm as oracle_spmm
+        cores = len(os.sched_getaffinity(0))
+        threads = min(cores, 16)
+        t0 = time.perf_counter()
+        C_ref, S, used = oracle_spmm.spmm(A.row_ptr, A.col_idx, A.val, B_np, threads=threads)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(flops / cpu_s / 1e9, 2), "unit": "GFLOP/s", "cores": used,
+                               "kind": "oracle", "sample": "whole matrix, one run, %.2f s" % cpu_s}
+        C_host = C.cpu().numpy().astype(np.float64)
+        err = np.abs(C_host - C_ref)
+        ok = bool(np.all(err <= 1e-4 * S))
+        out["parity"] = {"ok": ok, "max_err_over_S": float((err / np.where(S > 0, S, 1.0)).max())}
+        del C_ref, S, C_host, err
+    print(json.dumps(out), flush=True)
+    plan.destroy()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

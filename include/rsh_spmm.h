@@ -85,6 +85,9 @@ typedef struct {
     int64_t n_combine, n_scratch_slots;        /* combine entries; fp32 rows of N in scratch     */
     int64_t sum_window_cols;                   /* sum over windows of |U_w| (distinct columns)   */
     int64_t plan_bytes, csr_bytes;             /* device bytes of the plan vs 6*nnz + 8*(n_rows+1) */
+    int64_t tile_part_bytes, irregular_part_bytes; /* plan bytes read by the tile / irregular kernel */
+    int64_t cols_all, cols_tile, cols_irregular;   /* distinct columns referenced overall / per part */
+    int64_t rows_tile, rows_irregular;         /* rows of C each kernel writes directly or via scratch */
     int32_t tau_nnz, tau_inc;                  /* thresholds actually used                       */
     double ms_validate, ms_reorder, ms_partition, ms_pack, ms_worklist, ms_upload, ms_total;
 } rsh_plan_stats_t;
@@ -113,6 +116,16 @@ int rsh_plan_create(const rsh_csr_t *csr, int32_t N, const rsh_plan_opts_t *opts
  * from run to run: no atomics are used.
  */
 int rsh_spmm(const rsh_plan_t *plan, const void *B_dev, void *C_dev, void *hip_stream);
+
+/*
+ * Same work as rsh_spmm, but brackets each kernel with HIP events on hip_stream,
+ * waits for the stream, and reports the elapsed milliseconds of the tile kernel,
+ * the irregular kernel and the combine kernel (0 for a kernel that was not
+ * launched).  For benchmarks; it synchronises and creates events on every call.
+ */
+typedef struct { float ms_tile, ms_irregular, ms_combine; } rsh_kernel_times_t;
+int rsh_spmm_profile(const rsh_plan_t *plan, const void *B_dev, void *C_dev, void *hip_stream,
+                     rsh_kernel_times_t *out);
 
 int rsh_plan_destroy(rsh_plan_t *plan); /* NULL is a no-op */
 

@@ -29,7 +29,7 @@ _ARRAY_DTYPES = {
 }
 
 EXPORTED_SYMBOLS = [
-    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_plan_destroy", "rsh_plan_stats",
+    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_profile", "rsh_plan_destroy", "rsh_plan_stats",
     "rsh_plan_decode", "rsh_plan_row_order", "rsh_plan_array", "rsh_plan_teams_per_wave",
     "rsh_status_string", "rsh_last_hip_error",
 ]
@@ -49,12 +49,18 @@ class rsh_plan_opts_t(ctypes.Structure):
                 ("threads", ctypes.c_int32)]
 
 
+class rsh_kernel_times_t(ctypes.Structure):
+    _fields_ = [("ms_tile", ctypes.c_float), ("ms_irregular", ctypes.c_float), ("ms_combine", ctypes.c_float)]
+
+
 class rsh_plan_stats_t(ctypes.Structure):
     _fields_ = ([(n, ctypes.c_int64) for n in ("n_rows", "n_cols", "nnz")] + [("N", ctypes.c_int32)] +
                 [(n, ctypes.c_int64) for n in (
                     "n_windows", "n_tiles", "nnz_tile", "n_irregular_rows", "nnz_irregular", "n_empty_rows",
                     "n_tile_items", "n_split_windows", "n_segments", "n_irregular_waves", "n_split_rows",
-                    "n_combine", "n_scratch_slots", "sum_window_cols", "plan_bytes", "csr_bytes")] +
+                    "n_combine", "n_scratch_slots", "sum_window_cols", "plan_bytes", "csr_bytes",
+                    "tile_part_bytes", "irregular_part_bytes", "cols_all", "cols_tile", "cols_irregular",
+                    "rows_tile", "rows_irregular")] +
                 [("tau_nnz", ctypes.c_int32), ("tau_inc", ctypes.c_int32)] +
                 [(n, ctypes.c_double) for n in ("ms_validate", "ms_reorder", "ms_partition", "ms_pack",
                                                 "ms_worklist", "ms_upload", "ms_total")])
@@ -78,6 +84,7 @@ def lib() -> ctypes.CDLL:
         L.rsh_plan_create.argtypes = [ctypes.POINTER(rsh_csr_t), i32, ctypes.POINTER(rsh_plan_opts_t),
                                       ctypes.POINTER(vp)]
         L.rsh_spmm.argtypes = [vp, vp, vp, vp]
+        L.rsh_spmm_profile.argtypes = [vp, vp, vp, vp, ctypes.POINTER(rsh_kernel_times_t)]
         L.rsh_plan_destroy.argtypes = [vp]
         L.rsh_plan_stats.argtypes = [vp, ctypes.POINTER(rsh_plan_stats_t)]
         L.rsh_plan_decode.argtypes = [vp, vp, vp, vp, vp]
@@ -148,6 +155,16 @@ class Plan:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
         _check(lib().rsh_spmm(self._h, ctypes.c_void_p(b_ptr), ctypes.c_void_p(c_ptr), ctypes.c_void_p(stream)))
+
+    def spmm_profile(self, B, C, stream=None) -> dict:
+        """rsh_spmm_profile: same work, returns per-kernel milliseconds (synchronises)."""
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        t = rsh_kernel_times_t()
+        _check(lib().rsh_spmm_profile(self._h, ctypes.c_void_p(B.data_ptr()), ctypes.c_void_p(C.data_ptr()),
+                                      ctypes.c_void_p(stream), ctypes.byref(t)))
+        return {"tile": t.ms_tile, "irregular": t.ms_irregular, "combine": t.ms_combine}
 
     # --- introspection ------------------------------------------------------
     def stats(self) -> dict:

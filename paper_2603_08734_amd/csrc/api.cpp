@@ -196,8 +196,35 @@ int rsh_spmm(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_s
     if (plan->host.n_rows == 0) return RSH_OK;
     if (!C_dev || (!B_dev && plan->host.nnz > 0)) return RSH_ERR_NULL;
     if (((uintptr_t)B_dev & 15u) || ((uintptr_t)C_dev & 15u)) return RSH_ERR_BAD_OPTION;
-    const int rc = rsh::launch_spmm(plan->dev, B_dev, C_dev, hip_stream);
+    const int rc = rsh::launch_spmm(plan->dev, B_dev, C_dev, hip_stream, nullptr);
     if (rc == RSH_ERR_HIP) g_hip_error = "kernel launch failed";
+    return rc;
+}
+
+int rsh_spmm_profile(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_stream, rsh_kernel_times_t* out) {
+    if (!plan || !out) return RSH_ERR_NULL;
+    out->ms_tile = out->ms_irregular = out->ms_combine = 0.f;
+    if (!plan->uploaded) return RSH_ERR_NOT_UPLOADED;
+    if (plan->host.n_rows == 0) return RSH_OK;
+    if (!C_dev || (!B_dev && plan->host.nnz > 0)) return RSH_ERR_NULL;
+    if (((uintptr_t)B_dev & 15u) || ((uintptr_t)C_dev & 15u)) return RSH_ERR_BAD_OPTION;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int rc = RSH_OK;
+    for (int i = 0; i < 4 && rc == RSH_OK; ++i)
+        if (!hip_ok(hipEventCreate(&ev[i]))) rc = RSH_ERR_HIP;
+    if (rc == RSH_OK) {
+        void* evp[4] = {ev[0], ev[1], ev[2], ev[3]};
+        rc = rsh::launch_spmm(plan->dev, B_dev, C_dev, hip_stream, evp);
+        if (!hip_ok(hipStreamSynchronize((hipStream_t)hip_stream))) rc = RSH_ERR_HIP;
+        if (rc == RSH_OK) {
+            float ms = 0.f;
+            if (plan->dev.n_tile_items > 0 && hip_ok(hipEventElapsedTime(&ms, ev[0], ev[1]))) out->ms_tile = ms;
+            if (plan->dev.n_segments > 0 && hip_ok(hipEventElapsedTime(&ms, ev[1], ev[2]))) out->ms_irregular = ms;
+            if (plan->dev.n_combine > 0 && hip_ok(hipEventElapsedTime(&ms, ev[2], ev[3]))) out->ms_combine = ms;
+        }
+    }
+    for (int i = 0; i < 4; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
     return rc;
 }
 

@@ -296,8 +296,12 @@ static void launch_tile_t(const DevicePlan& d, const void* B, void* C, hipStream
                        (const __half*)B, (float*)C, d.scratch, d.geo.N);
 }
 
-int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream) {
+int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void* const* events) {
     hipStream_t st = (hipStream_t)stream;
+    auto mark = [&](int i) {
+        if (events) (void)hipEventRecord((hipEvent_t)events[i], st);
+    };
+    mark(0);
     if (d.n_tile_items > 0) {
         switch (d.geo.tile_nch) {
             case 1: launch_tile_t<1>(d, B, C, st); break;
@@ -308,6 +312,7 @@ int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream) {
             default: return RSH_ERR_UNSUPPORTED_N;
         }
     }
+    mark(1);
     if (d.n_segments > 0) {
         switch (d.geo.irr_tpr) {
             case 2: launch_irregular_t<2>(d, B, C, st); break;
@@ -319,11 +324,13 @@ int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream) {
             default: return RSH_ERR_UNSUPPORTED_N;
         }
     }
+    mark(2);
     if (d.n_combine > 0) {
         const uint32_t n = (uint32_t)d.n_combine;
         hipLaunchKernelGGL(rsh_combine_kernel, dim3((n + kWavesPerBlock - 1) / kWavesPerBlock), dim3(64 * kWavesPerBlock),
                            0, st, (const uint4*)d.combine, n, d.scratch, (float*)C, d.geo.N);
     }
+    mark(3);
     return hipGetLastError() == hipSuccess ? RSH_OK : RSH_ERR_HIP;
 }
 

@@ -23,7 +23,9 @@ struct DevicePlan {
     float* scratch = nullptr;
 };
 
-// Enqueue the tile, irregular and combine kernels on `stream` (a hipStream_t).
-int launch_spmm(const DevicePlan& d, const void* B_dev, void* C_dev, void* stream);
+// Enqueue the tile, irregular and combine kernels on `stream` (a hipStream_t).  When
+// `events` is not null it points at four hipEvent_t recorded before the tile kernel and
+// after each of the three kernels.
+int launch_spmm(const DevicePlan& d, const void* B_dev, void* C_dev, void* stream, void* const* events);
 
 }  // namespace rsh

@@ -459,6 +459,30 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                               plan.tile_item.size() * 4 + plan.irr_col.size() * 4 + plan.irr_val.size() * 2 +
                               plan.seg.size() * 4 + plan.combine.size() * 4);
     st.csr_bytes = 6 * a.nnz + 8 * (a.n_rows + 1);
+    st.tile_part_bytes = (int64_t)(plan.win_row.size() * 4 + plan.tile_colid.size() * 4 + plan.tile_mask.size() * 8 +
+                                   plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 + plan.tile_item.size() * 4);
+    st.irregular_part_bytes = (int64_t)(plan.irr_col.size() * 4 + plan.irr_val.size() * 2 + plan.seg.size() * 4);
+    {
+        // distinct columns referenced by each part (the B rows each kernel must fetch at least once)
+        std::vector<uint8_t> seen((size_t)a.n_cols, 0);
+        for (int32_t c : plan.tile_colid) seen[(size_t)c] |= 1;
+        for (int64_t i = 0; i < nnz_irr; ++i) seen[(size_t)plan.irr_col[(size_t)i]] |= 2;
+        int64_t all = 0, ct = 0, ci = 0;
+        for (uint8_t f : seen) {
+            all += f != 0;
+            ct += (f & 1) != 0;
+            ci += (f & 2) != 0;
+        }
+        st.cols_all = all;
+        st.cols_tile = ct;
+        st.cols_irregular = ci;
+    }
+    {
+        int64_t rows_in_windows = 0;
+        for (int32_t r : plan.win_row) rows_in_windows += r >= 0;
+        st.rows_tile = rows_in_windows;
+        st.rows_irregular = n_irr + (int64_t)part.empty.size();
+    }
     return RSH_OK;
 }
 

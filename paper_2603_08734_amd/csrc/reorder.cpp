@@ -1,18 +1,343 @@
 // Locality-aware row reordering (paper, Section 3.4, Algorithm 3).
+//
+// The paper fixes the stages -- candidate rows through an inverted index over
+// "representative features", top-k neighbours under the degree-weighted Jaccard
+// affinity, a spanning tree of the kNN graph walked depth-first, then 2-opt inside each
+// prospective window and relocation of isolated rows -- but none of the constants or
+// tie-breaks.  The choices made here (all deterministic):
+//   * features of a row: its (at most) 4 lowest-degree columns among columns with
+//     2 <= d_j <= 4096, ties by column id;
+//   * candidates: rows that contain one of those columns, at most 64 rows scanned per
+//     column, the 64 candidates sharing most feature columns are scored;
+//   * the tree is the maximum-affinity spanning forest (Kruskal on cost 1 - sim, ties by
+//     row ids); components are visited by smallest row id, children by decreasing affinity;
+//   * 2-opt = segment reversals inside blocks of 16 consecutive positions (even blocks,
+//     then odd blocks, so that blocks handled concurrently never share a boundary row);
+//   * a row is isolated when its affinity to both neighbours in the order is below 0.05;
+//     it moves behind its most similar kNN neighbour that is not isolated, else to the tail;
+//   * rows without stored entries go last.
 #include "plan.hpp"
 
+#include <algorithm>
+#include <cmath>
 #include <numeric>
 
 namespace rsh {
 
+namespace {
+
+constexpr int kMaxFeatures = 4;
+constexpr int kMaxFeatureDegree = 4096;
+constexpr int kScanPerFeature = 64;
+constexpr int kMaxCandidates = 64;
+constexpr double kIsolatedBelow = 0.05;
+constexpr int kTwoOptSweeps = 4;
+
+struct Sim {
+    const rsh_csr_t& a;
+    const std::vector<double>& w;      // w_j = d_j^-alpha
+    const std::vector<double>& row_w;  // sum of w over the row's columns
+
+    // weighted Jaccard: w(S_r & S_u) / w(S_r | S_u), 0 when both rows are empty
+    double operator()(int32_t r, int32_t u) const {
+        const int32_t* p = a.col_idx + a.row_ptr[r];
+        const int32_t* pe = a.col_idx + a.row_ptr[r + 1];
+        const int32_t* q = a.col_idx + a.row_ptr[u];
+        const int32_t* qe = a.col_idx + a.row_ptr[u + 1];
+        double inter = 0.0;
+        while (p < pe && q < qe) {
+            if (*p < *q) ++p;
+            else if (*q < *p) ++q;
+            else {
+                inter += w[(size_t)*p];
+                ++p;
+                ++q;
+            }
+        }
+        const double uni = row_w[(size_t)r] + row_w[(size_t)u] - inter;
+        return uni > 0.0 ? inter / uni : 0.0;
+    }
+};
+
+struct Edge {
+    float sim;
+    int32_t a, b;  // a < b
+};
+
+struct Dsu {
+    std::vector<int32_t> parent;
+    explicit Dsu(size_t n) : parent(n) { std::iota(parent.begin(), parent.end(), 0); }
+    int32_t find(int32_t x) {
+        while (parent[(size_t)x] != x) {
+            parent[(size_t)x] = parent[(size_t)parent[(size_t)x]];
+            x = parent[(size_t)x];
+        }
+        return x;
+    }
+    bool unite(int32_t x, int32_t y) {
+        x = find(x);
+        y = find(y);
+        if (x == y) return false;
+        if (x < y) parent[(size_t)y] = x;
+        else parent[(size_t)x] = y;
+        return true;
+    }
+};
+
+}  // namespace
+
 int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& col_deg,
                  std::vector<int32_t>& order, int threads) {
-    (void)col_deg;
-    (void)threads;
-    (void)o;
-    order.resize((size_t)a.n_rows);
+    const int64_t n = a.n_rows;
+    const int K = o.knn_k;
+    order.resize((size_t)n);
     std::iota(order.begin(), order.end(), 0);
-    return RSH_OK;
+    if (n < 3 || a.nnz == 0) return RSH_OK;
+
+    // ---- column weights and per-row weight sums ------------------------------------------
+    std::vector<double> w((size_t)a.n_cols, 0.0), row_w((size_t)n, 0.0);
+    for (int64_t j = 0; j < a.n_cols; ++j)
+        if (col_deg[(size_t)j] > 0) w[(size_t)j] = std::pow((double)col_deg[(size_t)j], -(double)o.alpha);
+    parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t r = b; r < e; ++r) {
+            double s = 0.0;
+            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) s += w[(size_t)a.col_idx[p]];
+            row_w[(size_t)r] = s;
+        }
+    });
+    const Sim sim{a, w, row_w};
+
+    // ---- step I: inverted index (column -> rows) over feature columns ----------------------
+    // column-major copy of the pattern, restricted to columns that may serve as features
+    std::vector<int64_t> col_ptr((size_t)a.n_cols + 1, 0);
+    for (int64_t j = 0; j < a.n_cols; ++j) {
+        const int32_t d = col_deg[(size_t)j];
+        col_ptr[(size_t)j + 1] = col_ptr[(size_t)j] + ((d >= 2 && d <= kMaxFeatureDegree) ? d : 0);
+    }
+    std::vector<int32_t> col_rows((size_t)col_ptr[(size_t)a.n_cols]);
+    {
+        std::vector<int64_t> fill(col_ptr.begin(), col_ptr.end() - 1);
+        for (int64_t r = 0; r < n; ++r)
+            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
+                const int32_t j = a.col_idx[p];
+                const int32_t d = col_deg[(size_t)j];
+                if (d >= 2 && d <= kMaxFeatureDegree) col_rows[(size_t)fill[(size_t)j]++] = (int32_t)r;
+            }
+    }
+
+    // ---- step II: top-k neighbours per row ---------------------------------------------------
+    std::vector<int32_t> nbr((size_t)n * (size_t)K, -1);
+    std::vector<float> nbr_sim((size_t)n * (size_t)K, 0.f);
+    parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
+        std::vector<int32_t> cand;
+        std::vector<std::pair<int32_t, int32_t>> counted;   // (-shared features, row)
+        std::vector<std::pair<double, int32_t>> scored;
+        for (int64_t r = b; r < e; ++r) {
+            // the row's lowest-degree eligible columns
+            std::pair<int32_t, int32_t> feat[kMaxFeatures];
+            int nf = 0;
+            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
+                const int32_t j = a.col_idx[p], d = col_deg[(size_t)j];
+                if (d < 2 || d > kMaxFeatureDegree) continue;
+                std::pair<int32_t, int32_t> f(d, j);
+                if (nf < kMaxFeatures) feat[nf++] = f;
+                else {
+                    int worst = 0;
+                    for (int i = 1; i < nf; ++i)
+                        if (feat[i] > feat[worst]) worst = i;
+                    if (f < feat[worst]) feat[worst] = f;
+                }
+            }
+            cand.clear();
+            for (int i = 0; i < nf; ++i) {
+                const int32_t j = feat[i].second;
+                const int64_t cb = col_ptr[(size_t)j], ce = col_ptr[(size_t)j + 1];
+                // scan at most kScanPerFeature rows of the posting list, centred on r's own position
+                const int64_t len = ce - cb;
+                int64_t lo = cb;
+                if (len > kScanPerFeature) {
+                    const int64_t me = std::lower_bound(col_rows.begin() + cb, col_rows.begin() + ce, (int32_t)r) - col_rows.begin();
+                    lo = std::max(cb, std::min(ce - kScanPerFeature, me - kScanPerFeature / 2));
+                }
+                const int64_t hi = std::min(ce, lo + kScanPerFeature);
+                for (int64_t q = lo; q < hi; ++q)
+                    if (col_rows[(size_t)q] != (int32_t)r) cand.push_back(col_rows[(size_t)q]);
+            }
+            std::sort(cand.begin(), cand.end());
+            counted.clear();
+            for (size_t i = 0; i < cand.size();) {
+                size_t j = i;
+                while (j < cand.size() && cand[j] == cand[i]) ++j;
+                counted.emplace_back(-(int32_t)(j - i), cand[i]);
+                i = j;
+            }
+            if ((int)counted.size() > kMaxCandidates) {
+                std::partial_sort(counted.begin(), counted.begin() + kMaxCandidates, counted.end());
+                counted.resize(kMaxCandidates);
+            }
+            scored.clear();
+            for (auto& c : counted) {
+                const double s = sim((int32_t)r, c.second);
+                if (s > 0.0) scored.emplace_back(-s, c.second);
+            }
+            const size_t keep = std::min<size_t>((size_t)K, scored.size());
+            std::partial_sort(scored.begin(), scored.begin() + keep, scored.end());
+            for (size_t i = 0; i < keep; ++i) {
+                nbr[(size_t)r * K + i] = scored[i].second;
+                nbr_sim[(size_t)r * K + i] = (float)-scored[i].first;
+            }
+        }
+    });
+
+    // ---- step III: undirected kNN graph -> maximum-affinity spanning forest -> DFS order ------
+    std::vector<Edge> edges;
+    edges.reserve((size_t)n * (size_t)K);
+    for (int64_t r = 0; r < n; ++r)
+        for (int i = 0; i < K; ++i) {
+            const int32_t u = nbr[(size_t)r * K + i];
+            if (u < 0) break;
+            edges.push_back({nbr_sim[(size_t)r * K + i], std::min((int32_t)r, u), std::max((int32_t)r, u)});
+        }
+    std::sort(edges.begin(), edges.end(), [](const Edge& x, const Edge& y) {
+        if (x.sim != y.sim) return x.sim > y.sim;
+        if (x.a != y.a) return x.a < y.a;
+        return x.b < y.b;
+    });
+    Dsu dsu((size_t)n);
+    std::vector<int32_t> deg_t((size_t)n + 1, 0);
+    std::vector<Edge> tree;
+    tree.reserve((size_t)n);
+    for (size_t i = 0; i < edges.size(); ++i) {
+        if (i && edges[i].a == edges[i - 1].a && edges[i].b == edges[i - 1].b) continue;
+        if (dsu.unite(edges[i].a, edges[i].b)) {
+            tree.push_back(edges[i]);
+            ++deg_t[(size_t)edges[i].a];
+            ++deg_t[(size_t)edges[i].b];
+        }
+    }
+    std::vector<int64_t> adj_ptr((size_t)n + 1, 0);
+    for (int64_t r = 0; r < n; ++r) adj_ptr[(size_t)r + 1] = adj_ptr[(size_t)r] + deg_t[(size_t)r];
+    std::vector<std::pair<float, int32_t>> adj((size_t)adj_ptr[(size_t)n]);
+    {
+        std::vector<int64_t> fill(adj_ptr.begin(), adj_ptr.end() - 1);
+        for (const Edge& e : tree) {
+            adj[(size_t)fill[(size_t)e.a]++] = {e.sim, e.b};
+            adj[(size_t)fill[(size_t)e.b]++] = {e.sim, e.a};
+        }
+    }
+    parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t r = b; r < e; ++r)
+            // stored ascending (sim, then descending id) so that popping from the back visits
+            // the most similar child first, smaller id first among equals
+            std::sort(adj.begin() + adj_ptr[(size_t)r], adj.begin() + adj_ptr[(size_t)r + 1],
+                      [](const std::pair<float, int32_t>& x, const std::pair<float, int32_t>& y) {
+                          if (x.first != y.first) return x.first < y.first;
+                          return x.second > y.second;
+                      });
+    });
+    std::vector<int32_t> seq;
+    seq.reserve((size_t)n);
+    std::vector<int32_t> empties;
+    {
+        std::vector<uint8_t> seen((size_t)n, 0);
+        std::vector<int32_t> stack;
+        for (int64_t root = 0; root < n; ++root) {
+            if (seen[(size_t)root]) continue;
+            if (a.row_ptr[root + 1] == a.row_ptr[root]) {
+                seen[(size_t)root] = 1;
+                empties.push_back((int32_t)root);
+                continue;
+            }
+            stack.push_back((int32_t)root);
+            seen[(size_t)root] = 1;
+            while (!stack.empty()) {
+                const int32_t v = stack.back();
+                stack.pop_back();
+                seq.push_back(v);
+                // push children so that the most similar is popped first
+                for (int64_t q = adj_ptr[(size_t)v]; q < adj_ptr[(size_t)v + 1]; ++q) {
+                    const int32_t c = adj[(size_t)q].second;
+                    if (!seen[(size_t)c]) {
+                        seen[(size_t)c] = 1;
+                        stack.push_back(c);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- step IV a: 2-opt inside blocks of kW positions -----------------------------------------
+    const int64_t m = (int64_t)seq.size();
+    auto dist = [&](int64_t i, int64_t j) -> double {   // positions; out-of-range = no edge
+        if (i < 0 || j < 0 || i >= m || j >= m) return 0.0;
+        return 1.0 - sim(seq[(size_t)i], seq[(size_t)j]);
+    };
+    const int64_t n_blocks = (m + kW - 1) / kW;
+    for (int parity = 0; parity < 2; ++parity) {
+        const int64_t cnt = (n_blocks - parity + 1) / 2;
+        parallel_chunks(cnt, threads, [&](int64_t b, int64_t e, int) {
+            for (int64_t h = b; h < e; ++h) {
+                const int64_t s = (2 * h + parity) * kW, t = std::min(m, s + kW);
+                for (int sweep = 0; sweep < kTwoOptSweeps; ++sweep) {
+                    bool improved = false;
+                    for (int64_t i = s; i < t - 1; ++i)
+                        for (int64_t j = i + 1; j < t; ++j) {
+                            // reversing seq[i..j] replaces edges (i-1,i),(j,j+1) by (i-1,j),(i,j+1)
+                            const double before = dist(i - 1, i) + dist(j, j + 1);
+                            const double after = dist(i - 1, j) + dist(i, j + 1);
+                            if (after + 1e-12 < before) {
+                                std::reverse(seq.begin() + i, seq.begin() + j + 1);
+                                improved = true;
+                            }
+                        }
+                    if (!improved) break;
+                }
+            }
+        });
+    }
+
+    // ---- step IV b: isolated rows move next to their best non-isolated neighbour ----------------
+    std::vector<uint8_t> isolated((size_t)n, 0);
+    parallel_chunks(m, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const double left = i > 0 ? sim(seq[(size_t)i - 1], seq[(size_t)i]) : 0.0;
+            const double right = i + 1 < m ? sim(seq[(size_t)i], seq[(size_t)i + 1]) : 0.0;
+            if (left < kIsolatedBelow && right < kIsolatedBelow) isolated[(size_t)seq[(size_t)i]] = 1;
+        }
+    });
+    std::vector<int32_t> host_of((size_t)n, -1);   // isolated row -> row it is placed behind
+    std::vector<int32_t> guests_head((size_t)n, -1), guests_next((size_t)n, -1), tail_rows;
+    for (int64_t i = m - 1; i >= 0; --i) {          // reverse so that lists come out in sequence order
+        const int32_t r = seq[(size_t)i];
+        if (!isolated[(size_t)r]) continue;
+        int32_t host = -1;
+        for (int q = 0; q < K; ++q) {
+            const int32_t u = nbr[(size_t)r * K + q];
+            if (u < 0) break;
+            if (!isolated[(size_t)u]) {
+                host = u;
+                break;
+            }
+        }
+        host_of[(size_t)r] = host;
+        if (host >= 0) {
+            guests_next[(size_t)r] = guests_head[(size_t)host];
+            guests_head[(size_t)host] = r;
+        }
+    }
+    order.clear();
+    for (int64_t i = 0; i < m; ++i) {
+        const int32_t r = seq[(size_t)i];
+        if (isolated[(size_t)r]) {
+            if (host_of[(size_t)r] < 0) tail_rows.push_back(r);
+            continue;
+        }
+        order.push_back(r);
+        for (int32_t g = guests_head[(size_t)r]; g >= 0; g = guests_next[(size_t)g]) order.push_back(g);
+    }
+    order.insert(order.end(), tail_rows.begin(), tail_rows.end());
+    order.insert(order.end(), empties.begin(), empties.end());
+    return (int64_t)order.size() == n ? RSH_OK : RSH_ERR_INVALID_CSR;
 }
 
 }  // namespace rsh
