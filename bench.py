@@ -32,6 +32,8 @@ def main() -> int:
     ap.add_argument("--reorder", type=int, default=-1, help="override the plan's reorder option")
     ap.add_argument("--opt", action="append", default=[], help="plan option override name=value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run the library's plain copy kernel on 1 GiB (for scaling profiler traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU (no sharding, no collectives); run with --gpus 1",
@@ -74,6 +76,15 @@ def main() -> int:
     ms_per_step = 1e3 * elapsed / args.steps
     flops = 2.0 * A.nnz * N
     gflops = flops / (ms_per_step * 1e-3) / 1e9
+
+    if args.calibrate_copy:
+        from paper_2603_08734_amd.binding import rsh_copy_probe
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            rsh_copy_probe(src, dst, 1 << 30)
+        torch.cuda.synchronize()
+        del src, dst
 
     # per-kernel durations with HIP events on the launch stream
     acc = {"tile": 0.0, "irregular": 0.0, "combine": 0.0}

@@ -81,7 +81,8 @@ typedef struct {
     int64_t n_irregular_rows, nnz_irregular;   /* residual part                                  */
     int64_t n_empty_rows;
     int64_t n_tile_items, n_split_windows;     /* tile work items; windows cut into > 1 item     */
-    int64_t n_segments, n_irregular_waves, n_split_rows; /* team segments, waves, rows cut in > 1 slice */
+    int64_t n_irregular_waves, n_slice_waves, n_short_row_waves, n_zero_waves; /* irregular-kernel waves by kind */
+    int64_t n_split_rows;                      /* irregular rows cut into more than one slice    */
     int64_t n_combine, n_scratch_slots;        /* combine entries; fp32 rows of N in scratch     */
     int64_t sum_window_cols;                   /* sum over windows of |U_w| (distinct columns)   */
     int64_t plan_bytes, csr_bytes;             /* device bytes of the plan vs 6*nnz + 8*(n_rows+1) */
@@ -127,6 +128,13 @@ typedef struct { float ms_tile, ms_irregular, ms_combine; } rsh_kernel_times_t;
 int rsh_spmm_profile(const rsh_plan_t *plan, const void *B_dev, void *C_dev, void *hip_stream,
                      rsh_kernel_times_t *out);
 
+/*
+ * Measurement aid, not part of the method: enqueue a plain device-to-device copy of
+ * `bytes` bytes (a multiple of 16; both pointers 16-byte aligned) on hip_stream.  A kernel
+ * that moves a known number of bytes calibrates the HBM traffic counters of a profiler.
+ */
+int rsh_copy_probe(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream);
+
 int rsh_plan_destroy(rsh_plan_t *plan); /* NULL is a no-op */
 
 int rsh_plan_stats(const rsh_plan_t *plan, rsh_plan_stats_t *out);
@@ -166,21 +174,29 @@ int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
  * Irregular part (RS-Tile "residual part", Section 3.2):
  *   RSH_ARR_IRR_COL      int32  []              column ids, CSR order inside a row
  *   RSH_ARR_IRR_VAL      uint16 []              binary16 values, same order
- *   RSH_ARR_SEG          uint32 [n_segments*4]  {start, len, dst, kind} per team segment;
- *                                               kind bit0: dst is a scratch slot (else a row of C,
- *                                               0xffffffff = nothing to write), bit1: the teams of
- *                                               this wave hold pieces of one row slice and are summed
+ *   RSH_ARR_IRR_WAVE     uint32 [n_waves*4]     {start, count, dst, info} per wave of the irregular
+ *                                               kernel; info = kind | flags | L << 8 | R << 16:
+ *                                                 kind 0 (short rows): `count` rows of exactly L entries
+ *                                                   each lie back to back from `start`; their row ids are
+ *                                                   IRR_ROW[dst .. dst+count); a team handles R = T/L rows
+ *                                                   (T = lanes per team);
+ *                                                 kind 1 (slice): `count` consecutive entries of one row
+ *                                                   from `start`; dst is the row of C, or with flag bit 2
+ *                                                   a scratch slot; the teams split the slice evenly;
+ *                                                 kind 2 (zero rows): rows IRR_ROW[dst .. dst+count) of C
+ *                                                   are set to 0
+ *   RSH_ARR_IRR_ROW      int32  []              row ids named by kind-0 and kind-2 waves
  * Combine:
  *   RSH_ARR_COMBINE      uint32 [n_combine*4]   {row, first slot, parts, slot stride}
  */
 enum {
     RSH_ARR_WIN_ROW = 0, RSH_ARR_WIN_TILE_OFF, RSH_ARR_TILE_COLID, RSH_ARR_TILE_MASK,
     RSH_ARR_TILE_VAL_OFF, RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL,
-    RSH_ARR_SEG, RSH_ARR_COMBINE, RSH_ARR_COUNT
+    RSH_ARR_IRR_WAVE, RSH_ARR_IRR_ROW, RSH_ARR_COMBINE, RSH_ARR_COUNT
 };
 int rsh_plan_array(const rsh_plan_t *plan, int32_t which, const void **ptr, int64_t *count);
 
-/* Number of team segments one wave of the irregular kernel consumes for this plan's N. */
+/* Number of lane teams in one wave of the irregular kernel for this plan's N (64 / lanes per team). */
 int rsh_plan_teams_per_wave(const rsh_plan_t *plan, int32_t *teams);
 
 const char *rsh_status_string(int status);

@@ -9,9 +9,11 @@ numpy, following only the layout documented in the public header:
   column ids, a 256-bit map (four 64-bit words; cell (row r, column k) is bit
   (k // 4) * 16 + r of word k % 4) and a run of values that starts at
   tile_val_off[t] and is ordered by ((k // 4) * 16 + r, k % 4);
-* an irregular segment (start, len, dst, kind) holds len consecutive entries of one
-  row; the row is dst itself, or, when kind has bit 0 set, the row whose combine
-  entry (row, first slot, parts, stride) covers scratch slot dst.
+* an irregular wave (start, count, dst, info) is, by info & 3: kind 0 -- count rows
+  of exactly L = (info >> 8) & 255 entries each, back to back from start, whose row
+  ids are irr_row[dst .. dst+count); kind 1 -- count consecutive entries of one row,
+  the row being dst itself or, when info has bit 2 set, the row whose combine entry
+  (row, first slot, parts, stride) covers scratch slot dst; kind 2 -- no entries.
 """
 from __future__ import annotations
 
@@ -19,7 +21,7 @@ import numpy as np
 
 
 def entries_from_arrays(win_row, win_tile_off, tile_colid, tile_mask, tile_val_off, tile_val,
-                        irr_col, irr_val, seg, combine, n_scratch_slots):
+                        irr_col, irr_val, irr_wave, irr_row, combine, n_scratch_slots):
     rows, cols, vals, paths = [], [], [], []
     n_win = len(win_row) // 16
     for w in range(n_win):
@@ -45,16 +47,24 @@ def entries_from_arrays(win_row, win_tile_off, tile_colid, tile_mask, tile_val_o
             slot = first + p * stride
             assert slot not in slot_row and slot < n_scratch_slots
             slot_row[slot] = row
-    for s in range(len(seg) // 4):
-        start, length, dst, kind = (int(x) for x in seg[4 * s:4 * s + 4])
-        if length == 0:
-            continue
-        row = slot_row[dst] if (kind & 1) else dst
-        for q in range(length):
-            rows.append(row)
-            cols.append(int(irr_col[start + q]))
-            vals.append(int(irr_val[start + q]))
-            paths.append(1)
+    for s in range(len(irr_wave) // 4):
+        start, count, dst, info = (int(x) for x in irr_wave[4 * s:4 * s + 4])
+        kind = info & 3
+        if kind == 0:
+            L = (info >> 8) & 255
+            for q in range(count):
+                for j in range(L):
+                    rows.append(int(irr_row[dst + q]))
+                    cols.append(int(irr_col[start + q * L + j]))
+                    vals.append(int(irr_val[start + q * L + j]))
+                    paths.append(1)
+        elif kind == 1:
+            row = slot_row[dst] if (info & 4) else dst
+            for q in range(count):
+                rows.append(row)
+                cols.append(int(irr_col[start + q]))
+                vals.append(int(irr_val[start + q]))
+                paths.append(1)
     return (np.array(rows, dtype=np.int64), np.array(cols, dtype=np.int64),
             np.array(vals, dtype=np.uint16), np.array(paths, dtype=np.uint8))
 

@@ -18,18 +18,18 @@ RSH_OK = 0
  RSH_ERR_HIP, RSH_ERR_NOT_UPLOADED, RSH_ERR_TOO_LARGE) = range(1, 9)
 
 (RSH_ARR_WIN_ROW, RSH_ARR_WIN_TILE_OFF, RSH_ARR_TILE_COLID, RSH_ARR_TILE_MASK, RSH_ARR_TILE_VAL_OFF,
- RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL, RSH_ARR_SEG, RSH_ARR_COMBINE,
- RSH_ARR_COUNT) = range(12)
+ RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL, RSH_ARR_IRR_WAVE, RSH_ARR_IRR_ROW,
+ RSH_ARR_COMBINE, RSH_ARR_COUNT) = range(13)
 
 _ARRAY_DTYPES = {
     RSH_ARR_WIN_ROW: np.int32, RSH_ARR_WIN_TILE_OFF: np.uint32, RSH_ARR_TILE_COLID: np.int32,
     RSH_ARR_TILE_MASK: np.uint64, RSH_ARR_TILE_VAL_OFF: np.uint32, RSH_ARR_TILE_VAL: np.uint16,
     RSH_ARR_TILE_ITEM: np.uint32, RSH_ARR_IRR_COL: np.int32, RSH_ARR_IRR_VAL: np.uint16,
-    RSH_ARR_SEG: np.uint32, RSH_ARR_COMBINE: np.uint32,
+    RSH_ARR_IRR_WAVE: np.uint32, RSH_ARR_IRR_ROW: np.int32, RSH_ARR_COMBINE: np.uint32,
 }
 
 EXPORTED_SYMBOLS = [
-    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_profile", "rsh_plan_destroy", "rsh_plan_stats",
+    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_profile", "rsh_copy_probe", "rsh_plan_destroy", "rsh_plan_stats",
     "rsh_plan_decode", "rsh_plan_row_order", "rsh_plan_array", "rsh_plan_teams_per_wave",
     "rsh_status_string", "rsh_last_hip_error",
 ]
@@ -57,7 +57,8 @@ class rsh_plan_stats_t(ctypes.Structure):
     _fields_ = ([(n, ctypes.c_int64) for n in ("n_rows", "n_cols", "nnz")] + [("N", ctypes.c_int32)] +
                 [(n, ctypes.c_int64) for n in (
                     "n_windows", "n_tiles", "nnz_tile", "n_irregular_rows", "nnz_irregular", "n_empty_rows",
-                    "n_tile_items", "n_split_windows", "n_segments", "n_irregular_waves", "n_split_rows",
+                    "n_tile_items", "n_split_windows", "n_irregular_waves", "n_slice_waves", "n_short_row_waves",
+                    "n_zero_waves", "n_split_rows",
                     "n_combine", "n_scratch_slots", "sum_window_cols", "plan_bytes", "csr_bytes",
                     "tile_part_bytes", "irregular_part_bytes", "cols_all", "cols_tile", "cols_irregular",
                     "rows_tile", "rows_irregular")] +
@@ -85,6 +86,7 @@ def lib() -> ctypes.CDLL:
                                       ctypes.POINTER(vp)]
         L.rsh_spmm.argtypes = [vp, vp, vp, vp]
         L.rsh_spmm_profile.argtypes = [vp, vp, vp, vp, ctypes.POINTER(rsh_kernel_times_t)]
+        L.rsh_copy_probe.argtypes = [vp, vp, ctypes.c_int64, vp]
         L.rsh_plan_destroy.argtypes = [vp]
         L.rsh_plan_stats.argtypes = [vp, ctypes.POINTER(rsh_plan_stats_t)]
         L.rsh_plan_decode.argtypes = [vp, vp, vp, vp, vp]
@@ -120,6 +122,15 @@ def rsh_plan_opts_default() -> rsh_plan_opts_t:
     o = rsh_plan_opts_t()
     _check(lib().rsh_plan_opts_default(ctypes.byref(o)))
     return o
+
+
+def rsh_copy_probe(src, dst, nbytes: int, stream=None) -> None:
+    """Enqueue the calibration copy kernel (src, dst: device tensors)."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().rsh_copy_probe(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), int(nbytes),
+                                ctypes.c_void_p(stream)))
 
 
 class Plan:

@@ -42,7 +42,7 @@ int upload_array(const std::vector<T>& h, T** d) {
 
 void free_device(rsh::DevicePlan& d) {
     void* ptrs[] = {d.win_row, d.win_tile_off, d.tile_colid, d.tile_mask, d.tile_val_off, d.tile_val,
-                    d.tile_item, d.irr_col, d.irr_val, d.seg, d.combine, d.scratch};
+                    d.tile_item, d.irr_col, d.irr_val, d.irr_wave, d.irr_row, d.combine, d.scratch};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = rsh::DevicePlan{};
@@ -53,9 +53,11 @@ int upload_plan(rsh_plan& p) {
     rsh::DevicePlan& d = p.dev;
     d.geo = h.geo;
     d.n_tile_items = (int64_t)h.tile_item.size() / 4;
-    d.n_segments = (int64_t)h.seg.size() / 4;
+    d.n_irr_waves = (int64_t)h.irr_wave.size() / 4;
     d.n_combine = (int64_t)h.combine.size() / 4;
     d.n_scratch_slots = h.n_scratch_slots;
+    d.tile_split = h.tile_split;
+    d.irr_split = h.irr_split;
     int rc;
     if ((rc = upload_array(h.win_row, &d.win_row))) return rc;
     if ((rc = upload_array(h.win_tile_off, &d.win_tile_off))) return rc;
@@ -66,7 +68,8 @@ int upload_plan(rsh_plan& p) {
     if ((rc = upload_array(h.tile_item, &d.tile_item))) return rc;
     if ((rc = upload_array(h.irr_col, &d.irr_col))) return rc;
     if ((rc = upload_array(h.irr_val, &d.irr_val))) return rc;
-    if ((rc = upload_array(h.seg, &d.seg))) return rc;
+    if ((rc = upload_array(h.irr_wave, &d.irr_wave))) return rc;
+    if ((rc = upload_array(h.irr_row, &d.irr_row))) return rc;
     if ((rc = upload_array(h.combine, &d.combine))) return rc;
     const size_t sbytes = (size_t)std::max<int64_t>(1, h.n_scratch_slots) * (size_t)h.geo.N * sizeof(float);
     if (!hip_ok(hipMalloc((void**)&d.scratch, sbytes))) return RSH_ERR_OOM;
@@ -219,13 +222,19 @@ int rsh_spmm_profile(const rsh_plan_t* plan, const void* B_dev, void* C_dev, voi
         if (rc == RSH_OK) {
             float ms = 0.f;
             if (plan->dev.n_tile_items > 0 && hip_ok(hipEventElapsedTime(&ms, ev[0], ev[1]))) out->ms_tile = ms;
-            if (plan->dev.n_segments > 0 && hip_ok(hipEventElapsedTime(&ms, ev[1], ev[2]))) out->ms_irregular = ms;
+            if (plan->dev.n_irr_waves > 0 && hip_ok(hipEventElapsedTime(&ms, ev[1], ev[2]))) out->ms_irregular = ms;
             if (plan->dev.n_combine > 0 && hip_ok(hipEventElapsedTime(&ms, ev[2], ev[3]))) out->ms_combine = ms;
         }
     }
     for (int i = 0; i < 4; ++i)
         if (ev[i]) (void)hipEventDestroy(ev[i]);
     return rc;
+}
+
+int rsh_copy_probe(const void* src_dev, void* dst_dev, int64_t bytes, void* hip_stream) {
+    if (!src_dev || !dst_dev) return RSH_ERR_NULL;
+    if (bytes < 0 || (bytes & 15) || ((uintptr_t)src_dev & 15u) || ((uintptr_t)dst_dev & 15u)) return RSH_ERR_BAD_OPTION;
+    return rsh::launch_copy_probe(src_dev, dst_dev, (size_t)bytes, hip_stream);
 }
 
 int rsh_plan_destroy(rsh_plan_t* plan) {
@@ -275,7 +284,8 @@ int rsh_plan_array(const rsh_plan_t* plan, int32_t which, const void** ptr, int6
         RSH_CASE(RSH_ARR_TILE_ITEM, h.tile_item)
         RSH_CASE(RSH_ARR_IRR_COL, h.irr_col)
         RSH_CASE(RSH_ARR_IRR_VAL, h.irr_val)
-        RSH_CASE(RSH_ARR_SEG, h.seg)
+        RSH_CASE(RSH_ARR_IRR_WAVE, h.irr_wave)
+        RSH_CASE(RSH_ARR_IRR_ROW, h.irr_row)
         RSH_CASE(RSH_ARR_COMBINE, h.combine)
         default: return RSH_ERR_BAD_OPTION;
     }

@@ -8,6 +8,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
+
 #include "launch.hpp"
 
 namespace rsh {
@@ -17,11 +19,15 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kWavesPerBlock = 4;
 
-// Workgroups are dealt to the 8 XCDs round-robin; each XCD has its own L2.  Remap the
-// block index so that one XCD walks a contiguous eighth of the work list and rows that
-// are neighbours in the plan share an L2.  `per_xcd` = gridDim.x / 8.
-__device__ __forceinline__ uint32_t xcd_contiguous_block(uint32_t b, uint32_t per_xcd) {
-    return (b & 7u) * per_xcd + (b >> 3);
+// Workgroups are dealt to the 8 XCDs round-robin; each XCD has its own L2.  Block b
+// therefore serves XCD b % 8 and takes the (b / 8)-th group of kWavesPerBlock items of
+// that XCD's contiguous, cost-balanced part of the work list, so that items which are
+// neighbours in the plan share an L2.  Returns false when the part is exhausted.
+__device__ __forceinline__ bool xcd_work_item(const XcdSplit& xs, uint32_t* item) {
+    const uint32_t x = blockIdx.x & 7u;
+    const uint32_t i = xs.start[x] + (blockIdx.x >> 3) * kWavesPerBlock + (threadIdx.x >> 6);
+    *item = __builtin_amdgcn_readfirstlane(i);
+    return i < xs.start[x + 1];
 }
 
 __device__ __forceinline__ int shfl_i32(int v, int src_lane) { return __builtin_amdgcn_ds_bpermute(src_lane << 2, v); }
@@ -42,78 +48,136 @@ union Pack16 {
 // ---------------------------------------------------------------------------
 // Irregular rows.  A wave is G = 64/TPR teams of TPR lanes; lane t of a team owns
 // features [8t, 8t+8) of the current panel, so a team reads one B row segment as TPR
-// coalesced 16-byte loads.  Each team walks its own segment of stored entries; the
-// (column, value) pairs of TPR consecutive entries are fetched by the team's lanes in
-// one coalesced load and handed round with a cross-lane read.  A wave whose teams
-// hold pieces of the same row slice sums them with a butterfly over the teams.
+// coalesced 16-byte loads.  The (column, value) pairs of TPR consecutive stored entries
+// are fetched by the team's lanes with one coalesced load and handed round with a
+// cross-lane read, and up to eight B-row loads are in flight per team before the first
+// FMA.  Three kinds of wave (see the plan format):
+//   short rows : every team owns R complete rows of L entries (L*R <= TPR), all teams
+//                of the wave step in lock step and store a row after every L entries;
+//   slice      : the G teams split one run of a long row evenly and are summed with a
+//                butterfly over the teams; the sum goes to C or to a scratch slot;
+//   zero rows  : rows without stored entries are cleared.
 // ---------------------------------------------------------------------------
 template <int TPR>
+__device__ __forceinline__ void gather_fma(const __half* __restrict__ Bp, int N, int my_col, float my_val,
+                                           int team_base, int j0, int nb, float (&acc)[8]) {
+    Pack16 b[8];
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        if (u < nb) {
+            const int c = shfl_i32(my_col, team_base + j0 + u);
+            v[u] = shfl_f32(my_val, team_base + j0 + u);
+            b[u].u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
+        }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        if (u < nb) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = fmaf(v[u], __half2float(b[u].h[i]), acc[i]);
+        }
+}
+
+template <int TPR>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
-    const uint4* __restrict__ seg, uint32_t n_waves, uint32_t blocks_per_xcd,
-    const int32_t* __restrict__ irr_col, const uint16_t* __restrict__ irr_val,
-    const __half* __restrict__ B, float* __restrict__ C, float* __restrict__ scratch, int N) {
+    const uint4* __restrict__ waves, XcdSplit xs,
+    const int32_t* __restrict__ irr_row, const int32_t* __restrict__ irr_col,
+    const uint16_t* __restrict__ irr_val, const __half* __restrict__ B, float* __restrict__ C,
+    float* __restrict__ scratch, int N) {
     constexpr int G = 64 / TPR;
     const int lane = threadIdx.x & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(
-        xcd_contiguous_block(blockIdx.x, blocks_per_xcd) * kWavesPerBlock + (threadIdx.x >> 6));
-    if (wave >= n_waves) return;
+    uint32_t wave;
+    if (!xcd_work_item(xs, &wave)) return;
     const int team = lane / TPR, tl = lane % TPR, team_base = team * TPR;
     const int feat = blockIdx.y * (TPR * 8) + tl * 8;
 
-    const uint4 s = seg[(size_t)wave * G + team];
-    const uint32_t start = s.x, len = s.y, dst = s.z, kind = s.w;
-
-    // longest segment among the teams (wave-uniform loop bound)
-    uint32_t max_len = len;
-#pragma unroll
-    for (int off = TPR; off < 64; off <<= 1) max_len = max(max_len, (uint32_t)shfl_i32((int)max_len, lane ^ off));
-    max_len = __builtin_amdgcn_readfirstlane(max_len);
+    const uint4 d = waves[wave];
+    const uint32_t start = __builtin_amdgcn_readfirstlane(d.x), count = __builtin_amdgcn_readfirstlane(d.y);
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(d.z), info = __builtin_amdgcn_readfirstlane(d.w);
+    const uint32_t kind = info & kWaveKindMask;
+    const __half* Bp = B + feat;
 
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
-    const __half* Bp = B + feat;
-    for (uint32_t base = 0; base < max_len; base += TPR) {
-        const uint32_t p = base + tl;
-        const bool ok = p < len;
-        const int my_col = ok ? irr_col[start + p] : 0;
-        const float my_val = ok ? __half2float(__ushort_as_half(irr_val[start + p])) : 0.f;
-        const int steps = (int)min((uint32_t)TPR, max_len - base);
-        int j = 0;
-        for (; j + 4 <= steps; j += 4) {
-            Pack16 b[4];
-            float v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = shfl_i32(my_col, team_base + j + u);
-                v[u] = shfl_f32(my_val, team_base + j + u);
-                b[u].u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = fmaf(v[u], __half2float(b[u].h[i]), acc[i]);
+    if (kind == kWaveZeroRows) {
+        for (uint32_t q = team; q < count; q += G) {
+            float* out = C + (size_t)irr_row[dst + q] * N + feat;
+            *reinterpret_cast<float4*>(out) = make_float4(0.f, 0.f, 0.f, 0.f);
+            *reinterpret_cast<float4*>(out + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        for (; j < steps; ++j) {
-            const int c = shfl_i32(my_col, team_base + j);
-            const float v = shfl_f32(my_val, team_base + j);
-            Pack16 b;
-            b.u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = fmaf(v, __half2float(b.h[i]), acc[i]);
-        }
+        return;
     }
 
-    if (kind & kSegWaveReduce) {
+    if (kind == kWaveShortRows) {
+        const int L = (int)((info >> 8) & 0xffu), R = (int)((info >> 16) & 0xffu);
+        const uint32_t q0 = (uint32_t)(team * R);
+        const int n_rows_mine = count > q0 ? (int)min((uint32_t)R, count - q0) : 0;
+        const int n_mine = n_rows_mine * L;
+        const uint32_t p0 = start + q0 * (uint32_t)L;
+        const int my_col = tl < n_mine ? irr_col[p0 + tl] : 0;
+        const float my_val = tl < n_mine ? __half2float(__ushort_as_half(irr_val[p0 + tl])) : 0.f;
+        const int my_row = tl < n_rows_mine ? irr_row[dst + q0 + tl] : -1;
+        const int steps = R * L;
+        int k = 0, rq = 0;
+        for (int j0 = 0; j0 < steps; j0 += 8) {
+            const int nb = min(8, steps - j0);
+            Pack16 b[8];
+            float v[8];
 #pragma unroll
-        for (int off = TPR; off < 64; off <<= 1)
+            for (int u = 0; u < 8; ++u)
+                if (u < nb) {
+                    const int c = shfl_i32(my_col, team_base + j0 + u);
+                    v[u] = shfl_f32(my_val, team_base + j0 + u);
+                    b[u].u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
+                }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += shfl_f32(acc[i], lane ^ off);
-        if (team != 0) return;
+            for (int u = 0; u < 8; ++u)
+                if (u < nb) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[i] = fmaf(v[u], __half2float(b[u].h[i]), acc[i]);
+                    if (++k == L) {   // a row is complete (same step for every team of the wave)
+                        k = 0;
+                        const int row = shfl_i32(my_row, team_base + rq);
+                        ++rq;
+                        if (row >= 0) {
+                            float* out = C + (size_t)row * N + feat;
+                            *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                            *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+                        }
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+                    }
+                }
+        }
+        return;
     }
-    if (dst == kNoDst) return;
-    float* out = ((kind & kSegToScratch) ? scratch : C) + (size_t)dst * N + feat;
+
+    // slice of a long row: team t owns entries [count*t/G, count*(t+1)/G) of the slice
+    const uint32_t pb = start + (uint32_t)(((uint64_t)count * (uint32_t)team) / G);
+    const uint32_t pe = start + (uint32_t)(((uint64_t)count * (uint32_t)(team + 1)) / G);
+    const uint32_t len = pe - pb;
+    const uint32_t max_len = (count + G - 1) / G;   // longest team piece
+    int nxt_col = (uint32_t)tl < len ? irr_col[pb + tl] : 0;
+    float nxt_val = (uint32_t)tl < len ? __half2float(__ushort_as_half(irr_val[pb + tl])) : 0.f;
+    for (uint32_t base = 0; base < max_len; base += TPR) {
+        const int my_col = nxt_col;
+        const float my_val = nxt_val;
+        if (base + TPR < max_len) {   // prefetch the next run of (column, value) pairs
+            const uint32_t p = base + TPR + tl;
+            nxt_col = p < len ? irr_col[pb + p] : 0;
+            nxt_val = p < len ? __half2float(__ushort_as_half(irr_val[pb + p])) : 0.f;
+        }
+        const int steps = (int)min((uint32_t)TPR, max_len - base);
+        for (int j0 = 0; j0 < steps; j0 += 8) gather_fma<TPR>(Bp, N, my_col, my_val, team_base, j0, min(8, steps - j0), acc);
+    }
+#pragma unroll
+    for (int off = TPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += shfl_f32(acc[i], lane ^ off);
+    if (team != 0) return;
+    float* out = ((info & kWaveToScratch) ? scratch : C) + (size_t)dst * N + feat;
     *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
     *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
 }
@@ -133,7 +197,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
 // ---------------------------------------------------------------------------
 template <int NCH>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
-    const uint4* __restrict__ items, uint32_t n_items, uint32_t blocks_per_xcd,
+    const uint4* __restrict__ items, XcdSplit xs,
     const int32_t* __restrict__ win_row, const int32_t* __restrict__ tile_colid,
     const uint64_t* __restrict__ tile_mask, const uint32_t* __restrict__ tile_val_off,
     const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, float* __restrict__ C,
@@ -149,8 +213,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
 
     const int lane = threadIdx.x & 63;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t item = xcd_contiguous_block(blockIdx.x, blocks_per_xcd) * kWavesPerBlock + wib;
-    if (item >= n_items) return;
+    uint32_t item;
+    if (!xcd_work_item(xs, &item)) return;
     const uint4 it = items[item];
     const uint32_t win = __builtin_amdgcn_readfirstlane(it.x), t_begin = __builtin_amdgcn_readfirstlane(it.y);
     const uint32_t t_end = __builtin_amdgcn_readfirstlane(it.z), dst = __builtin_amdgcn_readfirstlane(it.w);
@@ -269,30 +333,45 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_combine_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Plain streaming copy (16 bytes per lane per step).  It moves a known number of bytes,
+// which calibrates what the HBM traffic counters report per byte.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rsh_copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+int launch_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return RSH_OK;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(rsh_copy_probe_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, n16);
+    return hipGetLastError() == hipSuccess ? RSH_OK : RSH_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
-static inline uint32_t blocks_per_xcd_for(uint32_t n_waves) {
-    const uint32_t blocks = (n_waves + kWavesPerBlock - 1) / kWavesPerBlock;
-    return (blocks + 7) / 8;
+// Grid size: 8 x the number of blocks the largest XCD part needs.
+static inline uint32_t grid_for(const XcdSplit& xs) {
+    uint32_t longest = 0;
+    for (int x = 0; x < 8; ++x) longest = std::max(longest, xs.start[x + 1] - xs.start[x]);
+    return 8u * ((longest + kWavesPerBlock - 1) / kWavesPerBlock);
 }
 
 template <int TPR>
 static void launch_irregular_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
-    const uint32_t n_waves = (uint32_t)(d.n_segments / (64 / TPR));
-    const uint32_t per = blocks_per_xcd_for(n_waves);
-    dim3 grid(per * 8, (unsigned)(d.geo.N / d.geo.irr_panel));
+    dim3 grid(grid_for(d.irr_split), (unsigned)(d.geo.N / d.geo.irr_panel));
     hipLaunchKernelGGL(rsh_irregular_kernel<TPR>, grid, dim3(64 * kWavesPerBlock), 0, st,
-                       (const uint4*)d.seg, n_waves, per, d.irr_col, d.irr_val, (const __half*)B, (float*)C,
+                       (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, (float*)C,
                        d.scratch, d.geo.N);
 }
 
 template <int NCH>
 static void launch_tile_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
-    const uint32_t n_items = (uint32_t)d.n_tile_items;
-    const uint32_t per = blocks_per_xcd_for(n_items);
-    dim3 grid(per * 8, (unsigned)(d.geo.N / d.geo.tile_panel));
+    dim3 grid(grid_for(d.tile_split), (unsigned)(d.geo.N / d.geo.tile_panel));
     hipLaunchKernelGGL(rsh_tile_kernel<NCH>, grid, dim3(64 * kWavesPerBlock), 0, st, (const uint4*)d.tile_item,
-                       n_items, per, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off, d.tile_val,
+                       d.tile_split, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off, d.tile_val,
                        (const __half*)B, (float*)C, d.scratch, d.geo.N);
 }
 
@@ -313,7 +392,7 @@ int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void*
         }
     }
     mark(1);
-    if (d.n_segments > 0) {
+    if (d.n_irr_waves > 0) {
         switch (d.geo.irr_tpr) {
             case 2: launch_irregular_t<2>(d, B, C, st); break;
             case 4: launch_irregular_t<4>(d, B, C, st); break;

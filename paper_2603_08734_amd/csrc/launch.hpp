@@ -1,5 +1,6 @@
 // Device-side view of a plan and the launcher entry used by the C ABI.
 #pragma once
+#include <cstddef>
 #include <cstdint>
 
 #include "plan.hpp"
@@ -8,7 +9,8 @@ namespace rsh {
 
 struct DevicePlan {
     Geometry geo;
-    int64_t n_tile_items = 0, n_segments = 0, n_combine = 0, n_scratch_slots = 0;
+    int64_t n_tile_items = 0, n_irr_waves = 0, n_combine = 0, n_scratch_slots = 0;
+    XcdSplit tile_split, irr_split;
     int32_t* win_row = nullptr;
     uint32_t* win_tile_off = nullptr;
     int32_t* tile_colid = nullptr;
@@ -18,7 +20,8 @@ struct DevicePlan {
     uint32_t* tile_item = nullptr;
     int32_t* irr_col = nullptr;
     uint16_t* irr_val = nullptr;
-    uint32_t* seg = nullptr;
+    uint32_t* irr_wave = nullptr;
+    int32_t* irr_row = nullptr;
     uint32_t* combine = nullptr;
     float* scratch = nullptr;
 };
@@ -27,5 +30,8 @@ struct DevicePlan {
 // `events` is not null it points at four hipEvent_t recorded before the tile kernel and
 // after each of the three kernels.
 int launch_spmm(const DevicePlan& d, const void* B_dev, void* C_dev, void* stream, void* const* events);
+
+// Plain device-to-device copy of `bytes` (multiple of 16) used to calibrate traffic counters.
+int launch_copy_probe(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
 
 }  // namespace rsh

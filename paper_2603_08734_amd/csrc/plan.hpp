@@ -10,8 +10,12 @@ namespace rsh {
 constexpr int kW = 16;  // rows per window  (MFMA N extent)
 constexpr int kK = 16;  // condensed columns per fragment (MFMA K extent)
 constexpr uint32_t kNoDst = 0xffffffffu;
-constexpr uint32_t kSegToScratch = 1u;   // segment result goes to a scratch slot
-constexpr uint32_t kSegWaveReduce = 2u;  // the teams of the wave hold pieces of one row slice
+// irregular wave descriptor {start, count, dst, info}; info = kind | flags | L << 8 | R << 16
+constexpr uint32_t kWaveShortRows = 0u;  // `count` rows of L entries each, R rows per team; dst indexes irr_row
+constexpr uint32_t kWaveSlice = 1u;      // `count` consecutive entries of one row; dst = row of C or scratch slot
+constexpr uint32_t kWaveZeroRows = 2u;   // `count` rows of irr_row (from dst) receive zeros
+constexpr uint32_t kWaveKindMask = 3u;
+constexpr uint32_t kWaveToScratch = 4u;  // slice result goes to a scratch slot
 
 // Feature-panel geometry derived from N (both kernels walk N in panels).
 struct Geometry {
@@ -23,6 +27,13 @@ struct Geometry {
     int tile_nch = 0;   // 16-feature MFMA chunks per panel
 };
 Geometry make_geometry(int N);
+
+// Work lists are cut into 8 contiguous parts of equal estimated cost, one per XCD:
+// part x is items [start[x], start[x+1]).
+struct XcdSplit {
+    uint32_t start[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+};
+XcdSplit split_by_cost(const std::vector<uint32_t>& cost);
 
 struct HostPlan {
     int64_t n_rows = 0, n_cols = 0, nnz = 0;
@@ -41,8 +52,10 @@ struct HostPlan {
     // irregular part
     std::vector<int32_t> irr_col;
     std::vector<uint16_t> irr_val;
-    std::vector<uint32_t> seg;  // 4 per team segment
+    std::vector<uint32_t> irr_wave;  // 4 per wave
+    std::vector<int32_t> irr_row;    // row ids named by short-row and zero-row waves
     // combine
+    XcdSplit tile_split, irr_split;
     std::vector<uint32_t> combine;  // 4 per entry
     int64_t n_scratch_slots = 0;
 

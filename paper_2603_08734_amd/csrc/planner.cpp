@@ -208,6 +208,21 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
 // ---------------------------------------------------------------------------
 // packing
 // ---------------------------------------------------------------------------
+XcdSplit split_by_cost(const std::vector<uint32_t>& cost) {
+    XcdSplit s;
+    uint64_t total = 0;
+    for (uint32_t c : cost) total += c;
+    uint64_t run = 0;
+    int x = 1;
+    for (size_t i = 0; i < cost.size() && x < 8; ++i) {
+        run += cost[i];
+        while (x < 8 && run * 8 >= total * (uint64_t)x) s.start[x++] = (uint32_t)(i + 1);
+    }
+    for (; x < 8; ++x) s.start[x] = (uint32_t)cost.size();
+    s.start[8] = (uint32_t)cost.size();
+    return s;
+}
+
 static inline uint32_t round_up4(uint32_t x) { return (x + 3u) & ~3u; }
 
 struct WinEntry {
@@ -364,72 +379,102 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         slots += (int64_t)parts * kW;
     }
     const int64_t n_tile_combine = (int64_t)plan.combine.size() / 4;
+    {
+        std::vector<uint32_t> cost(plan.tile_item.size() / 4);
+        for (size_t i = 0; i < cost.size(); ++i) cost[i] = plan.tile_item[4 * i + 2] - plan.tile_item[4 * i + 1] + 4u;
+        plan.tile_split = split_by_cost(cost);
+    }
 
-    // ---- irregular rows -> team segments ------------------------------------------------
+    // ---- irregular rows -> wave work items ------------------------------------------------
+    // Stream layout: rows longer than one team pass first (processing order), then the short
+    // rows grouped by exact length, longest first, so that every wave of the short-row kind
+    // runs rows of one length and its teams stay in lock step.
     const int G = geo.irr_teams, TPR = geo.irr_tpr;
-    const int64_t short_max = std::max(2 * TPR, 16);
     const int64_t slice_max = plan.opts.max_nnz_per_slice > 0 ? plan.opts.max_nnz_per_slice : 256;
     const int64_t n_irr = (int64_t)part.irregular.size();
-    std::vector<uint32_t> irr_start((size_t)n_irr + 1, 0);
+    std::vector<std::vector<int32_t>> by_len((size_t)TPR + 1);   // by_len[L] = short rows with L entries
+    std::vector<int32_t> long_rows;
+    int64_t nnz_irr = 0;
     for (int64_t i = 0; i < n_irr; ++i) {
-        const uint64_t s = (uint64_t)irr_start[i] + (uint64_t)row_len(a, part.irregular[i]);
-        if (s >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
-        irr_start[i + 1] = (uint32_t)s;
+        const int32_t r = part.irregular[i];
+        const int64_t len = row_len(a, r);
+        nnz_irr += len;
+        if (len <= TPR) by_len[(size_t)len].push_back(r);
+        else long_rows.push_back(r);
     }
-    const int64_t nnz_irr = irr_start[n_irr];
+    if (nnz_irr >= (1ll << 31)) return RSH_ERR_TOO_LARGE;
+    std::vector<int32_t> stream_rows;                 // rows in stream order
+    stream_rows.reserve((size_t)n_irr);
+    stream_rows.insert(stream_rows.end(), long_rows.begin(), long_rows.end());
+    for (int L = TPR; L >= 1; --L) stream_rows.insert(stream_rows.end(), by_len[(size_t)L].begin(), by_len[(size_t)L].end());
+    std::vector<uint32_t> irr_start((size_t)n_irr + 1, 0);
+    for (int64_t i = 0; i < n_irr; ++i) irr_start[i + 1] = irr_start[i] + (uint32_t)row_len(a, stream_rows[(size_t)i]);
     plan.irr_col.assign((size_t)nnz_irr + 64, 0);   // tail pad keeps lane-wise reads in bounds
     plan.irr_val.assign((size_t)nnz_irr + 64, 0);
     parallel_chunks(n_irr, threads, [&](int64_t b, int64_t e, int) {
         for (int64_t i = b; i < e; ++i) {
-            const int32_t r = part.irregular[i];
+            const int32_t r = stream_rows[(size_t)i];
             const int64_t len = row_len(a, r);
             std::memcpy(&plan.irr_col[irr_start[i]], a.col_idx + a.row_ptr[r], (size_t)len * sizeof(int32_t));
             std::memcpy(&plan.irr_val[irr_start[i]], a.val_f16 + a.row_ptr[r], (size_t)len * sizeof(uint16_t));
         }
     });
-    plan.seg.clear();
-    int64_t n_split_rows = 0;
-    // (1) rows longer than a team's share: one or more wave slices, the wave's teams each
-    //     take a contiguous piece and are summed inside the wave
-    for (int64_t i = 0; i < n_irr; ++i) {
+    plan.irr_wave.clear();
+    plan.irr_row.clear();
+    int64_t n_split_rows = 0, n_slice_waves = 0, n_short_waves = 0, n_zero_waves = 0;
+    // (1) long rows: one or more wave slices; the wave's teams each take a contiguous piece
+    //     and are summed inside the wave
+    for (int64_t i = 0; i < (int64_t)long_rows.size(); ++i) {
         const int64_t len = irr_start[i + 1] - irr_start[i];
-        if (len <= short_max) continue;
         const int64_t n_slices = (len + slice_max - 1) / slice_max;
         if (n_slices > 1) {
             ++n_split_rows;
-            plan.combine.insert(plan.combine.end(), {(uint32_t)part.irregular[i], (uint32_t)slots, (uint32_t)n_slices, 1u});
+            plan.combine.insert(plan.combine.end(), {(uint32_t)long_rows[(size_t)i], (uint32_t)slots, (uint32_t)n_slices, 1u});
         }
-        for (int64_t s = 0; s < n_slices; ++s) {
-            const int64_t sb = len * s / n_slices, se = len * (s + 1) / n_slices;
-            const uint32_t dst = n_slices > 1 ? (uint32_t)(slots + s) : (uint32_t)part.irregular[i];
-            const uint32_t kind = kSegWaveReduce | (n_slices > 1 ? kSegToScratch : 0u);
-            for (int t = 0; t < G; ++t) {
-                const int64_t tb = sb + (se - sb) * t / G, te = sb + (se - sb) * (t + 1) / G;
-                plan.seg.insert(plan.seg.end(), {(uint32_t)(irr_start[i] + tb), (uint32_t)(te - tb), dst, kind});
-            }
+        for (int64_t sl = 0; sl < n_slices; ++sl) {
+            const int64_t sb = len * sl / n_slices, se = len * (sl + 1) / n_slices;
+            const uint32_t dst = n_slices > 1 ? (uint32_t)(slots + sl) : (uint32_t)long_rows[(size_t)i];
+            plan.irr_wave.insert(plan.irr_wave.end(), {(uint32_t)(irr_start[i] + sb), (uint32_t)(se - sb), dst,
+                                                       kWaveSlice | (n_slices > 1 ? kWaveToScratch : 0u)});
+            ++n_slice_waves;
         }
         if (n_slices > 1) slots += n_slices;
     }
-    // (2) short rows: one team each, grouped by length class so the teams of a wave finish together
+    // (2) short rows: a wave takes G * R rows of L entries each, R = TPR / L rows per team
     {
-        auto bucket_of = [](int64_t len) {
-            int b = 0;
-            while ((1ll << b) < len) ++b;   // 1 -> 0, 2 -> 1, 3-4 -> 2, 5-8 -> 3, ...
-            return b;
-        };
-        std::vector<std::vector<int64_t>> buckets(40);
-        for (int64_t i = 0; i < n_irr; ++i) {
-            const int64_t len = irr_start[i + 1] - irr_start[i];
-            if (len <= short_max) buckets[(size_t)bucket_of(len)].push_back(i);
+        int64_t pos = (int64_t)long_rows.size();   // index into stream_rows
+        for (int L = TPR; L >= 1; --L) {
+            const int64_t cnt = (int64_t)by_len[(size_t)L].size();
+            const int R = TPR / L;
+            const int64_t per_wave = (int64_t)G * R;
+            for (int64_t q = 0; q < cnt; q += per_wave) {
+                const uint32_t rows_here = (uint32_t)std::min<int64_t>(per_wave, cnt - q);
+                plan.irr_wave.insert(plan.irr_wave.end(), {irr_start[pos + q], rows_here, (uint32_t)plan.irr_row.size(),
+                                                           kWaveShortRows | ((uint32_t)L << 8) | ((uint32_t)R << 16)});
+                for (uint32_t t = 0; t < rows_here; ++t) plan.irr_row.push_back(by_len[(size_t)L][(size_t)(q + t)]);
+                ++n_short_waves;
+            }
+            pos += cnt;
         }
-        for (int b = 39; b >= 0; --b)
-            for (int64_t i : buckets[(size_t)b])
-                plan.seg.insert(plan.seg.end(), {irr_start[i], (uint32_t)(irr_start[i + 1] - irr_start[i]),
-                                                 (uint32_t)part.irregular[i], 0u});
     }
-    // (3) rows without stored entries: zero-length segments make the kernel write zeros
-    for (int32_t r : part.empty) plan.seg.insert(plan.seg.end(), {0u, 0u, (uint32_t)r, 0u});
-    while ((plan.seg.size() / 4) % (size_t)G) plan.seg.insert(plan.seg.end(), {0u, 0u, kNoDst, 0u});
+    // (3) rows without stored entries are zero-filled, 4 per team
+    for (int64_t q = 0; q < (int64_t)part.empty.size(); q += 4 * G) {
+        const uint32_t rows_here = (uint32_t)std::min<int64_t>(4 * G, (int64_t)part.empty.size() - q);
+        plan.irr_wave.insert(plan.irr_wave.end(), {0u, rows_here, (uint32_t)plan.irr_row.size(), kWaveZeroRows});
+        for (uint32_t t = 0; t < rows_here; ++t) plan.irr_row.push_back(part.empty[(size_t)(q + t)]);
+        ++n_zero_waves;
+    }
+    plan.irr_row.resize(plan.irr_row.size() + 64, 0);   // tail pad for lane-wise reads
+    {
+        // cost in units of one gathered B row: entries + two per stored row of C + a fixed share
+        std::vector<uint32_t> cost(plan.irr_wave.size() / 4);
+        for (size_t i = 0; i < cost.size(); ++i) {
+            const uint32_t count = plan.irr_wave[4 * i + 1], info = plan.irr_wave[4 * i + 3];
+            const uint32_t kind = info & kWaveKindMask;
+            cost[i] = 32u + (kind == kWaveSlice ? count : kind == kWaveShortRows ? count * (((info >> 8) & 0xffu) + 2u) : count * 2u);
+        }
+        plan.irr_split = split_by_cost(cost);
+    }
 
     plan.n_scratch_slots = slots;
 
@@ -447,8 +492,10 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     st.n_empty_rows = (int64_t)part.empty.size();
     st.n_tile_items = (int64_t)plan.tile_item.size() / 4;
     st.n_split_windows = n_split_windows;
-    st.n_segments = (int64_t)plan.seg.size() / 4;
-    st.n_irregular_waves = st.n_segments / G;
+    st.n_irregular_waves = (int64_t)plan.irr_wave.size() / 4;
+    st.n_slice_waves = n_slice_waves;
+    st.n_short_row_waves = n_short_waves;
+    st.n_zero_waves = n_zero_waves;
     st.n_split_rows = n_split_rows;
     st.n_combine = (int64_t)plan.combine.size() / 4;
     (void)n_tile_combine;
@@ -457,11 +504,12 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     st.plan_bytes = (int64_t)(plan.win_row.size() * 4 + plan.win_tile_off.size() * 4 + plan.tile_colid.size() * 4 +
                               plan.tile_mask.size() * 8 + plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 +
                               plan.tile_item.size() * 4 + plan.irr_col.size() * 4 + plan.irr_val.size() * 2 +
-                              plan.seg.size() * 4 + plan.combine.size() * 4);
+                              plan.irr_wave.size() * 4 + plan.irr_row.size() * 4 + plan.combine.size() * 4);
     st.csr_bytes = 6 * a.nnz + 8 * (a.n_rows + 1);
     st.tile_part_bytes = (int64_t)(plan.win_row.size() * 4 + plan.tile_colid.size() * 4 + plan.tile_mask.size() * 8 +
                                    plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 + plan.tile_item.size() * 4);
-    st.irregular_part_bytes = (int64_t)(plan.irr_col.size() * 4 + plan.irr_val.size() * 2 + plan.seg.size() * 4);
+    st.irregular_part_bytes = (int64_t)(plan.irr_col.size() * 4 + plan.irr_val.size() * 2 + plan.irr_wave.size() * 4 +
+                                        plan.irr_row.size() * 4);
     {
         // distinct columns referenced by each part (the B rows each kernel must fetch at least once)
         std::vector<uint8_t> seen((size_t)a.n_cols, 0);
@@ -517,13 +565,19 @@ int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t*
     std::vector<int32_t> slot_row((size_t)p.n_scratch_slots, -1);
     for (size_t c = 0; c + 3 < p.combine.size(); c += 4)
         for (uint32_t q = 0; q < p.combine[c + 2]; ++q) slot_row[p.combine[c + 1] + (size_t)q * p.combine[c + 3]] = (int32_t)p.combine[c];
-    for (size_t s = 0; s + 3 < p.seg.size(); s += 4) {
-        const uint32_t start = p.seg[s], len = p.seg[s + 1], dst = p.seg[s + 2], kind = p.seg[s + 3];
-        if (len == 0) continue;
-        if (dst == kNoDst) return RSH_ERR_INVALID_CSR;
-        const int32_t row = (kind & kSegToScratch) ? slot_row[dst] : (int32_t)dst;
-        if (row < 0) return RSH_ERR_INVALID_CSR;
-        for (uint32_t q = 0; q < len; ++q) ent.push_back({row, p.irr_col[start + q], p.irr_val[start + q], 1});
+    for (size_t s = 0; s + 3 < p.irr_wave.size(); s += 4) {
+        const uint32_t start = p.irr_wave[s], count = p.irr_wave[s + 1], dst = p.irr_wave[s + 2], info = p.irr_wave[s + 3];
+        const uint32_t kind = info & kWaveKindMask;
+        if (kind == kWaveShortRows) {
+            const uint32_t L = (info >> 8) & 0xffu;
+            for (uint32_t q = 0; q < count; ++q)
+                for (uint32_t j = 0; j < L; ++j)
+                    ent.push_back({p.irr_row[dst + q], p.irr_col[start + q * L + j], p.irr_val[start + q * L + j], 1});
+        } else if (kind == kWaveSlice) {
+            const int32_t row = (info & kWaveToScratch) ? slot_row[dst] : (int32_t)dst;
+            if (row < 0) return RSH_ERR_INVALID_CSR;
+            for (uint32_t q = 0; q < count; ++q) ent.push_back({row, p.irr_col[start + q], p.irr_val[start + q], 1});
+        }
     }
     if ((int64_t)ent.size() != p.nnz) return RSH_ERR_INVALID_CSR;
     std::sort(ent.begin(), ent.end(), [](const Ent& x, const Ent& y) { return x.row != y.row ? x.row < y.row : x.col < y.col; });

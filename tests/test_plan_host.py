@@ -29,7 +29,7 @@ def host_plan(A, N, **kw):
 
 def arrays_of(p):
     names = ["WIN_ROW", "WIN_TILE_OFF", "TILE_COLID", "TILE_MASK", "TILE_VAL_OFF", "TILE_VAL", "TILE_ITEM",
-             "IRR_COL", "IRR_VAL", "SEG", "COMBINE"]
+             "IRR_COL", "IRR_VAL", "IRR_WAVE", "IRR_ROW", "COMBINE"]
     return {n: p.array(getattr(B_, "RSH_ARR_" + n)) for n in names}
 
 
@@ -75,7 +75,7 @@ def test_independent_reader_rebuilds_A_from_raw_arrays(k, mode):
     st = p.stats()
     rows, cols, vals, paths = rstile.entries_from_arrays(
         a["WIN_ROW"], a["WIN_TILE_OFF"], a["TILE_COLID"], a["TILE_MASK"], a["TILE_VAL_OFF"], a["TILE_VAL"],
-        a["IRR_COL"], a["IRR_VAL"], a["SEG"], a["COMBINE"], st["n_scratch_slots"])
+        a["IRR_COL"], a["IRR_VAL"], a["IRR_WAVE"], a["IRR_ROW"], a["COMBINE"], st["n_scratch_slots"])
     assert rows.size == A.nnz           # every stored entry once ...
     row_ptr, col_idx, val, _ = rstile.csr_from_entries(rows, cols, vals, paths, A.n_rows, A.n_cols)  # ... and only once
     assert np.array_equal(row_ptr, A.row_ptr)
@@ -93,12 +93,15 @@ def test_plan_structure_invariants(k, mode):
     win_row = a["WIN_ROW"].reshape(n_win, 16)
     # rows: windows + irregular + empty partition the row set
     in_win = win_row[win_row >= 0]
-    seg = a["SEG"].reshape(-1, 4)
+    waves = a["IRR_WAVE"].reshape(-1, 4)
+    irr_row = a["IRR_ROW"]
     comb = a["COMBINE"].reshape(-1, 4)
-    direct = seg[((seg[:, 3] & 1) == 0) & (seg[:, 2] != 0xFFFFFFFF)]
-    seg_rows = np.unique(direct[:, 2]).astype(np.int64)
+    kind = waves[:, 3] & 3
+    listed = [irr_row[int(w[2]):int(w[2]) + int(w[1])] for w in waves[(kind == 0) | (kind == 2)]]
+    listed = np.concatenate(listed).astype(np.int64) if listed else np.zeros(0, np.int64)
+    direct_slices = waves[(kind == 1) & ((waves[:, 3] & 4) == 0)][:, 2].astype(np.int64)
     irr_comb_rows = comb[comb[:, 3] == 1][:, 0].astype(np.int64)
-    covered = np.concatenate([in_win.astype(np.int64), seg_rows, irr_comb_rows])
+    covered = np.concatenate([in_win.astype(np.int64), listed, direct_slices, irr_comb_rows])
     assert np.array_equal(np.sort(covered), np.arange(A.n_rows)), "every row is written by exactly one path"
     # fragments: offsets, bitmap popcounts, padding
     off = a["WIN_TILE_OFF"]
@@ -141,27 +144,33 @@ def test_plan_structure_invariants(k, mode):
         assert lst[0][0] == off[w] and lst[-1][1] == off[w + 1]
         assert all(lst[i][1] == lst[i + 1][0] for i in range(len(lst) - 1))
         assert (len(lst) == 1) == (lst[0][2] == 0xFFFFFFFF)
-    # irregular segments tile the irregular stream exactly once
+    # irregular waves tile the irregular stream exactly once
     G = p.teams_per_wave()
-    assert seg.shape[0] % G == 0
-    nz = seg[seg[:, 1] > 0]
-    order = np.argsort(nz[:, 0], kind="stable")
-    starts, lens = nz[order, 0].astype(np.int64), nz[order, 1].astype(np.int64)
-    assert starts.size == 0 or (starts[0] == 0 and np.all(starts[1:] == (starts + lens)[:-1]) and
-                                starts[-1] + lens[-1] == st["nnz_irregular"])
-    # wave-reduce waves hold G pieces of one destination
-    waves = seg.reshape(-1, G, 4)
-    red = (waves[:, :, 3] & 2) != 0
-    assert np.all(red.all(axis=1) | (~red).all(axis=1))
-    rw = waves[red.all(axis=1)]
-    assert np.all(rw[:, :, 2] == rw[:, :1, 2]) and np.all(rw[:, :, 3] == rw[:, :1, 3])
+    T = 64 // G
+    spans = []
+    for start, count, dst, info in waves:
+        k = int(info) & 3
+        if k == 0:
+            L, R = (int(info) >> 8) & 255, (int(info) >> 16) & 255
+            assert 1 <= L <= T and R == T // L and 1 <= count <= G * R
+            spans.append((int(start), int(count) * L))
+        elif k == 1:
+            assert count >= 1
+            spans.append((int(start), int(count)))
+        else:
+            assert k == 2 and 1 <= count <= 4 * G
+    spans.sort()
+    pos = 0
+    for sbeg, slen in spans:
+        assert sbeg == pos
+        pos += slen
+    assert pos == st["nnz_irregular"]
     # scratch slots: every slot is produced once and consumed once
     produced = []
     for w, b, e, dst in items:
         if dst != 0xFFFFFFFF:
             produced.extend(range(int(dst), int(dst) + 16))
-    slot_waves = waves[red.all(axis=1) & ((waves[:, 0, 3] & 1) != 0)]
-    produced.extend(int(x) for x in slot_waves[:, 0, 2])
+    produced.extend(int(x) for x in waves[(kind == 1) & ((waves[:, 3] & 4) != 0)][:, 2])
     consumed = []
     for row, first, parts, stride in comb:
         consumed.extend(int(first) + q * int(stride) for q in range(int(parts)))
@@ -188,12 +197,15 @@ def test_alg1_literal_matches_the_python_oracle(k):
         for s, rows in zip(wins, win_row):
             want = [r if r < A.n_rows else -1 for r in range(s, s + 16)]
             assert rows.tolist() == want
-        seg = p.array(B_.RSH_ARR_SEG).reshape(-1, 4)
+        waves = p.array(B_.RSH_ARR_IRR_WAVE).reshape(-1, 4)
+        irr_row = p.array(B_.RSH_ARR_IRR_ROW)
         comb = p.array(B_.RSH_ARR_COMBINE).reshape(-1, 4)
-        nonempty = seg[seg[:, 1] > 0]
-        direct = nonempty[(nonempty[:, 3] & 1) == 0][:, 2]
-        got_res = sorted(set(int(x) for x in direct) | set(int(x) for x in comb[comb[:, 3] == 1][:, 0]))
-        assert got_res == res
+        kind = waves[:, 3] & 3
+        got = set(int(x) for x in waves[(kind == 1) & ((waves[:, 3] & 4) == 0)][:, 2])
+        got |= set(int(x) for x in comb[comb[:, 3] == 1][:, 0])
+        for w in waves[kind == 0]:
+            got |= set(int(x) for x in irr_row[int(w[2]):int(w[2]) + int(w[1])])
+        assert sorted(got) == res
 
 
 def test_row_order_is_identity_without_reordering():
@@ -268,10 +280,8 @@ def test_long_rows_are_split_into_bounded_slices_and_windows_into_bounded_items(
     p = host_plan(A, 128, max_nnz_per_slice=256)
     st = p.stats()
     assert st["n_split_rows"] == 1 and st["n_scratch_slots"] == 10 and st["n_combine"] == 1
-    seg = p.array(B_.RSH_ARR_SEG).reshape(-1, 4)
-    G = p.teams_per_wave()
-    waves = seg.reshape(-1, G, 4)
-    assert waves[:, :, 1].sum(axis=1).max() <= 256
+    waves = p.array(B_.RSH_ARR_IRR_WAVE).reshape(-1, 4)
+    assert waves[(waves[:, 3] & 3) == 1][:, 1].max() <= 256
     p2 = host_plan(A, 128, force_path=2, max_tiles_per_item=8)
     items = p2.array(B_.RSH_ARR_TILE_ITEM).reshape(-1, 4)
     assert (items[:, 2] - items[:, 1]).max() <= 8 and p2.stats()["n_split_windows"] == 1
