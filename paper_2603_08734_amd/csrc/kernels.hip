@@ -16,6 +16,9 @@ namespace rsh {
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kWavesPerBlock = 4;
 
@@ -185,16 +188,35 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
 // ---------------------------------------------------------------------------
 // Dense fragments.  One wave per work item (a window or a bounded run of its
 // fragments).  Per fragment the wave gathers the 16 B rows named by the fragment's
-// column ids with coalesced 16-byte loads, stages them in LDS, expands the bitmap-
+// column ids with coalesced 16-byte loads and stages them in LDS, expands the bitmap-
 // compressed 16x16 piece of A into an MFMA operand with popcount prefixes, and issues
-// one v_mfma_f32_16x16x16_f16 per 16-feature chunk.  The product is formed transposed
-// (features along M, window rows along N) so that a lane ends up owning 4*NCH
-// consecutive features of one output row and stores them as 16-byte vectors.
+// one v_mfma_f32_16x16x16_f16 per 16-feature chunk.  The loop is software-pipelined:
+// while fragment t is decoded and multiplied out of LDS, the global loads of fragment
+// t+1 are in flight into registers and the metadata of fragment t+2 is being fetched.
+//
+// The product is formed transposed (features along M, window rows along N), so a lane
+// ends up with four consecutive features of one output row per chunk (16-byte stores).
 //
 // MFMA 16x16x16 f16 operand layout (lane l, i = 0..3):
 //   A[m = l%16][k = 4*(l/16)+i]   B[k = 4*(l/16)+i][n = l%16]   D[m = 4*(l/16)+i][n = l%16]
-// Chunk c maps M index m to feature (m/4)*(4*NCH) + 4c + m%4.
+// Chunk c maps M index m to feature 16c + m.
+//
+// The A operand (B rows, K-major in registers) comes out of LDS, where B rows lie
+// feature-major, through the transposing read ds_read_b64_tr_b16: inside a group of 16
+// lanes, lane 4r+s supplies the address of 4 consecutive halves and lane 4s+e receives
+// element e of the runs supplied by lanes s, 4+s, 8+s, 12+s.  Lane 4r+s therefore points
+// at features 16c+4s.. of staged row 4*(l/16)+r.  The LDS row stride is chosen so that
+// the 16 addresses of a group fall in distinct banks.
 // ---------------------------------------------------------------------------
+template <int NCH>
+struct TileGeom {
+    static constexpr int P = 16 * NCH;                      // features per panel
+    static constexpr int TPR = P / 8;                       // lanes per B row (16 bytes each)
+    static constexpr int ROWS_PER_LOAD = (64 / TPR) > 16 ? 16 : (64 / TPR);
+    static constexpr int NLD = 16 / ROWS_PER_LOAD;          // load instructions per fragment
+    static constexpr int LDB = P == 16 ? 16 : (P == 32 ? 80 : P + 16);   // LDS row stride, halves
+};
+
 template <int NCH>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
     const uint4* __restrict__ items, XcdSplit xs,
@@ -202,12 +224,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
     const uint64_t* __restrict__ tile_mask, const uint32_t* __restrict__ tile_val_off,
     const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, float* __restrict__ C,
     float* __restrict__ scratch, int N) {
-    constexpr int P = 16 * NCH;            // features per panel
-    constexpr int TPR = P / 8;             // lanes per B row (16 bytes each)
-    constexpr int RPI = TPR >= 64 ? 1 : 64 / TPR;   // B rows per load instruction
-    constexpr int ROWS_PER_LOAD = RPI > 16 ? 16 : RPI;
-    constexpr int NLD = 16 / ROWS_PER_LOAD;
-    constexpr int LDB = P + 8;             // LDS row stride in halves (16-byte aligned, skews banks)
+    using Gm = TileGeom<NCH>;
+    constexpr int P = Gm::P, TPR = Gm::TPR, ROWS_PER_LOAD = Gm::ROWS_PER_LOAD, NLD = Gm::NLD, LDB = Gm::LDB;
     __shared__ __attribute__((aligned(16))) _Float16 lds_b[kWavesPerBlock][16 * LDB];
     __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWavesPerBlock][256 + 8];
 
@@ -224,62 +242,91 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
 
     const int ld_row = lane / TPR;          // row handled inside one load instruction
     const int ld_col = (lane % TPR) * 8;    // feature offset inside the panel
-    const bool ld_active = ld_row < 16;     // only false when TPR < 4
+    const bool ld_active = TPR >= 4 || ld_row < 16;   // a B row narrower than 4 lanes leaves lanes idle
     const int m = lane & 15, kg = lane >> 4;
+    const __half* Bp = B + panel + ld_col;
+    // address of this lane's run for the transposing read (chunk 0)
+    const _Float16* tr_ptr = sb + (4 * kg + (m >> 2)) * LDB + 4 * (m & 3);
 
     float4_t acc[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) acc[c] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    for (uint32_t t = t_begin; t < t_end; ++t) {
-        const int my_colid = tile_colid[(size_t)t * 16 + m];
-        uint4 breg[NLD];
+    if (t_begin < t_end) {
+        const uint32_t t_last = t_end - 1;
+        // fragment metadata, fetched two fragments ahead
+        int colid_a = tile_colid[(size_t)t_begin * 16 + m];
+        int colid_b = tile_colid[(size_t)min(t_begin + 1, t_last) * 16 + m];
+        uint32_t voff_a = tile_val_off[t_begin], vend_a = tile_val_off[t_begin + 1];
+        uint32_t voff_b = tile_val_off[min(t_begin + 1, t_last)], vend_b = tile_val_off[min(t_begin + 1, t_last) + 1];
+        // staged registers of the next fragment
+        uint4_t breg[NLD];
+        uint2_t vreg = {0u, 0u};
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) breg[j] = (uint4_t){0u, 0u, 0u, 0u};
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            const int k = j * ROWS_PER_LOAD + ld_row;
-            const int c = shfl_i32(my_colid, k & 15);
-            if (ld_active) breg[j] = *reinterpret_cast<const uint4*>(B + (size_t)c * N + panel + ld_col);
+            const int c = shfl_i32(colid_a, (j * ROWS_PER_LOAD + ld_row) & 15);
+            if (ld_active) breg[j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N);
         }
-        const uint32_t voff = tile_val_off[t];
-        const uint32_t vcnt = tile_val_off[t + 1] - voff;
-        uint2 vreg = make_uint2(0u, 0u);
-        if ((uint32_t)lane * 4u < vcnt) vreg = *reinterpret_cast<const uint2*>(tile_val + voff + lane * 4);
-        const uint64_t m0 = tile_mask[(size_t)t * 4 + 0], m1 = tile_mask[(size_t)t * 4 + 1];
-        const uint64_t m2 = tile_mask[(size_t)t * 4 + 2], m3 = tile_mask[(size_t)t * 4 + 3];
+        if ((uint32_t)lane * 4u < vend_a - voff_a) vreg = *reinterpret_cast<const uint2_t*>(tile_val + voff_a + lane * 4);
 
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int j = 0; j < NLD; ++j) {
-            const int k = j * ROWS_PER_LOAD + ld_row;
-            if (ld_active) *reinterpret_cast<uint4*>(sb + k * LDB + ld_col) = breg[j];
-        }
-        *reinterpret_cast<uint2*>(sv + lane * 4) = vreg;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        for (uint32_t t = t_begin; t < t_end; ++t) {
+            // bitmaps of this fragment (wave-uniform)
+            const uint64_t m0 = tile_mask[(size_t)t * 4 + 0], m1 = tile_mask[(size_t)t * 4 + 1];
+            const uint64_t m2 = tile_mask[(size_t)t * 4 + 2], m3 = tile_mask[(size_t)t * 4 + 3];
+            // metadata two fragments ahead
+            const uint32_t t2 = min(t + 2, t_last);
+            const int colid_c = tile_colid[(size_t)t2 * 16 + m];
+            const uint32_t voff_c = tile_val_off[t2], vend_c = tile_val_off[t2 + 1];
 
-        // expand this lane's four cells (window row m, fragment columns 4kg..4kg+3)
-        const uint32_t bit0 = (uint32_t)(m0 >> lane) & 1u, bit1 = (uint32_t)(m1 >> lane) & 1u;
-        const uint32_t bit2 = (uint32_t)(m2 >> lane) & 1u, bit3 = (uint32_t)(m3 >> lane) & 1u;
-        const uint32_t i0 = bits_below_lane(m0) + bits_below_lane(m1) + bits_below_lane(m2) + bits_below_lane(m3);
-        const uint32_t i1 = i0 + bit0, i2 = i1 + bit1, i3 = i2 + bit2;
-        half4_t a_frag;
-        a_frag[0] = bit0 ? __builtin_bit_cast(_Float16, sv[i0]) : (_Float16)0;
-        a_frag[1] = bit1 ? __builtin_bit_cast(_Float16, sv[i1]) : (_Float16)0;
-        a_frag[2] = bit2 ? __builtin_bit_cast(_Float16, sv[i2]) : (_Float16)0;
-        a_frag[3] = bit3 ? __builtin_bit_cast(_Float16, sv[i3]) : (_Float16)0;
+            // staged registers -> LDS (LDS operations of one wave complete in order, so the
+            // reads of the previous fragment are already done)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < NLD; ++j)
+                if (ld_active) *reinterpret_cast<uint4_t*>(sb + (j * ROWS_PER_LOAD + ld_row) * LDB + ld_col) = breg[j];
+            *reinterpret_cast<uint2_t*>(sv + lane * 4) = vreg;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
 
-        const _Float16* brow = sb + (4 * kg) * LDB + (m >> 2) * (4 * NCH) + (m & 3);
+            // global loads of the next fragment go out before this one is multiplied
+            if (t + 1 < t_end) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            half4_t b_frag;
+                for (int j = 0; j < NLD; ++j) {
+                    const int c = shfl_i32(colid_b, (j * ROWS_PER_LOAD + ld_row) & 15);
+                    if (ld_active) breg[j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N);
+                }
+                vreg = (uint2_t){0u, 0u};
+                if ((uint32_t)lane * 4u < vend_b - voff_b) vreg = *reinterpret_cast<const uint2_t*>(tile_val + voff_b + lane * 4);
+            }
+
+            // expand this lane's four cells (window row m, fragment columns 4kg..4kg+3)
+            const uint32_t bit0 = (uint32_t)(m0 >> lane) & 1u, bit1 = (uint32_t)(m1 >> lane) & 1u;
+            const uint32_t bit2 = (uint32_t)(m2 >> lane) & 1u, bit3 = (uint32_t)(m3 >> lane) & 1u;
+            const uint32_t i0 = bits_below_lane(m0) + bits_below_lane(m1) + bits_below_lane(m2) + bits_below_lane(m3);
+            const uint32_t i1 = i0 + bit0, i2 = i1 + bit1, i3 = i2 + bit2;
+            half4_t a_frag;
+            a_frag[0] = bit0 ? __builtin_bit_cast(_Float16, sv[i0]) : (_Float16)0;
+            a_frag[1] = bit1 ? __builtin_bit_cast(_Float16, sv[i1]) : (_Float16)0;
+            a_frag[2] = bit2 ? __builtin_bit_cast(_Float16, sv[i2]) : (_Float16)0;
+            a_frag[3] = bit3 ? __builtin_bit_cast(_Float16, sv[i3]) : (_Float16)0;
+
 #pragma unroll
-            for (int i = 0; i < 4; ++i) b_frag[i] = brow[i * LDB + 4 * c];
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
+            for (int c = 0; c < NCH; ++c) {
+                const half4_t b_frag = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (short4_t __attribute__((address_space(3)))*)(tr_ptr + 16 * c)));
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
+            }
+
+            colid_a = colid_b; colid_b = colid_c;
+            voff_a = voff_b; vend_a = vend_b;
+            voff_b = voff_c; vend_b = vend_c;
         }
     }
 
-    // lane (q = lane/16, r = lane%16) owns features [q*4*NCH, (q+1)*4*NCH) of window row r
+    // lane (q = lane/16, r = lane%16) owns features 16c + 4q .. 16c + 4q + 3 of window row r
     const int r = lane & 15, q = lane >> 4;
     float* out;
     if (dst == kNoDst) {
@@ -289,9 +336,9 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
     } else {
         out = scratch + ((size_t)dst + r) * N;
     }
-    out += panel + q * (4 * NCH);
+    out += panel + 4 * q;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(out + 4 * c) = acc[c];
+    for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(out + 16 * c) = acc[c];
 }
 
 // ---------------------------------------------------------------------------
