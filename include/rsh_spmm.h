@@ -60,7 +60,8 @@ typedef struct {
                              1 = cost-guided (default): short low-overlap rows and long rows leave
                                  first, the rest is grouped W eligible rows at a time, and a window
                                  whose column reuse nnz/|U| is below min_reuse is dissolved        */
-    int32_t reorder;      /* 0 = keep the given row order, 1 = locality-aware reordering (Section 3.4) */
+    int32_t reorder;      /* 0 = keep the given row order, 1 (default) = locality-aware reordering
+                             (Section 3.4); the found order is used only if it lowers the objective */
     int32_t knn_k;        /* neighbours kept per row in the kNN graph (Algorithm 3, step II)     */
     float alpha;          /* exponent of the column weight w_j = d_j^-alpha (Section 3.4)        */
     int32_t max_tiles_per_item; /* bound on fragments per tile work item; 0 = auto              */
@@ -90,6 +91,8 @@ typedef struct {
     int64_t cols_all, cols_tile, cols_irregular;   /* distinct columns referenced overall / per part */
     int64_t rows_tile, rows_irregular;         /* rows of C each kernel writes directly or via scratch */
     int32_t tau_nnz, tau_inc;                  /* thresholds actually used                       */
+    double reorder_cost_given, reorder_cost_found; /* Section 3.4 objective of the given order and of the
+                                                  order the heuristic found (the lower one is used) */
     double ms_validate, ms_reorder, ms_partition, ms_pack, ms_worklist, ms_upload, ms_total;
 } rsh_plan_stats_t;
 

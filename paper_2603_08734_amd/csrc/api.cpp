@@ -90,7 +90,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->tau_nnz = -1;
     o->tau_inc = -1;
     o->partition = 1;
-    o->reorder = 0;
+    o->reorder = 1;
     o->knn_k = 8;
     o->alpha = 0.5f;
     o->max_tiles_per_item = 0;
@@ -139,7 +139,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
 
         t0 = std::chrono::steady_clock::now();
         if (o.reorder) {
-            rc = rsh::reorder_rows(*csr, o, col_deg, h.order, threads);
+            rc = rsh::reorder_rows(*csr, o, col_deg, h.order, threads, &h.stats.reorder_cost_given, &h.stats.reorder_cost_found);
             if (rc) throw rc;
         } else {
             h.order.resize((size_t)csr->n_rows);

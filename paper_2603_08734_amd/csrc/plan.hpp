@@ -74,7 +74,7 @@ int validate_csr(const rsh_csr_t& a);
 void column_degrees(const rsh_csr_t& a, std::vector<int32_t>& deg, int threads);
 void estimate_threshold(int64_t n_rows, int64_t nnz, int32_t* tau_nnz, int32_t* tau_inc);
 int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& col_deg,
-                 std::vector<int32_t>& order, int threads);
+                 std::vector<int32_t>& order, int threads, double* cost_given, double* cost_found);
 void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
                     int32_t tau_nnz, int32_t tau_inc, Partition& out, int threads);
 int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads);

@@ -87,8 +87,9 @@ struct Dsu {
 }  // namespace
 
 int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& col_deg,
-                 std::vector<int32_t>& order, int threads) {
+                 std::vector<int32_t>& order, int threads, double* cost_given, double* cost_found) {
     const int64_t n = a.n_rows;
+    *cost_given = *cost_found = 0.0;
     const int K = o.knn_k;
     order.resize((size_t)n);
     std::iota(order.begin(), order.end(), 0);
@@ -337,7 +338,26 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     }
     order.insert(order.end(), tail_rows.begin(), tail_rows.end());
     order.insert(order.end(), empties.begin(), empties.end());
-    return (int64_t)order.size() == n ? RSH_OK : RSH_ERR_INVALID_CSR;
+    if ((int64_t)order.size() != n) return RSH_ERR_INVALID_CSR;
+
+    // The objective of Section 3.4: sum of (1 - sim) over consecutive rows.  The heuristic is
+    // meant to lower it; when the given order already scores at least as well it is kept.
+    auto path_cost = [&](const std::vector<int32_t>* ord) {
+        std::vector<double> part((size_t)std::max(1, threads), 0.0);
+        parallel_chunks(n - 1, threads, [&](int64_t b, int64_t e, int t) {
+            double s = 0.0;
+            for (int64_t i = b; i < e; ++i)
+                s += 1.0 - (ord ? sim((*ord)[(size_t)i], (*ord)[(size_t)i + 1]) : sim((int32_t)i, (int32_t)i + 1));
+            part[(size_t)t] = s;
+        });
+        double s = 0.0;
+        for (double x : part) s += x;
+        return s;
+    };
+    *cost_given = path_cost(nullptr);
+    *cost_found = path_cost(&order);
+    if (*cost_given <= *cost_found) std::iota(order.begin(), order.end(), 0);
+    return RSH_OK;
 }
 
 }  // namespace rsh

@@ -49,6 +49,7 @@ def assert_parity(C_gpu, C_ref, S, what=""):
 
 OPTION_SETS = {
     "hybrid": dict(),
+    "no_reorder": dict(reorder=0),
     "all_irregular": dict(force_path=1),
     "all_tile": dict(force_path=2),
     "alg1_literal": dict(partition=0),
@@ -109,7 +110,7 @@ def edge_matrices():
     return out
 
 
-@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "alg1_literal", "tiny_items", "tiny_slices"])
+@pytest.mark.parametrize("mode", ["hybrid", "no_reorder", "all_irregular", "all_tile", "alg1_literal", "tiny_items", "tiny_slices"])
 @pytest.mark.parametrize("name", list(edge_matrices()))
 def test_edge_cases(name, mode):
     A = edge_matrices()[name]
@@ -139,3 +140,35 @@ def test_row_permutation_metamorphic():
     C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
     assert_parity(Cp[inv], C_ref, S, "permuted rows")
     assert_parity(C, C_ref, S, "original rows")
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_full_size_configs_on_sampled_rows(k):
+    """The five named workloads at full size, in the plan configuration the benchmark times;
+    the oracle recomputes a sample of output rows (random rows, the longest rows, the first
+    and last rows) one by one."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, N, dist = make_config(k)
+    B = dense_B(A.n_cols, N, dist, seed=1)
+    print(f"case full config={k} rows={A.n_rows} nnz={A.nnz} N={N}", flush=True)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N)
+    Bd = torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16)
+    C = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+    plan.spmm(Bd, C)
+    torch.cuda.synchronize()
+    C1 = C.clone()
+    plan.spmm(Bd, C)
+    torch.cuda.synchronize()
+    assert torch.equal(C1.view(torch.int32), C.view(torch.int32)), "two runs differ bitwise"
+    assert not torch.isnan(C).any()
+    rng = np.random.default_rng(k)
+    rn = A.row_nnz()
+    rows = np.unique(np.concatenate([rng.integers(0, A.n_rows, 4096), np.argsort(rn)[-64:], np.argsort(rn)[:64],
+                                     np.arange(32), np.arange(A.n_rows - 32, A.n_rows)])).astype(np.int64)
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B, rows=rows)
+    C_s = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ratio = assert_parity(C_s, C_ref, S, f"full config {k}")
+    st = plan.stats()
+    print(f"  max err/S = {ratio:.2e} nnz_tile={st['nnz_tile']} nnz_irregular={st['nnz_irregular']}", flush=True)
+    plan.destroy()

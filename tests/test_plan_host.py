@@ -187,7 +187,7 @@ def test_plan_structure_invariants(k, mode):
 def test_alg1_literal_matches_the_python_oracle(k):
     A, N, _ = make_config(k, small=True)
     for tau_nnz, tau_inc in [(-1, -1), (0, 2), (3, 1), (6, 4)]:
-        p = host_plan(A, N, partition=0, tau_nnz=tau_nnz, tau_inc=tau_inc)
+        p = host_plan(A, N, partition=0, reorder=0, tau_nnz=tau_nnz, tau_inc=tau_inc)
         st = p.stats()
         if tau_nnz < 0:
             assert (st["tau_nnz"], st["tau_inc"]) == opart.estimate_threshold(A.n_rows, A.nnz)
@@ -210,7 +210,7 @@ def test_alg1_literal_matches_the_python_oracle(k):
 
 def test_row_order_is_identity_without_reordering():
     A, N, _ = make_config(2, small=True)
-    p = host_plan(A, N)
+    p = host_plan(A, N, reorder=0)
     assert np.array_equal(p.row_order(), np.arange(A.n_rows))
 
 
