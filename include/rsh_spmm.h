@@ -70,6 +70,9 @@ typedef struct {
                              row in a window (tests compare the three)                          */
     float min_reuse;      /* partition == 1: dissolve windows with nnz/|U| below this           */
     int32_t long_row_nnz; /* partition == 1: rows longer than this go to the irregular path; 0 = auto */
+    int32_t xcd_partition_nnz; /* irregular rows with at least this many entries are cut by column group,
+                             one group per XCD, so that each XCD gathers one eighth of B's columns for
+                             them; 0 = auto (512), negative = off                                 */
     int32_t upload;       /* 1 = copy the plan to the current HIP device; 0 = host-only plan    */
     int32_t threads;      /* host threads used for planning; 0 = all available                  */
 } rsh_plan_opts_t;

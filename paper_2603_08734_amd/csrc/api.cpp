@@ -98,6 +98,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->force_path = 0;
     o->min_reuse = 1.25f;
     o->long_row_nnz = 0;
+    o->xcd_partition_nnz = 0;
     o->upload = 1;
     o->threads = 0;
     return RSH_OK;

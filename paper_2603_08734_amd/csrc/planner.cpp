@@ -409,23 +409,101 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     for (int L = TPR; L >= 1; --L) stream_rows.insert(stream_rows.end(), by_len[(size_t)L].begin(), by_len[(size_t)L].end());
     std::vector<uint32_t> irr_start((size_t)n_irr + 1, 0);
     for (int64_t i = 0; i < n_irr; ++i) irr_start[i + 1] = irr_start[i] + (uint32_t)row_len(a, stream_rows[(size_t)i]);
+
+    // Column groups for very long rows.  Each XCD has a private L2, so a long row is cut by
+    // column group -- one group per XCD, groups balanced by the entries they receive -- and
+    // the piece of group g is scheduled on XCD g.  An XCD then gathers only its eighth of the
+    // columns of B for this part of the work, which shortens the reuse distance of hot B rows
+    // eightfold.  The pieces are partial sums that the combine pass adds up.
+    const int64_t xp_min = plan.opts.xcd_partition_nnz == 0 ? 512 : plan.opts.xcd_partition_nnz;
+    const int64_t n_long = (int64_t)long_rows.size();
+    std::vector<uint8_t> col_group;
+    bool any_partitioned = false;
+    if (xp_min > 0) {
+        std::vector<uint32_t> cnt((size_t)a.n_cols, 0);
+        for (int64_t i = 0; i < n_long; ++i) {
+            const int32_t r = long_rows[(size_t)i];
+            if (row_len(a, r) < xp_min) continue;
+            any_partitioned = true;
+            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) ++cnt[(size_t)a.col_idx[p]];
+        }
+        if (any_partitioned) {
+            std::vector<int32_t> used;
+            for (int64_t c = 0; c < a.n_cols; ++c)
+                if (cnt[(size_t)c]) used.push_back((int32_t)c);
+            std::sort(used.begin(), used.end(), [&](int32_t x, int32_t y) {
+                return cnt[(size_t)x] != cnt[(size_t)y] ? cnt[(size_t)x] > cnt[(size_t)y] : x < y;
+            });
+            col_group.assign((size_t)a.n_cols, 0);
+            uint64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int32_t c : used) {   // heaviest column first, always into the lightest group
+                int g = 0;
+                for (int q = 1; q < 8; ++q)
+                    if (load[q] < load[g]) g = q;
+                col_group[(size_t)c] = (uint8_t)g;
+                load[g] += cnt[(size_t)c];
+            }
+        }
+    }
+    auto is_partitioned = [&](int64_t i) { return any_partitioned && i < n_long && (int64_t)(irr_start[i + 1] - irr_start[i]) >= xp_min; };
+    std::vector<uint32_t> group_off;   // 9 offsets per long row (only filled for partitioned rows)
+    if (any_partitioned) group_off.assign((size_t)n_long * 9, 0);
+
     plan.irr_col.assign((size_t)nnz_irr + 64, 0);   // tail pad keeps lane-wise reads in bounds
     plan.irr_val.assign((size_t)nnz_irr + 64, 0);
     parallel_chunks(n_irr, threads, [&](int64_t b, int64_t e, int) {
         for (int64_t i = b; i < e; ++i) {
             const int32_t r = stream_rows[(size_t)i];
             const int64_t len = row_len(a, r);
-            std::memcpy(&plan.irr_col[irr_start[i]], a.col_idx + a.row_ptr[r], (size_t)len * sizeof(int32_t));
-            std::memcpy(&plan.irr_val[irr_start[i]], a.val_f16 + a.row_ptr[r], (size_t)len * sizeof(uint16_t));
+            const int32_t* src_c = a.col_idx + a.row_ptr[r];
+            const uint16_t* src_v = a.val_f16 + a.row_ptr[r];
+            if (!is_partitioned(i)) {
+                std::memcpy(&plan.irr_col[irr_start[i]], src_c, (size_t)len * sizeof(int32_t));
+                std::memcpy(&plan.irr_val[irr_start[i]], src_v, (size_t)len * sizeof(uint16_t));
+                continue;
+            }
+            // stable split of the row's entries by column group (columns stay ascending inside a group)
+            uint32_t* off = &group_off[(size_t)i * 9];
+            uint32_t fill[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int64_t p = 0; p < len; ++p) ++fill[col_group[(size_t)src_c[p]]];
+            off[0] = 0;
+            for (int g = 0; g < 8; ++g) off[g + 1] = off[g] + fill[g];
+            for (int g = 0; g < 8; ++g) fill[g] = off[g];
+            for (int64_t p = 0; p < len; ++p) {
+                const uint32_t at = irr_start[i] + fill[col_group[(size_t)src_c[p]]]++;
+                plan.irr_col[at] = src_c[p];
+                plan.irr_val[at] = src_v[p];
+            }
         }
     });
-    plan.irr_wave.clear();
     plan.irr_row.clear();
+    // waves are collected in nine lists: one per XCD for column-group pieces, one for the rest
+    std::vector<uint32_t> bucket[8], free_waves;
     int64_t n_split_rows = 0, n_slice_waves = 0, n_short_waves = 0, n_zero_waves = 0;
     // (1) long rows: one or more wave slices; the wave's teams each take a contiguous piece
     //     and are summed inside the wave
-    for (int64_t i = 0; i < (int64_t)long_rows.size(); ++i) {
+    for (int64_t i = 0; i < n_long; ++i) {
         const int64_t len = irr_start[i + 1] - irr_start[i];
+        if (is_partitioned(i)) {
+            const uint32_t* off = &group_off[(size_t)i * 9];
+            int64_t total_slices = 0;
+            for (int g = 0; g < 8; ++g) total_slices += ((int64_t)(off[g + 1] - off[g]) + slice_max - 1) / slice_max;
+            ++n_split_rows;
+            plan.combine.insert(plan.combine.end(), {(uint32_t)long_rows[(size_t)i], (uint32_t)slots, (uint32_t)total_slices, 1u});
+            int64_t slot = slots;
+            for (int g = 0; g < 8; ++g) {
+                const int64_t glen = off[g + 1] - off[g];
+                const int64_t n_slices = (glen + slice_max - 1) / slice_max;
+                for (int64_t sl = 0; sl < n_slices; ++sl) {
+                    const int64_t sb = glen * sl / n_slices, se = glen * (sl + 1) / n_slices;
+                    bucket[g].insert(bucket[g].end(), {(uint32_t)(irr_start[i] + off[g] + sb), (uint32_t)(se - sb), (uint32_t)slot++,
+                                                       kWaveSlice | kWaveToScratch});
+                    ++n_slice_waves;
+                }
+            }
+            slots += total_slices;
+            continue;
+        }
         const int64_t n_slices = (len + slice_max - 1) / slice_max;
         if (n_slices > 1) {
             ++n_split_rows;
@@ -434,8 +512,8 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         for (int64_t sl = 0; sl < n_slices; ++sl) {
             const int64_t sb = len * sl / n_slices, se = len * (sl + 1) / n_slices;
             const uint32_t dst = n_slices > 1 ? (uint32_t)(slots + sl) : (uint32_t)long_rows[(size_t)i];
-            plan.irr_wave.insert(plan.irr_wave.end(), {(uint32_t)(irr_start[i] + sb), (uint32_t)(se - sb), dst,
-                                                       kWaveSlice | (n_slices > 1 ? kWaveToScratch : 0u)});
+            free_waves.insert(free_waves.end(), {(uint32_t)(irr_start[i] + sb), (uint32_t)(se - sb), dst,
+                                                 kWaveSlice | (n_slices > 1 ? kWaveToScratch : 0u)});
             ++n_slice_waves;
         }
         if (n_slices > 1) slots += n_slices;
@@ -449,8 +527,8 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
             const int64_t per_wave = (int64_t)G * R;
             for (int64_t q = 0; q < cnt; q += per_wave) {
                 const uint32_t rows_here = (uint32_t)std::min<int64_t>(per_wave, cnt - q);
-                plan.irr_wave.insert(plan.irr_wave.end(), {irr_start[pos + q], rows_here, (uint32_t)plan.irr_row.size(),
-                                                           kWaveShortRows | ((uint32_t)L << 8) | ((uint32_t)R << 16)});
+                free_waves.insert(free_waves.end(), {irr_start[pos + q], rows_here, (uint32_t)plan.irr_row.size(),
+                                                     kWaveShortRows | ((uint32_t)L << 8) | ((uint32_t)R << 16)});
                 for (uint32_t t = 0; t < rows_here; ++t) plan.irr_row.push_back(by_len[(size_t)L][(size_t)(q + t)]);
                 ++n_short_waves;
             }
@@ -460,20 +538,41 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     // (3) rows without stored entries are zero-filled, 4 per team
     for (int64_t q = 0; q < (int64_t)part.empty.size(); q += 4 * G) {
         const uint32_t rows_here = (uint32_t)std::min<int64_t>(4 * G, (int64_t)part.empty.size() - q);
-        plan.irr_wave.insert(plan.irr_wave.end(), {0u, rows_here, (uint32_t)plan.irr_row.size(), kWaveZeroRows});
+        free_waves.insert(free_waves.end(), {0u, rows_here, (uint32_t)plan.irr_row.size(), kWaveZeroRows});
         for (uint32_t t = 0; t < rows_here; ++t) plan.irr_row.push_back(part.empty[(size_t)(q + t)]);
         ++n_zero_waves;
     }
     plan.irr_row.resize(plan.irr_row.size() + 64, 0);   // tail pad for lane-wise reads
     {
-        // cost in units of one gathered B row: entries + two per stored row of C + a fixed share
-        std::vector<uint32_t> cost(plan.irr_wave.size() / 4);
-        for (size_t i = 0; i < cost.size(); ++i) {
-            const uint32_t count = plan.irr_wave[4 * i + 1], info = plan.irr_wave[4 * i + 3];
-            const uint32_t kind = info & kWaveKindMask;
-            cost[i] = 32u + (kind == kWaveSlice ? count : kind == kWaveShortRows ? count * (((info >> 8) & 0xffu) + 2u) : count * 2u);
+        // Assemble the wave list: XCD x runs its column-group pieces, then a contiguous run of
+        // the remaining waves sized so that all eight parts cost about the same.  Cost is in
+        // units of one gathered B row: entries + two per stored row of C + a fixed share.
+        auto wave_cost = [](const uint32_t* w) -> uint64_t {
+            const uint32_t count = w[1], info = w[3], kind = info & kWaveKindMask;
+            return 32u + (kind == kWaveSlice ? count : kind == kWaveShortRows ? count * (((info >> 8) & 0xffu) + 2u) : count * 2u);
+        };
+        uint64_t total = 0, bucket_cost[8];
+        for (int g = 0; g < 8; ++g) {
+            bucket_cost[g] = 0;
+            for (size_t i = 0; i < bucket[g].size(); i += 4) bucket_cost[g] += wave_cost(&bucket[g][i]);
+            total += bucket_cost[g];
         }
-        plan.irr_split = split_by_cost(cost);
+        for (size_t i = 0; i < free_waves.size(); i += 4) total += wave_cost(&free_waves[i]);
+        const uint64_t target = (total + 7) / 8;
+        plan.irr_wave.clear();
+        plan.irr_wave.reserve(free_waves.size() + 4 * (size_t)n_slice_waves);
+        size_t next_free = 0;
+        for (int x = 0; x < 8; ++x) {
+            plan.irr_split.start[x] = (uint32_t)(plan.irr_wave.size() / 4);
+            plan.irr_wave.insert(plan.irr_wave.end(), bucket[x].begin(), bucket[x].end());
+            uint64_t acc = bucket_cost[x];
+            while (next_free < free_waves.size() && (x == 7 || acc < target)) {
+                acc += wave_cost(&free_waves[next_free]);
+                plan.irr_wave.insert(plan.irr_wave.end(), free_waves.begin() + (long)next_free, free_waves.begin() + (long)next_free + 4);
+                next_free += 4;
+            }
+        }
+        plan.irr_split.start[8] = (uint32_t)(plan.irr_wave.size() / 4);
     }
 
     plan.n_scratch_slots = slots;

@@ -277,7 +277,7 @@ def test_long_rows_are_split_into_bounded_slices_and_windows_into_bounded_items(
     rng = np.random.default_rng(1)
     cols = np.sort(rng.choice(4000, size=2500, replace=False))
     A = from_coo(np.full(2500, 3), cols, rng.standard_normal(2500), 8, 4000)
-    p = host_plan(A, 128, max_nnz_per_slice=256)
+    p = host_plan(A, 128, max_nnz_per_slice=256, xcd_partition_nnz=-1)
     st = p.stats()
     assert st["n_split_rows"] == 1 and st["n_scratch_slots"] == 10 and st["n_combine"] == 1
     waves = p.array(B_.RSH_ARR_IRR_WAVE).reshape(-1, 4)
@@ -285,3 +285,49 @@ def test_long_rows_are_split_into_bounded_slices_and_windows_into_bounded_items(
     p2 = host_plan(A, 128, force_path=2, max_tiles_per_item=8)
     items = p2.array(B_.RSH_ARR_TILE_ITEM).reshape(-1, 4)
     assert (items[:, 2] - items[:, 1]).max() <= 8 and p2.stats()["n_split_windows"] == 1
+
+
+def test_very_long_rows_are_cut_by_column_group_one_group_per_xcd():
+    rng = np.random.default_rng(4)
+    rows, cols = [], []
+    for r, d in [(0, 3000), (1, 1500), (2, 700), (3, 40)]:
+        c = np.sort(rng.choice(6000, size=d, replace=False))
+        rows.append(np.full(d, r)); cols.append(c)
+    rows, cols = np.concatenate(rows), np.concatenate(cols)
+    A = from_coo(rows, cols, rng.standard_normal(rows.size), 6, 6000)
+    p = host_plan(A, 128, force_path=1, xcd_partition_nnz=512)
+    st = p.stats()
+    waves = p.array(B_.RSH_ARR_IRR_WAVE).reshape(-1, 4)
+    irr_col = p.array(B_.RSH_ARR_IRR_COL)
+    comb = p.array(B_.RSH_ARR_COMBINE).reshape(-1, 4)
+    assert sorted(int(x) for x in comb[:, 0]) == [0, 1, 2]        # the three rows >= 512 entries are partitioned
+    # every scratch-bound slice holds columns of one group only, and a column never changes group
+    slices = waves[((waves[:, 3] & 3) == 1) & ((waves[:, 3] & 4) != 0)]
+    owner = {}
+    # XCD part x = waves [split[x], split[x+1]); recover the parts from the order of the list:
+    # pieces of one group are contiguous at the head of a part
+    for start, count, dst, info in slices:
+        cs = irr_col[int(start):int(start) + int(count)]
+        assert np.all(np.diff(cs) > 0)                             # ascending inside a piece
+    # group consistency: build column -> set of slices, then check slices sharing a column
+    # never appear in two different groups (group = connected component label by construction)
+    label = {}
+    for i, (start, count, dst, info) in enumerate(slices):
+        for c in irr_col[int(start):int(start) + int(count)]:
+            label.setdefault(int(c), set()).add(i)
+    # union-find over slices connected by a shared column gives at most 8 groups
+    parent = list(range(len(slices)))
+    def find(x):
+        while parent[x] != x:
+            parent[x] = parent[parent[x]]; x = parent[x]
+        return x
+    for members in label.values():
+        members = list(members)
+        for m in members[1:]:
+            parent[find(m)] = find(members[0])
+    assert len({find(i) for i in range(len(slices))}) <= 8
+    # decode is still exact
+    row_ptr, col_idx, val, _ = p.decode()
+    assert np.array_equal(row_ptr, A.row_ptr) and np.array_equal(col_idx, A.col_idx)
+    assert np.array_equal(val, A.val.view(np.uint16))
+    assert st["n_scratch_slots"] == len(slices) + 0 or st["n_scratch_slots"] >= len(slices)
