@@ -52,7 +52,9 @@ typedef struct {
 
 /* Planning options.  Obtain defaults with rsh_plan_opts_default, then override. */
 typedef struct {
-    int32_t window_rows;  /* W of Algorithm 1; 16 (one MFMA N-extent) is the only supported value */
+    int32_t window_rows;  /* W of Algorithm 1: 16, 32 or 64.  A window is W/16 sub-windows of 16 rows (one
+                             MFMA N-extent each) that share one condensed column space; the W/16 waves
+                             of a workgroup share each staged B tile                              */
     int32_t tile_k;       /* condensed columns per fragment; 16 is the only supported value     */
     int32_t tau_nnz;      /* Algorithm 1 row-length threshold; -1 = estimate from the matrix     */
     int32_t tau_inc;      /* Algorithm 1 column-gain threshold; -1 = estimate                    */
@@ -70,6 +72,9 @@ typedef struct {
                              row in a window (tests compare the three)                          */
     float min_reuse;      /* partition == 1: dissolve windows with nnz/|U| below this           */
     int32_t long_row_nnz; /* partition == 1: rows longer than this go to the irregular path; 0 = auto */
+    int32_t hub_windows;  /* partition == 1: 1 = long rows are grouped among themselves, longest first, and a
+                             group whose reuse reaches min_reuse becomes a window; 0 = all long rows go
+                             to the irregular path                                                 */
     int32_t xcd_partition_nnz; /* irregular rows with at least this many entries are cut by column group,
                              one group per XCD, so that each XCD gathers one eighth of B's columns for
                              them; 0 = auto (512), negative = off                                 */
@@ -163,20 +168,23 @@ int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
  * Read-only access to the host mirror of one plan array (exactly the bytes the
  * device holds).  *count is the number of elements.
  *
- * Dense-fragment part (RS-Tile "TC block part", Section 3.2), W = 16 rows, K = 16 columns:
- *   RSH_ARR_WIN_ROW      int32  [n_windows*16]  original row id of each window row, -1 = absent
+ * Dense-fragment part (RS-Tile "TC block part", Section 3.2).  W = window_rows, NW = W/16,
+ * fragment = 16 condensed columns; fragment t has NW sub-fragments, sub-fragment s covering
+ * window rows 16s .. 16s+15:
+ *   RSH_ARR_WIN_ROW      int32  [n_windows*W]   original row id of each window row, -1 = absent
  *   RSH_ARR_WIN_TILE_OFF uint32 [n_windows+1]   prefix sum of fragments per window
  *   RSH_ARR_TILE_COLID   int32  [n_tiles*16]    original column of fragment column k; padding
  *                                               columns repeat the last valid one
- *   RSH_ARR_TILE_MASK    uint64 [n_tiles*4]     bitmap: cell (row r, column k) is bit
+ *   RSH_ARR_TILE_MASK    uint64 [n_tiles*NW*4]  bitmap of sub-fragment (t, s) at (t*NW+s)*4: cell
+ *                                               (row r of the sub-window, column k) is bit
  *                                               (k/4)*16 + r of word k%4; padding cells are 0
- *   RSH_ARR_TILE_VAL_OFF uint32 [n_tiles+1]     start of each fragment's values in TILE_VAL,
+ *   RSH_ARR_TILE_VAL_OFF uint32 [n_tiles*NW+1]  start of each sub-fragment's values in TILE_VAL,
  *                                               in elements, always a multiple of 4
- *   RSH_ARR_TILE_VAL     uint16 []              binary16 values, per fragment ordered by
+ *   RSH_ARR_TILE_VAL     uint16 []              binary16 values, per sub-fragment ordered by
  *                                               ((k/4)*16 + r, k%4) ascending; pad elements are 0
  *   RSH_ARR_TILE_ITEM    uint32 [n_items*4]     {window, first tile, end tile, dst}: dst ==
  *                                               0xffffffff -> rows of C; else first scratch slot
- *                                               of a 16-slot partial block
+ *                                               of a W-slot partial block
  * Irregular part (RS-Tile "residual part", Section 3.2):
  *   RSH_ARR_IRR_COL      int32  []              column ids, CSR order inside a row
  *   RSH_ARR_IRR_VAL      uint16 []              binary16 values, same order

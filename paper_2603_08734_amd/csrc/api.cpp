@@ -98,6 +98,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->force_path = 0;
     o->min_reuse = 1.25f;
     o->long_row_nnz = 0;
+    o->hub_windows = 0;
     o->xcd_partition_nnz = 0;
     o->upload = 1;
     o->threads = 0;
@@ -111,7 +112,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     rsh_plan_opts_t o;
     rsh_plan_opts_default(&o);
     if (opts) o = *opts;
-    if (o.window_rows != rsh::kW || o.tile_k != rsh::kK) return RSH_ERR_BAD_OPTION;
+    if ((o.window_rows != 16 && o.window_rows != 32 && o.window_rows != 64) || o.tile_k != rsh::kK) return RSH_ERR_BAD_OPTION;
     if (o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2) return RSH_ERR_BAD_OPTION;
     if (o.reorder < 0 || o.reorder > 1 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
@@ -132,7 +133,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         h.n_rows = csr->n_rows;
         h.n_cols = csr->n_cols;
         h.nnz = csr->nnz;
-        h.geo = rsh::make_geometry(N);
+        h.geo = rsh::make_geometry(N, o.window_rows);
         h.opts = o;
         std::vector<int32_t> col_deg;
         rsh::column_degrees(*csr, col_deg, threads);

@@ -208,45 +208,66 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
 // at features 16c+4s.. of staged row 4*(l/16)+r.  The LDS row stride is chosen so that
 // the 16 addresses of a group fall in distinct banks.
 // ---------------------------------------------------------------------------
-template <int NCH>
+template <int NCH, int NW>
 struct TileGeom {
     static constexpr int P = 16 * NCH;                      // features per panel
     static constexpr int TPR = P / 8;                       // lanes per B row (16 bytes each)
-    static constexpr int ROWS_PER_LOAD = (64 / TPR) > 16 ? 16 : (64 / TPR);
-    static constexpr int NLD = 16 / ROWS_PER_LOAD;          // load instructions per fragment
+    static constexpr int THREADS = 64 * NW;                 // threads that share one staged B tile
+    static constexpr int NLD = (16 * TPR + THREADS - 1) / THREADS;   // 16-byte loads per thread per fragment
     static constexpr int LDB = P == 16 ? 16 : (P == 32 ? 80 : P + 16);   // LDS row stride, halves
+    static constexpr int ITEMS_PER_BLOCK = NW == 1 ? kWavesPerBlock : 1;
+    static constexpr int NBUF = NW == 1 ? 1 : 2;            // shared tiles are double-buffered
 };
 
-template <int NCH>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
+// NW = sub-windows (waves) per window.  With NW == 1 a block runs four independent items,
+// one per wave, and needs no barrier (LDS operations of one wave complete in order).  With
+// NW > 1 the NW waves of a block share one item: they load the fragment's 16 B rows together,
+// once, into a double-buffered LDS tile, meet at one barrier per fragment, and each wave
+// multiplies its own 16 rows of the window against the shared tile.
+template <int NCH, int NW, int D>
+__global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_tile_kernel(
     const uint4* __restrict__ items, XcdSplit xs,
     const int32_t* __restrict__ win_row, const int32_t* __restrict__ tile_colid,
     const uint64_t* __restrict__ tile_mask, const uint32_t* __restrict__ tile_val_off,
     const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, float* __restrict__ C,
     float* __restrict__ scratch, int N) {
-    using Gm = TileGeom<NCH>;
-    constexpr int P = Gm::P, TPR = Gm::TPR, ROWS_PER_LOAD = Gm::ROWS_PER_LOAD, NLD = Gm::NLD, LDB = Gm::LDB;
-    __shared__ __attribute__((aligned(16))) _Float16 lds_b[kWavesPerBlock][16 * LDB];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWavesPerBlock][256 + 8];
+    using Gm = TileGeom<NCH, NW>;
+    constexpr int P = Gm::P, TPR = Gm::TPR, NLD = Gm::NLD, LDB = Gm::LDB, THREADS = Gm::THREADS;
+    __shared__ __attribute__((aligned(16))) _Float16 lds_b[Gm::ITEMS_PER_BLOCK][Gm::NBUF][16 * LDB];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWavesPerBlock > NW ? kWavesPerBlock : NW][256 + 8];
 
     const int lane = threadIdx.x & 63;
-    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave in block
+    const int sub = NW == 1 ? 0 : wib;                                  // sub-window of this wave
     uint32_t item;
-    if (!xcd_work_item(xs, &item)) return;
+    {
+        const uint32_t x = blockIdx.x & 7u;
+        const uint32_t i = xs.start[x] + (blockIdx.x >> 3) * Gm::ITEMS_PER_BLOCK + (NW == 1 ? (uint32_t)wib : 0u);
+        item = __builtin_amdgcn_readfirstlane(i);
+        if (i >= xs.start[x + 1]) return;   // uniform per wave (NW == 1) or per block (NW > 1)
+    }
     const uint4 it = items[item];
     const uint32_t win = __builtin_amdgcn_readfirstlane(it.x), t_begin = __builtin_amdgcn_readfirstlane(it.y);
     const uint32_t t_end = __builtin_amdgcn_readfirstlane(it.z), dst = __builtin_amdgcn_readfirstlane(it.w);
     const int panel = blockIdx.y * P;
-    _Float16* sb = lds_b[wib];
+    _Float16* sb0 = lds_b[NW == 1 ? wib : 0][0];
     uint16_t* sv = lds_v[wib];
 
-    const int ld_row = lane / TPR;          // row handled inside one load instruction
-    const int ld_col = (lane % TPR) * 8;    // feature offset inside the panel
-    const bool ld_active = TPR >= 4 || ld_row < 16;   // a B row narrower than 4 lanes leaves lanes idle
+    // cooperative staging: thread `tix` of the THREADS sharing the tile takes 16-byte piece
+    // j*THREADS + tix of the 16 x TPR pieces of a fragment's B rows
+    const int tix = NW == 1 ? lane : (int)threadIdx.x;
+    int ld_row[NLD], ld_col[NLD];
+    bool ld_on[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int piece = j * THREADS + tix;
+        ld_row[j] = piece / TPR;
+        ld_col[j] = (piece % TPR) * 8;
+        ld_on[j] = ld_row[j] < 16;
+    }
     const int m = lane & 15, kg = lane >> 4;
-    const __half* Bp = B + panel + ld_col;
-    // address of this lane's run for the transposing read (chunk 0)
-    const _Float16* tr_ptr = sb + (4 * kg + (m >> 2)) * LDB + 4 * (m & 3);
+    const __half* Bp = B + panel;
+    const int tr_off = (4 * kg + (m >> 2)) * LDB + 4 * (m & 3);   // this lane's run for the transposing read
 
     float4_t acc[NCH];
 #pragma unroll
@@ -254,83 +275,104 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_tile_kernel(
 
     if (t_begin < t_end) {
         const uint32_t t_last = t_end - 1;
-        // fragment metadata, fetched two fragments ahead
-        int colid_a = tile_colid[(size_t)t_begin * 16 + m];
-        int colid_b = tile_colid[(size_t)min(t_begin + 1, t_last) * 16 + m];
-        uint32_t voff_a = tile_val_off[t_begin], vend_a = tile_val_off[t_begin + 1];
-        uint32_t voff_b = tile_val_off[min(t_begin + 1, t_last)], vend_b = tile_val_off[min(t_begin + 1, t_last) + 1];
-        // staged registers of the next fragment
-        uint4_t breg[NLD];
-        uint2_t vreg = {0u, 0u};
+        // Ring of D fragments in flight per thread: slot d holds the staged B pieces and values
+        // of fragment base+d; the metadata ring holds column ids / value ranges of base+D+d.
+        uint4_t breg[D][NLD];
+        uint2_t vreg[D];
+        int colid_n[D];
+        uint32_t voff_n[D], vend_n[D];
 #pragma unroll
-        for (int j = 0; j < NLD; ++j) breg[j] = (uint4_t){0u, 0u, 0u, 0u};
+        for (int d = 0; d < D; ++d) {
+            const uint32_t t = min(t_begin + (uint32_t)d, t_last);
+            const int colid = tile_colid[(size_t)t * 16 + m];
+            const uint32_t voff = tile_val_off[(size_t)t * NW + sub], vend = tile_val_off[(size_t)t * NW + sub + 1];
+            const uint32_t tn = min(t_begin + (uint32_t)(D + d), t_last);
+            colid_n[d] = tile_colid[(size_t)tn * 16 + m];
+            voff_n[d] = tile_val_off[(size_t)tn * NW + sub];
+            vend_n[d] = tile_val_off[(size_t)tn * NW + sub + 1];
+            vreg[d] = (uint2_t){0u, 0u};
 #pragma unroll
-        for (int j = 0; j < NLD; ++j) {
-            const int c = shfl_i32(colid_a, (j * ROWS_PER_LOAD + ld_row) & 15);
-            if (ld_active) breg[j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N);
-        }
-        if ((uint32_t)lane * 4u < vend_a - voff_a) vreg = *reinterpret_cast<const uint2_t*>(tile_val + voff_a + lane * 4);
-
-        for (uint32_t t = t_begin; t < t_end; ++t) {
-            // bitmaps of this fragment (wave-uniform)
-            const uint64_t m0 = tile_mask[(size_t)t * 4 + 0], m1 = tile_mask[(size_t)t * 4 + 1];
-            const uint64_t m2 = tile_mask[(size_t)t * 4 + 2], m3 = tile_mask[(size_t)t * 4 + 3];
-            // metadata two fragments ahead
-            const uint32_t t2 = min(t + 2, t_last);
-            const int colid_c = tile_colid[(size_t)t2 * 16 + m];
-            const uint32_t voff_c = tile_val_off[t2], vend_c = tile_val_off[t2 + 1];
-
-            // staged registers -> LDS (LDS operations of one wave complete in order, so the
-            // reads of the previous fragment are already done)
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int j = 0; j < NLD; ++j)
-                if (ld_active) *reinterpret_cast<uint4_t*>(sb + (j * ROWS_PER_LOAD + ld_row) * LDB + ld_col) = breg[j];
-            *reinterpret_cast<uint2_t*>(sv + lane * 4) = vreg;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-
-            // global loads of the next fragment go out before this one is multiplied
-            if (t + 1 < t_end) {
+            for (int j = 0; j < NLD; ++j) breg[d][j] = (uint4_t){0u, 0u, 0u, 0u};
+            if (t_begin + (uint32_t)d < t_end) {
 #pragma unroll
                 for (int j = 0; j < NLD; ++j) {
-                    const int c = shfl_i32(colid_b, (j * ROWS_PER_LOAD + ld_row) & 15);
-                    if (ld_active) breg[j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N);
+                    const int c = shfl_i32(colid, ld_row[j] & 15);
+                    if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N + ld_col[j]);
                 }
-                vreg = (uint2_t){0u, 0u};
-                if ((uint32_t)lane * 4u < vend_b - voff_b) vreg = *reinterpret_cast<const uint2_t*>(tile_val + voff_b + lane * 4);
+                if ((uint32_t)lane * 4u < vend - voff) vreg[d] = *reinterpret_cast<const uint2_t*>(tile_val + voff + lane * 4);
             }
+        }
 
-            // expand this lane's four cells (window row m, fragment columns 4kg..4kg+3)
-            const uint32_t bit0 = (uint32_t)(m0 >> lane) & 1u, bit1 = (uint32_t)(m1 >> lane) & 1u;
-            const uint32_t bit2 = (uint32_t)(m2 >> lane) & 1u, bit3 = (uint32_t)(m3 >> lane) & 1u;
-            const uint32_t i0 = bits_below_lane(m0) + bits_below_lane(m1) + bits_below_lane(m2) + bits_below_lane(m3);
-            const uint32_t i1 = i0 + bit0, i2 = i1 + bit1, i3 = i2 + bit2;
-            half4_t a_frag;
-            a_frag[0] = bit0 ? __builtin_bit_cast(_Float16, sv[i0]) : (_Float16)0;
-            a_frag[1] = bit1 ? __builtin_bit_cast(_Float16, sv[i1]) : (_Float16)0;
-            a_frag[2] = bit2 ? __builtin_bit_cast(_Float16, sv[i2]) : (_Float16)0;
-            a_frag[3] = bit3 ? __builtin_bit_cast(_Float16, sv[i3]) : (_Float16)0;
-
+        int buf = 0;
+        for (uint32_t base = t_begin; base < t_end; base += D) {
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const half4_t b_frag = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (short4_t __attribute__((address_space(3)))*)(tr_ptr + 16 * c)));
-                acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
-            }
+            for (int d = 0; d < D; ++d) {
+                const uint32_t t = base + (uint32_t)d;
+                if (t < t_end) {   // uniform
+                    // bitmaps of this wave's sub-fragment (wave-uniform)
+                    const uint64_t* mk = tile_mask + ((size_t)t * NW + sub) * 4;
+                    const uint64_t m0 = mk[0], m1 = mk[1], m2 = mk[2], m3 = mk[3];
 
-            colid_a = colid_b; colid_b = colid_c;
-            voff_a = voff_b; vend_a = vend_b;
-            voff_b = voff_c; vend_b = vend_c;
+                    // staged registers -> LDS
+                    _Float16* sb = sb0 + buf * (16 * LDB);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int j = 0; j < NLD; ++j)
+                        if (ld_on[j]) *reinterpret_cast<uint4_t*>(sb + ld_row[j] * LDB + ld_col[j]) = breg[d][j];
+                    *reinterpret_cast<uint2_t*>(sv + lane * 4) = vreg[d];
+                    if (NW > 1) __syncthreads();
+                    else {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+
+                    // refill slot d with fragment t+D, whose metadata arrived one round ago
+                    if (t + D < t_end) {
+#pragma unroll
+                        for (int j = 0; j < NLD; ++j) {
+                            const int c = shfl_i32(colid_n[d], ld_row[j] & 15);
+                            if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N + ld_col[j]);
+                        }
+                        vreg[d] = (uint2_t){0u, 0u};
+                        if ((uint32_t)lane * 4u < vend_n[d] - voff_n[d])
+                            vreg[d] = *reinterpret_cast<const uint2_t*>(tile_val + voff_n[d] + lane * 4);
+                    }
+                    // metadata of fragment t+2D
+                    const uint32_t t2 = min(t + 2u * D, t_last);
+                    colid_n[d] = tile_colid[(size_t)t2 * 16 + m];
+                    voff_n[d] = tile_val_off[(size_t)t2 * NW + sub];
+                    vend_n[d] = tile_val_off[(size_t)t2 * NW + sub + 1];
+
+                    if (NW == 1 || (m0 | m1 | m2 | m3) != 0ull) {
+                        // expand this lane's four cells (window row m, fragment columns 4kg..4kg+3)
+                        const uint32_t bit0 = (uint32_t)(m0 >> lane) & 1u, bit1 = (uint32_t)(m1 >> lane) & 1u;
+                        const uint32_t bit2 = (uint32_t)(m2 >> lane) & 1u, bit3 = (uint32_t)(m3 >> lane) & 1u;
+                        const uint32_t i0 = bits_below_lane(m0) + bits_below_lane(m1) + bits_below_lane(m2) + bits_below_lane(m3);
+                        const uint32_t i1 = i0 + bit0, i2 = i1 + bit1, i3 = i2 + bit2;
+                        half4_t a_frag;
+                        a_frag[0] = bit0 ? __builtin_bit_cast(_Float16, sv[i0]) : (_Float16)0;
+                        a_frag[1] = bit1 ? __builtin_bit_cast(_Float16, sv[i1]) : (_Float16)0;
+                        a_frag[2] = bit2 ? __builtin_bit_cast(_Float16, sv[i2]) : (_Float16)0;
+                        a_frag[3] = bit3 ? __builtin_bit_cast(_Float16, sv[i3]) : (_Float16)0;
+#pragma unroll
+                        for (int c = 0; c < NCH; ++c) {
+                            const half4_t b_frag = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 16 * c)));
+                            acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
+                        }
+                    }
+                    if (NW > 1) buf ^= 1;
+                }
+            }
         }
     }
 
-    // lane (q = lane/16, r = lane%16) owns features 16c + 4q .. 16c + 4q + 3 of window row r
-    const int r = lane & 15, q = lane >> 4;
+    // lane (q = lane/16, r = lane%16) owns features 16c + 4q .. 16c + 4q + 3 of the wave's row r
+    const int r = sub * 16 + (lane & 15), q = lane >> 4;
     float* out;
     if (dst == kNoDst) {
-        const int row = win_row[(size_t)win * 16 + r];
+        const int row = win_row[(size_t)win * (16 * NW) + r];
         if (row < 0) return;
         out = C + (size_t)row * N;
     } else {
@@ -414,12 +456,33 @@ static void launch_irregular_t(const DevicePlan& d, const void* B, void* C, hipS
                        d.scratch, d.geo.N);
 }
 
-template <int NCH>
+template <int NCH, int NW, int D>
 static void launch_tile_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
-    dim3 grid(grid_for(d.tile_split), (unsigned)(d.geo.N / d.geo.tile_panel));
-    hipLaunchKernelGGL(rsh_tile_kernel<NCH>, grid, dim3(64 * kWavesPerBlock), 0, st, (const uint4*)d.tile_item,
-                       d.tile_split, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off, d.tile_val,
-                       (const __half*)B, (float*)C, d.scratch, d.geo.N);
+    constexpr int items_per_block = NW == 1 ? kWavesPerBlock : 1;
+    uint32_t longest = 0;
+    for (int x = 0; x < 8; ++x) longest = std::max(longest, d.tile_split.start[x + 1] - d.tile_split.start[x]);
+    dim3 grid(8u * ((longest + items_per_block - 1) / items_per_block), (unsigned)(d.geo.N / d.geo.tile_panel));
+    hipLaunchKernelGGL((rsh_tile_kernel<NCH, NW, D>), grid, dim3(NW == 1 ? 64 * kWavesPerBlock : 64 * NW), 0, st,
+                       (const uint4*)d.tile_item, d.tile_split, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off,
+                       d.tile_val, (const __half*)B, (float*)C, d.scratch, d.geo.N);
+}
+
+// Fragments in flight per thread: one for 16-row windows (each thread stages four 16-byte pieces
+// of a fragment), two when the waves of a window share the staging (measured best of 1, 2, 4, 8).
+template <int NCH, int NW>
+static int launch_tile_d(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+    launch_tile_t<NCH, NW, (NW == 1 ? 1 : 2)>(d, B, C, st);
+    return RSH_OK;
+}
+
+template <int NCH>
+static int launch_tile_nw(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+    switch (d.geo.nw) {
+        case 1: return launch_tile_d<NCH, 1>(d, B, C, st);
+        case 2: return launch_tile_d<NCH, 2>(d, B, C, st);
+        case 4: return launch_tile_d<NCH, 4>(d, B, C, st);
+        default: return RSH_ERR_BAD_OPTION;
+    }
 }
 
 int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void* const* events) {
@@ -428,15 +491,17 @@ int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void*
         if (events) (void)hipEventRecord((hipEvent_t)events[i], st);
     };
     mark(0);
+    int rc = RSH_OK;
     if (d.n_tile_items > 0) {
         switch (d.geo.tile_nch) {
-            case 1: launch_tile_t<1>(d, B, C, st); break;
-            case 2: launch_tile_t<2>(d, B, C, st); break;
-            case 4: launch_tile_t<4>(d, B, C, st); break;
-            case 8: launch_tile_t<8>(d, B, C, st); break;
-            case 16: launch_tile_t<16>(d, B, C, st); break;
+            case 1: rc = launch_tile_nw<1>(d, B, C, st); break;
+            case 2: rc = launch_tile_nw<2>(d, B, C, st); break;
+            case 4: rc = launch_tile_nw<4>(d, B, C, st); break;
+            case 8: rc = launch_tile_nw<8>(d, B, C, st); break;
+            case 16: rc = launch_tile_nw<16>(d, B, C, st); break;
             default: return RSH_ERR_UNSUPPORTED_N;
         }
+        if (rc != RSH_OK) return rc;
     }
     mark(1);
     if (d.n_irr_waves > 0) {

@@ -7,7 +7,8 @@
 
 namespace rsh {
 
-constexpr int kW = 16;  // rows per window  (MFMA N extent)
+constexpr int kW = 16;  // rows per sub-window (MFMA N extent); a window is nw of them
+constexpr int kMaxWindowRows = 64;
 constexpr int kK = 16;  // condensed columns per fragment (MFMA K extent)
 constexpr uint32_t kNoDst = 0xffffffffu;
 // irregular wave descriptor {start, count, dst, info}; info = kind | flags | L << 8 | R << 16
@@ -25,8 +26,10 @@ struct Geometry {
     int irr_teams = 0;  // 64 / irr_tpr
     int tile_panel = 0; // features per tile-kernel panel: gcd(N, 256)
     int tile_nch = 0;   // 16-feature MFMA chunks per panel
+    int win_rows = 16;  // rows per window (16, 32 or 64)
+    int nw = 1;         // sub-windows (waves) per window = win_rows / 16
 };
-Geometry make_geometry(int N);
+Geometry make_geometry(int N, int window_rows);
 
 // Work lists are cut into 8 contiguous parts of equal estimated cost, one per XCD:
 // part x is items [start[x], start[x+1]).
@@ -64,7 +67,7 @@ struct HostPlan {
 
 // Row classes produced by the partitioner (Section 3.3.1).
 struct Partition {
-    std::vector<int32_t> win_row;     // kW ids per window, -1 = absent
+    std::vector<int32_t> win_row;     // window_rows ids per window, -1 = absent
     std::vector<int32_t> irregular;   // non-empty rows routed to the residual path, processing order
     std::vector<int32_t> empty;       // rows without stored entries
 };

@@ -21,9 +21,11 @@ int hardware_threads() {
 
 static int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
 
-Geometry make_geometry(int N) {
+Geometry make_geometry(int N, int window_rows) {
     Geometry g;
     g.N = N;
+    g.win_rows = window_rows;
+    g.nw = window_rows / kW;
     g.irr_panel = gcd_int(N, 512);
     g.irr_tpr = g.irr_panel / 8;
     g.irr_teams = 64 / g.irr_tpr;
@@ -103,6 +105,7 @@ static int64_t union_size(const rsh_csr_t& a, const int32_t* rows, int n, std::v
 void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
                     int32_t tau_nnz, int32_t tau_inc, Partition& out, int threads) {
     const int64_t n = a.n_rows;
+    const int W = o.window_rows;
     out.win_row.clear();
     out.irregular.clear();
     out.empty.clear();
@@ -115,7 +118,7 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
             else if (o.force_path == 1) out.irregular.push_back(r);
             else out.win_row.push_back(r);
         }
-        while (out.win_row.size() % kW) out.win_row.push_back(-1);
+        while (out.win_row.size() % W) out.win_row.push_back(-1);
         return;
     }
 
@@ -132,14 +135,14 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
                 ++i;
                 continue;
             }
-            const int n_others = (int)std::min<int64_t>(kW - 1, n - i - 1);
+            const int n_others = (int)std::min<int64_t>(W - 1, n - i - 1);
             const int64_t gain = own_columns(a, r, order.data() + i + 1, n_others);
             if (gain < tau_inc && nz <= tau_nnz) {
                 out.irregular.push_back(r);
                 ++i;
             } else {
-                for (int q = 0; q < kW; ++q) out.win_row.push_back(i + q < n ? order[i + q] : -1);
-                i += kW;
+                for (int q = 0; q < W; ++q) out.win_row.push_back(i + q < n ? order[i + q] : -1);
+                i += W;
             }
         }
         return;
@@ -149,40 +152,40 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
     // that are very short *and* share few columns with the rows around them; long rows are
     // split off as well (Section 3.3.3 treats them separately), and a window is only kept
     // if staging its distinct columns once beats gathering per stored entry.
-    enum : uint8_t { kEmpty = 0, kIrr = 1, kWin = 2 };
-    std::vector<uint8_t> cls((size_t)n, kWin);
+    enum : uint8_t { kEmpty = 0, kIrr = 1, kWinCls = 2, kLong = 3 };
+    std::vector<uint8_t> cls((size_t)n, kWinCls);
     const double mean = n > 0 ? (double)a.nnz / (double)n : 0.0;
     const int64_t long_thr = o.long_row_nnz > 0 ? o.long_row_nnz : (int64_t)std::max(4.0 * mean, 4.0 * kK);
     parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
-        int32_t others[kW];
+        int32_t others[kMaxWindowRows];
         for (int64_t i = b; i < e; ++i) {
             const int32_t r = order[i];
             const int64_t nz = row_len(a, r);
             if (nz == 0) cls[i] = kEmpty;
-            else if (nz > long_thr) cls[i] = kIrr;
+            else if (nz > long_thr) cls[i] = kLong;
             else if (nz <= tau_nnz) {
                 int n_others = 0;
-                for (int64_t q = i + 1; q < n && n_others < kW - 1; ++q)
+                for (int64_t q = i + 1; q < n && n_others < W - 1; ++q)
                     if (row_len(a, order[q]) > 0) others[n_others++] = order[q];
                 const int64_t shared = nz - own_columns(a, r, others, n_others);
                 if (shared < tau_inc) cls[i] = kIrr;
             }
         }
     });
-    // group eligible rows kW at a time, then test each group's column reuse
+    // group eligible rows W at a time, then test each group's column reuse
     std::vector<int64_t> win_pos;  // positions (in `order`) of eligible rows
     win_pos.reserve((size_t)n);
     for (int64_t i = 0; i < n; ++i)
-        if (cls[i] == kWin) win_pos.push_back(i);
-    const int64_t n_groups = ((int64_t)win_pos.size() + kW - 1) / kW;
+        if (cls[i] == kWinCls) win_pos.push_back(i);
+    const int64_t n_groups = ((int64_t)win_pos.size() + W - 1) / W;
     std::vector<uint8_t> keep((size_t)n_groups, 1);
     parallel_chunks(n_groups, threads, [&](int64_t b, int64_t e, int) {
         std::vector<int32_t> tmp;
-        int32_t rows[kW];
+        int32_t rows[kMaxWindowRows];
         for (int64_t g = b; g < e; ++g) {
             int cnt = 0;
             int64_t nnz_w = 0;
-            for (int64_t q = g * kW; q < std::min<int64_t>((g + 1) * kW, (int64_t)win_pos.size()); ++q) {
+            for (int64_t q = g * W; q < std::min<int64_t>((g + 1) * W, (int64_t)win_pos.size()); ++q) {
                 rows[cnt++] = order[win_pos[q]];
                 nnz_w += row_len(a, rows[cnt - 1]);
             }
@@ -192,16 +195,48 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
     });
     for (int64_t g = 0; g < n_groups; ++g)
         if (!keep[g])
-            for (int64_t q = g * kW; q < std::min<int64_t>((g + 1) * kW, (int64_t)win_pos.size()); ++q)
+            for (int64_t q = g * W; q < std::min<int64_t>((g + 1) * W, (int64_t)win_pos.size()); ++q)
                 cls[win_pos[q]] = kIrr;
     for (int64_t g = 0; g < n_groups; ++g) {
         if (!keep[g]) continue;
-        for (int64_t q = g * kW; q < (g + 1) * kW; ++q)
+        for (int64_t q = g * W; q < (g + 1) * W; ++q)
             out.win_row.push_back(q < (int64_t)win_pos.size() ? order[win_pos[q]] : -1);
+    }
+    // Long rows are grouped among themselves, longest first: rows of similar length in a
+    // heavy-tailed matrix share the frequent columns, so a group can still reach the reuse
+    // that makes a window pay; groups that do not are left to the irregular path.
+    if (o.hub_windows) {
+        std::vector<int64_t> long_pos;
+        for (int64_t i = 0; i < n; ++i)
+            if (cls[i] == kLong) long_pos.push_back(i);
+        std::stable_sort(long_pos.begin(), long_pos.end(), [&](int64_t x, int64_t y) { return row_len(a, order[x]) > row_len(a, order[y]); });
+        const int64_t n_lg = ((int64_t)long_pos.size() + W - 1) / W;
+        std::vector<uint8_t> keep_l((size_t)n_lg, 0);
+        parallel_chunks(n_lg, threads, [&](int64_t b, int64_t e, int) {
+            std::vector<int32_t> tmp;
+            int32_t rows[kMaxWindowRows];
+            for (int64_t g = b; g < e; ++g) {
+                int cnt = 0;
+                int64_t nnz_w = 0;
+                for (int64_t q = g * W; q < std::min<int64_t>((g + 1) * W, (int64_t)long_pos.size()); ++q) {
+                    rows[cnt++] = order[long_pos[q]];
+                    nnz_w += row_len(a, rows[cnt - 1]);
+                }
+                const int64_t u = union_size(a, rows, cnt, tmp);
+                keep_l[g] = (double)nnz_w >= (double)o.min_reuse * (double)u;
+            }
+        });
+        for (int64_t g = 0; g < n_lg; ++g) {
+            if (!keep_l[g]) continue;
+            for (int64_t q = g * W; q < (g + 1) * W; ++q) {
+                if (q < (int64_t)long_pos.size()) cls[long_pos[q]] = kWinCls;
+                out.win_row.push_back(q < (int64_t)long_pos.size() ? order[long_pos[q]] : -1);
+            }
+        }
     }
     for (int64_t i = 0; i < n; ++i) {
         if (cls[i] == kEmpty) out.empty.push_back(order[i]);
-        else if (cls[i] == kIrr) out.irregular.push_back(order[i]);
+        else if (cls[i] == kIrr || cls[i] == kLong) out.irregular.push_back(order[i]);
     }
 }
 
@@ -226,17 +261,17 @@ XcdSplit split_by_cost(const std::vector<uint32_t>& cost) {
 static inline uint32_t round_up4(uint32_t x) { return (x + 3u) & ~3u; }
 
 struct WinEntry {
-    uint64_t key;  // col << 4 | window row
+    uint64_t key;  // col << 6 | window row
     uint16_t val;
 };
 
 // Collect the stored entries of one window sorted by (column, window row).
-static void gather_window(const rsh_csr_t& a, const int32_t* rows, std::vector<WinEntry>& ent) {
+static void gather_window(const rsh_csr_t& a, const int32_t* rows, int W, std::vector<WinEntry>& ent) {
     ent.clear();
-    for (int r = 0; r < kW; ++r) {
+    for (int r = 0; r < W; ++r) {
         if (rows[r] < 0) continue;
         for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p)
-            ent.push_back({((uint64_t)(uint32_t)a.col_idx[p] << 4) | (uint64_t)r, a.val_f16[p]});
+            ent.push_back({((uint64_t)(uint32_t)a.col_idx[p] << 6) | (uint64_t)r, a.val_f16[p]});
     }
     std::sort(ent.begin(), ent.end(), [](const WinEntry& x, const WinEntry& y) { return x.key < y.key; });
 }
@@ -245,32 +280,35 @@ static inline int popc64(uint64_t x) { return __builtin_popcountll(x); }
 
 int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads) {
     const Geometry& geo = plan.geo;
-    const int64_t n_win = (int64_t)part.win_row.size() / kW;
+    const int W = geo.win_rows, NW = geo.nw;
+    const int64_t n_win = (int64_t)part.win_row.size() / W;
     plan.win_row = part.win_row;
 
     // ---- pass 1: fragments and padded value count per window ---------------------------
+    // A window of W = 16*NW rows shares one condensed column space; fragment t of the window
+    // has NW sub-fragments (rows 16s .. 16s+15), each with its own bitmap and value run.
     std::vector<uint32_t> win_tiles((size_t)n_win), win_vals((size_t)n_win);
     std::vector<int64_t> win_cols((size_t)n_win);
     parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
         std::vector<WinEntry> ent;
-        std::vector<uint32_t> cnt;
+        std::vector<uint32_t> cnt;   // entries per (fragment, sub-fragment)
         for (int64_t w = b; w < e; ++w) {
-            gather_window(a, &part.win_row[w * kW], ent);
+            gather_window(a, &part.win_row[w * W], W, ent);
             int64_t u = 0;
             cnt.clear();
             uint64_t prev_col = ~0ull;
             for (const WinEntry& x : ent) {
-                const uint64_t c = x.key >> 4;
+                const uint64_t c = x.key >> 6;
                 if (c != prev_col) {
                     prev_col = c;
-                    if (u % kK == 0) cnt.push_back(0);
+                    if (u % kK == 0) cnt.insert(cnt.end(), (size_t)NW, 0u);
                     ++u;
                 }
-                ++cnt.back();
+                ++cnt[cnt.size() - (size_t)NW + (size_t)((x.key & 63) >> 4)];
             }
             uint32_t v = 0;
             for (uint32_t c : cnt) v += round_up4(c);
-            win_tiles[w] = (uint32_t)cnt.size();
+            win_tiles[w] = (uint32_t)(cnt.size() / (size_t)NW);
             win_vals[w] = v;
             win_cols[w] = u;
         }
@@ -280,7 +318,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     int64_t sum_cols = 0;
     for (int64_t w = 0; w < n_win; ++w) {
         const uint64_t t = (uint64_t)plan.win_tile_off[w] + win_tiles[w];
-        if (t >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+        if (t * (uint64_t)NW >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
         plan.win_tile_off[w + 1] = (uint32_t)t;
         win_val_off[w + 1] = win_val_off[w] + win_vals[w];
         sum_cols += win_cols[w];
@@ -288,8 +326,8 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     const int64_t n_tiles = plan.win_tile_off[n_win];
     if (win_val_off[n_win] >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
     plan.tile_colid.assign((size_t)n_tiles * kK, 0);
-    plan.tile_mask.assign((size_t)n_tiles * 4, 0);
-    plan.tile_val_off.assign((size_t)n_tiles + 1, 0);
+    plan.tile_mask.assign((size_t)n_tiles * NW * 4, 0);
+    plan.tile_val_off.assign((size_t)n_tiles * NW + 1, 0);
     plan.tile_val.assign((size_t)win_val_off[n_win] + 8, 0);  // tail pad: kernels read 4 elements per lane
 
     // ---- pass 2: fill -------------------------------------------------------------------
@@ -298,7 +336,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         std::vector<WinEntry> ent;
         std::vector<uint32_t> ucol;   // condensed column index of each entry
         for (int64_t w = b; w < e; ++w) {
-            gather_window(a, &part.win_row[w * kW], ent);
+            gather_window(a, &part.win_row[w * W], W, ent);
             win_nnz[w] = (int64_t)ent.size();
             const uint32_t t0 = plan.win_tile_off[w];
             const uint32_t nt = plan.win_tile_off[w + 1] - t0;
@@ -307,15 +345,15 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
             int64_t u = -1;
             uint64_t prev_col = ~0ull;
             for (size_t i = 0; i < ent.size(); ++i) {
-                const uint64_t c = ent[i].key >> 4;
+                const uint64_t c = ent[i].key >> 6;
                 if (c != prev_col) {
                     prev_col = c;
                     ++u;
                     plan.tile_colid[(size_t)t0 * kK + (size_t)u] = (int32_t)c;
                 }
                 ucol[i] = (uint32_t)u;
-                const uint32_t t = (uint32_t)u / kK, k = (uint32_t)u % kK, r = (uint32_t)(ent[i].key & 15);
-                plan.tile_mask[(size_t)(t0 + t) * 4 + (k & 3)] |= 1ull << ((k >> 2) * 16 + r);
+                const uint32_t t = (uint32_t)u / kK, k = (uint32_t)u % kK, r = (uint32_t)(ent[i].key & 63);
+                plan.tile_mask[((size_t)(t0 + t) * NW + (r >> 4)) * 4 + (k & 3)] |= 1ull << ((k >> 2) * 16 + (r & 15));
             }
             // padding columns of the last fragment repeat its last valid column
             if (nt > 0) {
@@ -323,28 +361,29 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 for (int64_t k = n_u; k < (int64_t)nt * kK; ++k)
                     plan.tile_colid[(size_t)t0 * kK + (size_t)k] = plan.tile_colid[(size_t)t0 * kK + (size_t)(n_u - 1)];
             }
-            // value offsets
+            // value offsets of every sub-fragment
             uint64_t off = win_val_off[w];
-            for (uint32_t t = 0; t < nt; ++t) {
-                plan.tile_val_off[t0 + t] = (uint32_t)off;
+            for (uint32_t q = 0; q < nt * (uint32_t)NW; ++q) {
+                plan.tile_val_off[(size_t)t0 * NW + q] = (uint32_t)off;
                 uint32_t c = 0;
-                for (int q = 0; q < 4; ++q) c += (uint32_t)popc64(plan.tile_mask[(size_t)(t0 + t) * 4 + q]);
+                for (int j = 0; j < 4; ++j) c += (uint32_t)popc64(plan.tile_mask[((size_t)t0 * NW + q) * 4 + j]);
                 off += round_up4(c);
             }
             // values: position = (entries of lower lanes) + (entries of this lane in lower words)
             for (size_t i = 0; i < ent.size(); ++i) {
-                const uint32_t t = ucol[i] / kK, k = ucol[i] % kK, r = (uint32_t)(ent[i].key & 15);
-                const uint32_t lane = (k >> 2) * 16 + r, word = k & 3;
-                const uint64_t* m = &plan.tile_mask[(size_t)(t0 + t) * 4];
+                const uint32_t t = ucol[i] / kK, k = ucol[i] % kK, r = (uint32_t)(ent[i].key & 63);
+                const uint32_t lane = (k >> 2) * 16 + (r & 15), word = k & 3;
+                const size_t sub = (size_t)(t0 + t) * NW + (r >> 4);
+                const uint64_t* m = &plan.tile_mask[sub * 4];
                 const uint64_t below = lane ? (~0ull >> (64 - lane)) : 0ull;
                 uint32_t pos = 0;
                 for (uint32_t q = 0; q < 4; ++q) pos += (uint32_t)popc64(m[q] & below);
                 for (uint32_t q = 0; q < word; ++q) pos += (uint32_t)((m[q] >> lane) & 1ull);
-                plan.tile_val[plan.tile_val_off[t0 + t] + pos] = ent[i].val;
+                plan.tile_val[plan.tile_val_off[sub] + pos] = ent[i].val;
             }
         }
     });
-    plan.tile_val_off[n_tiles] = (uint32_t)win_val_off[n_win];
+    plan.tile_val_off[(size_t)n_tiles * NW] = (uint32_t)win_val_off[n_win];
     int64_t nnz_tile = 0;
     for (int64_t w = 0; w < n_win; ++w) nnz_tile += win_nnz[w];
 
@@ -370,13 +409,13 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         for (uint32_t p = 0; p < parts; ++p) {
             const uint32_t b = t0 + (uint32_t)((uint64_t)nt * p / parts);
             const uint32_t e = t0 + (uint32_t)((uint64_t)nt * (p + 1) / parts);
-            plan.tile_item.insert(plan.tile_item.end(), {(uint32_t)w, b, e, (uint32_t)(slots + (int64_t)p * kW)});
+            plan.tile_item.insert(plan.tile_item.end(), {(uint32_t)w, b, e, (uint32_t)(slots + (int64_t)p * W)});
         }
-        for (int r = 0; r < kW; ++r) {
-            const int32_t row = part.win_row[w * kW + r];
-            if (row >= 0) plan.combine.insert(plan.combine.end(), {(uint32_t)row, (uint32_t)(slots + r), parts, (uint32_t)kW});
+        for (int r = 0; r < W; ++r) {
+            const int32_t row = part.win_row[w * W + r];
+            if (row >= 0) plan.combine.insert(plan.combine.end(), {(uint32_t)row, (uint32_t)(slots + r), parts, (uint32_t)W});
         }
-        slots += (int64_t)parts * kW;
+        slots += (int64_t)parts * W;
     }
     const int64_t n_tile_combine = (int64_t)plan.combine.size() / 4;
     {
@@ -645,20 +684,22 @@ int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t*
     std::vector<Ent> ent;
     ent.reserve((size_t)p.nnz);
     // dense-fragment part
-    const int64_t n_win = (int64_t)p.win_row.size() / kW;
+    const int W = p.geo.win_rows, NW = p.geo.nw;
+    const int64_t n_win = (int64_t)p.win_row.size() / W;
     for (int64_t w = 0; w < n_win; ++w) {
-        for (uint32_t t = p.win_tile_off[w]; t < p.win_tile_off[w + 1]; ++t) {
-            const uint64_t* m = &p.tile_mask[(size_t)t * 4];
-            uint32_t pos = p.tile_val_off[t];
-            for (int lane = 0; lane < 64; ++lane)
-                for (int word = 0; word < 4; ++word)
-                    if ((m[word] >> lane) & 1ull) {
-                        const int r = lane & 15, k = (lane >> 4) * 4 + word;
-                        const int32_t row = p.win_row[(size_t)w * kW + r];
-                        if (row < 0) return RSH_ERR_INVALID_CSR;
-                        ent.push_back({row, p.tile_colid[(size_t)t * kK + k], p.tile_val[pos++], 0});
-                    }
-        }
+        for (uint32_t t = p.win_tile_off[w]; t < p.win_tile_off[w + 1]; ++t)
+            for (int sw = 0; sw < NW; ++sw) {
+                const uint64_t* m = &p.tile_mask[((size_t)t * NW + sw) * 4];
+                uint32_t pos = p.tile_val_off[(size_t)t * NW + sw];
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int word = 0; word < 4; ++word)
+                        if ((m[word] >> lane) & 1ull) {
+                            const int r = sw * 16 + (lane & 15), k = (lane >> 4) * 4 + word;
+                            const int32_t row = p.win_row[(size_t)w * W + r];
+                            if (row < 0) return RSH_ERR_INVALID_CSR;
+                            ent.push_back({row, p.tile_colid[(size_t)t * kK + k], p.tile_val[pos++], 0});
+                        }
+            }
     }
     // irregular part: a scratch slot belongs to the row named by its combine entry
     std::vector<int32_t> slot_row((size_t)p.n_scratch_slots, -1);

@@ -11,7 +11,7 @@
 //     column, the 64 candidates sharing most feature columns are scored;
 //   * the tree is the maximum-affinity spanning forest (Kruskal on cost 1 - sim, ties by
 //     row ids); components are visited by smallest row id, children by decreasing affinity;
-//   * 2-opt = segment reversals inside blocks of 16 consecutive positions (even blocks,
+//   * 2-opt = segment reversals inside blocks of window_rows consecutive positions (even blocks,
 //     then odd blocks, so that blocks handled concurrently never share a boundary row);
 //   * a row is isolated when its affinity to both neighbours in the order is below 0.05;
 //     it moves behind its most similar kNN neighbour that is not isolated, else to the tail;
@@ -267,18 +267,19 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
         }
     }
 
-    // ---- step IV a: 2-opt inside blocks of kW positions -----------------------------------------
+    // ---- step IV a: 2-opt inside blocks of window_rows positions -----------------------------------------
     const int64_t m = (int64_t)seq.size();
     auto dist = [&](int64_t i, int64_t j) -> double {   // positions; out-of-range = no edge
         if (i < 0 || j < 0 || i >= m || j >= m) return 0.0;
         return 1.0 - sim(seq[(size_t)i], seq[(size_t)j]);
     };
-    const int64_t n_blocks = (m + kW - 1) / kW;
+    const int64_t BW = o.window_rows;   // 2-opt works inside each prospective window
+    const int64_t n_blocks = (m + BW - 1) / BW;
     for (int parity = 0; parity < 2; ++parity) {
         const int64_t cnt = (n_blocks - parity + 1) / 2;
         parallel_chunks(cnt, threads, [&](int64_t b, int64_t e, int) {
             for (int64_t h = b; h < e; ++h) {
-                const int64_t s = (2 * h + parity) * kW, t = std::min(m, s + kW);
+                const int64_t s = (2 * h + parity) * BW, t = std::min(m, s + BW);
                 for (int sweep = 0; sweep < kTwoOptSweeps; ++sweep) {
                     bool improved = false;
                     for (int64_t i = s; i < t - 1; ++i)

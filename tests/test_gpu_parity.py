@@ -50,6 +50,9 @@ def assert_parity(C_gpu, C_ref, S, what=""):
 OPTION_SETS = {
     "hybrid": dict(),
     "no_reorder": dict(reorder=0),
+    "w64": dict(window_rows=64),
+    "w64_all_tile": dict(window_rows=64, force_path=2, max_tiles_per_item=5),
+    "w32_all_tile": dict(window_rows=32, force_path=2),
     "all_irregular": dict(force_path=1),
     "all_tile": dict(force_path=2),
     "alg1_literal": dict(partition=0),
@@ -72,7 +75,7 @@ def test_reduced_configs_all_routings(k, mode):
 
 
 @pytest.mark.parametrize("N", [16, 32, 48, 64, 96, 128, 256, 512, 1024])
-@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile"])
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "w64_all_tile", "w32_all_tile"])
 def test_feature_widths(N, mode):
     A, _, _ = make_config(3, small=True)
     B = dense_B(A.n_cols, N, "normal", seed=N)
@@ -110,7 +113,8 @@ def edge_matrices():
     return out
 
 
-@pytest.mark.parametrize("mode", ["hybrid", "no_reorder", "all_irregular", "all_tile", "alg1_literal", "tiny_items", "tiny_slices"])
+@pytest.mark.parametrize("mode", ["hybrid", "no_reorder", "all_irregular", "all_tile", "alg1_literal", "tiny_items", "tiny_slices",
+                                  "w64_all_tile", "w32_all_tile"])
 @pytest.mark.parametrize("name", list(edge_matrices()))
 def test_edge_cases(name, mode):
     A = edge_matrices()[name]

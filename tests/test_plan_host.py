@@ -15,6 +15,8 @@ B_ = binding
 
 MODES = {
     "hybrid": dict(),
+    "w64": dict(window_rows=64),
+    "w32_all_tile": dict(window_rows=32, force_path=2, max_tiles_per_item=3),
     "all_irregular": dict(force_path=1),
     "all_tile": dict(force_path=2),
     "alg1_literal": dict(partition=0),
@@ -64,7 +66,7 @@ def test_decode_is_bit_exact_and_paths_are_disjoint(k, mode):
         assert st["nnz_irregular"] == 0
 
 
-@pytest.mark.parametrize("mode", ["hybrid", "alg1_literal", "tiny_items", "tiny_slices"])
+@pytest.mark.parametrize("mode", ["hybrid", "alg1_literal", "tiny_items", "tiny_slices", "w64", "w32_all_tile"])
 @pytest.mark.parametrize("k", [2, 4, 5])
 def test_independent_reader_rebuilds_A_from_raw_arrays(k, mode):
     A, N, _ = make_config(k, small=True)
@@ -75,7 +77,8 @@ def test_independent_reader_rebuilds_A_from_raw_arrays(k, mode):
     st = p.stats()
     rows, cols, vals, paths = rstile.entries_from_arrays(
         a["WIN_ROW"], a["WIN_TILE_OFF"], a["TILE_COLID"], a["TILE_MASK"], a["TILE_VAL_OFF"], a["TILE_VAL"],
-        a["IRR_COL"], a["IRR_VAL"], a["IRR_WAVE"], a["IRR_ROW"], a["COMBINE"], st["n_scratch_slots"])
+        a["IRR_COL"], a["IRR_VAL"], a["IRR_WAVE"], a["IRR_ROW"], a["COMBINE"], st["n_scratch_slots"],
+        window_rows=MODES[mode].get("window_rows", 16))
     assert rows.size == A.nnz           # every stored entry once ...
     row_ptr, col_idx, val, _ = rstile.csr_from_entries(rows, cols, vals, paths, A.n_rows, A.n_cols)  # ... and only once
     assert np.array_equal(row_ptr, A.row_ptr)
@@ -90,7 +93,9 @@ def test_plan_structure_invariants(k, mode):
     p = host_plan(A, N, **MODES[mode])
     a, st = arrays_of(p), p.stats()
     n_win, n_tiles = st["n_windows"], st["n_tiles"]
-    win_row = a["WIN_ROW"].reshape(n_win, 16)
+    W = MODES[mode].get("window_rows", 16)
+    NW = W // 16
+    win_row = a["WIN_ROW"].reshape(n_win, W)
     # rows: windows + irregular + empty partition the row set
     in_win = win_row[win_row >= 0]
     waves = a["IRR_WAVE"].reshape(-1, 4)
@@ -106,7 +111,7 @@ def test_plan_structure_invariants(k, mode):
     # fragments: offsets, bitmap popcounts, padding
     off = a["WIN_TILE_OFF"]
     assert off[0] == 0 and off[-1] == n_tiles and np.all(np.diff(off.astype(np.int64)) >= 0)
-    mask = a["TILE_MASK"].reshape(n_tiles, 4)
+    mask = a["TILE_MASK"].reshape(n_tiles * NW, 4)
     pop = np.array([[bin(int(x)).count("1") for x in row] for row in mask]).sum(axis=1) if n_tiles else np.zeros(0, int)
     voff = a["TILE_VAL_OFF"].astype(np.int64)
     assert np.all(voff % 4 == 0)
@@ -126,13 +131,14 @@ def test_plan_structure_invariants(k, mode):
         last = off[w + 1] - 1
         first_pad = n_u - 16 * (off[w + 1] - off[w] - 1)
         for k in range(first_pad, 16):
-            word = int(mask[last, k % 4])
-            assert (word >> ((k // 4) * 16)) & 0xFFFF == 0
+            for sw in range(NW):
+                word = int(mask[last * NW + sw, k % 4])
+                assert (word >> ((k // 4) * 16)) & 0xFFFF == 0
         # absent rows carry no bits
         for r in np.nonzero(win_row[w] < 0)[0]:
             for t in range(off[w], off[w + 1]):
-                for word in mask[t]:
-                    assert all(((int(word) >> (g * 16 + int(r))) & 1) == 0 for g in range(4))
+                for word in mask[t * NW + int(r) // 16]:
+                    assert all(((int(word) >> (g * 16 + int(r) % 16)) & 1) == 0 for g in range(4))
     # tile items cover each window's fragments exactly once, in order
     items = a["TILE_ITEM"].reshape(-1, 4)
     assert items.shape[0] == st["n_tile_items"]
@@ -169,7 +175,7 @@ def test_plan_structure_invariants(k, mode):
     produced = []
     for w, b, e, dst in items:
         if dst != 0xFFFFFFFF:
-            produced.extend(range(int(dst), int(dst) + 16))
+            produced.extend(range(int(dst), int(dst) + W))
     produced.extend(int(x) for x in waves[(kind == 1) & ((waves[:, 3] & 4) != 0)][:, 2])
     consumed = []
     for row, first, parts, stride in comb:
@@ -187,15 +193,16 @@ def test_plan_structure_invariants(k, mode):
 def test_alg1_literal_matches_the_python_oracle(k):
     A, N, _ = make_config(k, small=True)
     for tau_nnz, tau_inc in [(-1, -1), (0, 2), (3, 1), (6, 4)]:
-        p = host_plan(A, N, partition=0, reorder=0, tau_nnz=tau_nnz, tau_inc=tau_inc)
+        W = 16 if tau_inc != 1 else 32
+        p = host_plan(A, N, partition=0, reorder=0, tau_nnz=tau_nnz, tau_inc=tau_inc, window_rows=W)
         st = p.stats()
         if tau_nnz < 0:
             assert (st["tau_nnz"], st["tau_inc"]) == opart.estimate_threshold(A.n_rows, A.nnz)
-        wins, res = opart.partition_rows(A.row_ptr, A.col_idx, 16, st["tau_nnz"], st["tau_inc"])
-        win_row = p.array(B_.RSH_ARR_WIN_ROW).reshape(-1, 16)
+        wins, res = opart.partition_rows(A.row_ptr, A.col_idx, W, st["tau_nnz"], st["tau_inc"])
+        win_row = p.array(B_.RSH_ARR_WIN_ROW).reshape(-1, W)
         assert win_row[:, 0].tolist() == wins
         for s, rows in zip(wins, win_row):
-            want = [r if r < A.n_rows else -1 for r in range(s, s + 16)]
+            want = [r if r < A.n_rows else -1 for r in range(s, s + W)]
             assert rows.tolist() == want
         waves = p.array(B_.RSH_ARR_IRR_WAVE).reshape(-1, 4)
         irr_row = p.array(B_.RSH_ARR_IRR_ROW)
@@ -254,7 +261,7 @@ def test_abi_error_codes():
     assert create(bad, ci, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR
     bad = rp.copy(); bad[-1] -= 1
     assert create(bad, ci, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR
-    o2 = binding.rsh_plan_opts_default(); o2.upload = 0; o2.window_rows = 8
+    o2 = binding.rsh_plan_opts_default(); o2.upload = 0; o2.window_rows = 48
     assert create(rp, ci, v, A.n_rows, A.n_cols, o=o2) == B_.RSH_ERR_BAD_OPTION
     o3 = binding.rsh_plan_opts_default(); o3.upload = 0; o3.alpha = 0.0
     assert create(rp, ci, v, A.n_rows, A.n_cols, o=o3) == B_.RSH_ERR_BAD_OPTION
