@@ -61,27 +61,27 @@ union Pack16 {
 //                butterfly over the teams; the sum goes to C or to a scratch slot;
 //   zero rows  : rows without stored entries are cleared.
 // ---------------------------------------------------------------------------
-template <int TPR>
+template <int TPR, int U>
 __device__ __forceinline__ void gather_fma(const __half* __restrict__ Bp, int N, int my_col, float my_val,
                                            int team_base, int j0, int nb, float (&acc)[8]) {
-    Pack16 b[8];
-    float v[8];
+    Pack16 b[U];
+    float v[U];
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < U; ++u)
         if (u < nb) {
             const int c = shfl_i32(my_col, team_base + j0 + u);
             v[u] = shfl_f32(my_val, team_base + j0 + u);
             b[u].u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
         }
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < U; ++u)
         if (u < nb) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = fmaf(v[u], __half2float(b[u].h[i]), acc[i]);
         }
 }
 
-template <int TPR>
+template <int TPR, int U>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
     const uint4* __restrict__ waves, XcdSplit xs,
     const int32_t* __restrict__ irr_row, const int32_t* __restrict__ irr_col,
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
             nxt_val = p < len ? __half2float(__ushort_as_half(irr_val[pb + p])) : 0.f;
         }
         const int steps = (int)min((uint32_t)TPR, max_len - base);
-        for (int j0 = 0; j0 < steps; j0 += 8) gather_fma<TPR>(Bp, N, my_col, my_val, team_base, j0, min(8, steps - j0), acc);
+        for (int j0 = 0; j0 < steps; j0 += U) gather_fma<TPR, U>(Bp, N, my_col, my_val, team_base, j0, min(U, steps - j0), acc);
     }
 #pragma unroll
     for (int off = TPR; off < 64; off <<= 1)
@@ -451,7 +451,8 @@ static inline uint32_t grid_for(const XcdSplit& xs) {
 template <int TPR>
 static void launch_irregular_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
     dim3 grid(grid_for(d.irr_split), (unsigned)(d.geo.N / d.geo.irr_panel));
-    hipLaunchKernelGGL(rsh_irregular_kernel<TPR>, grid, dim3(64 * kWavesPerBlock), 0, st,
+    // up to eight B-row loads in flight per team (4 and 8 measure the same, 16 spills)
+    hipLaunchKernelGGL((rsh_irregular_kernel<TPR, (TPR >= 8 ? 8 : TPR)>), grid, dim3(64 * kWavesPerBlock), 0, st,
                        (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, (float*)C,
                        d.scratch, d.geo.N);
 }
