@@ -176,3 +176,70 @@ def test_full_size_configs_on_sampled_rows(k):
     st = plan.stats()
     print(f"  max err/S = {ratio:.2e} nnz_tile={st['nnz_tile']} nnz_irregular={st['nnz_irregular']}", flush=True)
     plan.destroy()
+
+
+def test_streams_plan_reuse_and_argument_errors():
+    """A plan is reused with different B operands, on a non-default stream, next to a second
+    plan; bad device arguments are refused before anything is launched."""
+    import ctypes
+    torch = _torch()
+    from paper_2603_08734_amd import Plan, binding
+    A1, N1, d1 = make_config(2, small=True)
+    A2, N2, d2 = make_config(5, small=True)
+    p1 = Plan(A1.row_ptr, A1.col_idx, A1.val, A1.n_cols, N1)
+    p2 = Plan(A2.row_ptr, A2.col_idx, A2.val, A2.n_cols, N2)
+    stream = torch.cuda.Stream()
+    results = []
+    with torch.cuda.stream(stream):
+        for seed in (1, 2, 3):
+            B1 = dense_B(A1.n_cols, N1, d1, seed=seed)
+            B2 = dense_B(A2.n_cols, N2, d2, seed=seed + 10)
+            B1d = torch.from_numpy(B1.view(np.int16)).cuda().view(torch.float16)
+            B2d = torch.from_numpy(B2.view(np.int16)).cuda().view(torch.float16)
+            C1 = torch.full((A1.n_rows, N1), float("nan"), dtype=torch.float32, device="cuda")
+            C2 = torch.full((A2.n_rows, N2), float("nan"), dtype=torch.float32, device="cuda")
+            p1.spmm(B1d, C1, stream=stream.cuda_stream)
+            p2.spmm(B2d, C2, stream=stream.cuda_stream)
+            results.append((B1, B2, C1, C2))
+    stream.synchronize()
+    for B1, B2, C1, C2 in results:
+        R1, S1, _ = oracle.spmm(A1.row_ptr, A1.col_idx, A1.val, B1)
+        R2, S2, _ = oracle.spmm(A2.row_ptr, A2.col_idx, A2.val, B2)
+        assert_parity(C1.cpu().numpy(), R1, S1, "plan 1 reuse")
+        assert_parity(C2.cpu().numpy(), R2, S2, "plan 2 reuse")
+    L = binding.lib()
+    B1d = torch.zeros((A1.n_cols, N1), dtype=torch.float16, device="cuda")
+    C1 = torch.zeros((A1.n_rows, N1), dtype=torch.float32, device="cuda")
+    vp = ctypes.c_void_p
+    assert L.rsh_spmm(p1._h, vp(B1d.data_ptr() + 2), vp(C1.data_ptr()), None) == binding.RSH_ERR_BAD_OPTION
+    assert L.rsh_spmm(p1._h, vp(B1d.data_ptr()), None, None) == binding.RSH_ERR_NULL
+    assert L.rsh_spmm(p1._h, None, vp(C1.data_ptr()), None) == binding.RSH_ERR_NULL
+    t = p1.spmm_profile(B1d, C1)
+    assert t["irregular"] > 0 and np.all(C1.cpu().numpy() == 0)      # B = 0 gives C = 0 exactly
+    p1.destroy()
+    p2.destroy()
+
+
+def test_random_matrices_with_random_options():
+    """40 seeded random matrices (mixed densities, a hub row, empty rows) under random plan options."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        n_rows, n_cols = int(rng.integers(1, 300)), int(rng.integers(1, 400))
+        density = float(rng.choice([0.005, 0.03, 0.15, 0.5]))
+        mask = rng.random((n_rows, n_cols)) < density
+        if n_rows > 3:
+            mask[rng.integers(0, n_rows)] = rng.random(n_cols) < 0.9
+            mask[rng.integers(0, n_rows)] = False
+        r, c = np.nonzero(mask)
+        A = from_coo(r, c, rng.standard_normal(r.size), n_rows, n_cols)
+        N = int(rng.choice([16, 32, 64, 80, 128, 256]))
+        opts = dict(window_rows=int(rng.choice([16, 32, 64])), partition=int(rng.integers(0, 2)),
+                    reorder=int(rng.integers(0, 2)), force_path=int(rng.choice([0, 0, 1, 2])),
+                    max_tiles_per_item=int(rng.choice([0, 1, 4])), max_nnz_per_slice=int(rng.choice([0, 20, 70])),
+                    xcd_partition_nnz=int(rng.choice([0, -1, 30])), hub_windows=int(rng.integers(0, 2)),
+                    long_row_nnz=int(rng.choice([0, 10])), min_reuse=float(rng.choice([0.0, 1.25, 2.5])))
+        B = dense_B(n_cols, N, "normal", seed=case)
+        print(f"case random={case} shape=({n_rows},{n_cols}) nnz={A.nnz} N={N} opts={opts}", flush=True)
+        (C,), _ = gpu_spmm(A, B, N, **opts)
+        C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+        assert_parity(C, C_ref, S, f"random case {case}")
