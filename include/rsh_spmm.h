@@ -67,7 +67,7 @@ typedef struct {
     int32_t knn_k;        /* neighbours kept per row in the kNN graph (Algorithm 3, step II)     */
     float alpha;          /* exponent of the column weight w_j = d_j^-alpha (Section 3.4)        */
     int32_t max_tiles_per_item; /* bound on fragments per tile work item; 0 = auto              */
-    int32_t max_nnz_per_slice;  /* bound on stored entries per wave slice of a long row; 0 = auto */
+    int32_t max_nnz_per_slice;  /* bound on stored entries per wave slice of a long row; 0 = auto (512) */
     int32_t force_path;   /* 0 = hybrid, 1 = every row on the irregular path, 2 = every non-empty
                              row in a window (tests compare the three)                          */
     float min_reuse;      /* partition == 1: dissolve windows with nnz/|U| below this           */
@@ -77,7 +77,7 @@ typedef struct {
                              to the irregular path                                                 */
     int32_t xcd_partition_nnz; /* irregular rows with at least this many entries are cut by column group,
                              one group per XCD, so that each XCD gathers one eighth of B's columns for
-                             them; 0 = auto (512), negative = off                                 */
+                             them; 0 = auto (256), negative = off                                 */
     int32_t upload;       /* 1 = copy the plan to the current HIP device; 0 = host-only plan    */
     int32_t threads;      /* host threads used for planning; 0 = all available                  */
 } rsh_plan_opts_t;

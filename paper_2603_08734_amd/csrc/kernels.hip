@@ -61,27 +61,92 @@ union Pack16 {
 //                butterfly over the teams; the sum goes to C or to a scratch slot;
 //   zero rows  : rows without stored entries are cleared.
 // ---------------------------------------------------------------------------
-template <int TPR, int U>
-__device__ __forceinline__ void gather_fma(const __half* __restrict__ Bp, int N, int my_col, float my_val,
-                                           int team_base, int j0, int nb, float (&acc)[8]) {
-    Pack16 b[U];
+// One group of U gather steps of a team: entries team_base+j0 .. +U-1 of the (column, value)
+// pairs held by the team's lanes.  Straight-line code on purpose: all U row loads are issued
+// back to back and only then consumed (a branch between two loads makes the compiler wait for
+// the first before it issues the second).
+template <int U>
+__device__ __forceinline__ void gather_group(const __half* __restrict__ Bp, int N, int my_col, float my_val,
+                                             int src_lane0, float (&acc)[8]) {
+    uint4_t b[U];
     float v[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-        if (u < nb) {
-            const int c = shfl_i32(my_col, team_base + j0 + u);
-            v[u] = shfl_f32(my_val, team_base + j0 + u);
-            b[u].u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
-        }
+    for (int u = 0; u < U; ++u) {
+        const int c = shfl_i32(my_col, src_lane0 + u);
+        v[u] = shfl_f32(my_val, src_lane0 + u);
+        b[u] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N);
+    }
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-        if (u < nb) {
+    for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = fmaf(v[u], __half2float(b[u].h[i]), acc[i]);
+        for (int q = 0; q < 4; ++q) {
+            const unsigned int w = b[u][q];   // copy first: bit_cast of a vector element lvalue reads element 0
+            const __half2 h2 = __builtin_bit_cast(__half2, w);
+            acc[2 * q] = fmaf(v[u], __low2float(h2), acc[2 * q]);
+            acc[2 * q + 1] = fmaf(v[u], __high2float(h2), acc[2 * q + 1]);
         }
+    }
 }
 
-template <int TPR, int U>
+// Short-row variant of a group: the same U back-to-back loads, but a row of C is stored
+// whenever L steps have been consumed (the step counter is uniform over the wave).
+struct ShortRowState {
+    float* C;
+    int N, feat, L, k, rq;
+};
+
+template <int U>
+__device__ __forceinline__ void short_rows_group(const __half* __restrict__ Bp, int my_col, float my_val, int my_row,
+                                                 int team_base, int j0, float (&acc)[8], ShortRowState& st) {
+    uint4_t b[U];
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int c = shfl_i32(my_col, team_base + j0 + u);
+        v[u] = shfl_f32(my_val, team_base + j0 + u);
+        b[u] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * st.N);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned int w = b[u][q];   // copy first: bit_cast of a vector element lvalue reads element 0
+            const __half2 h2 = __builtin_bit_cast(__half2, w);
+            acc[2 * q] = fmaf(v[u], __low2float(h2), acc[2 * q]);
+            acc[2 * q + 1] = fmaf(v[u], __high2float(h2), acc[2 * q + 1]);
+        }
+        if (++st.k == st.L) {
+            st.k = 0;
+            const int row = shfl_i32(my_row, team_base + st.rq);
+            ++st.rq;
+            if (row >= 0) {
+                float* out = st.C + (size_t)row * st.N + st.feat;
+                *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+        }
+    }
+}
+
+// `steps` gather steps starting at entry j0, as groups of 8, 4, 2, 1.
+__device__ __forceinline__ void gather_steps(const __half* __restrict__ Bp, int N, int my_col, float my_val,
+                                             int team_base, int steps, float (&acc)[8]) {
+    int j = 0;
+    for (; j + 8 <= steps; j += 8) gather_group<8>(Bp, N, my_col, my_val, team_base + j, acc);
+    if (steps & 4) {
+        gather_group<4>(Bp, N, my_col, my_val, team_base + j, acc);
+        j += 4;
+    }
+    if (steps & 2) {
+        gather_group<2>(Bp, N, my_col, my_val, team_base + j, acc);
+        j += 2;
+    }
+    if (steps & 1) gather_group<1>(Bp, N, my_col, my_val, team_base + j, acc);
+}
+
+template <int TPR>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
     const uint4* __restrict__ waves, XcdSplit xs,
     const int32_t* __restrict__ irr_row, const int32_t* __restrict__ irr_col,
@@ -122,38 +187,21 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
         const int my_col = tl < n_mine ? irr_col[p0 + tl] : 0;
         const float my_val = tl < n_mine ? __half2float(__ushort_as_half(irr_val[p0 + tl])) : 0.f;
         const int my_row = tl < n_rows_mine ? irr_row[dst + q0 + tl] : -1;
+        // R rows of L entries back to back: the loads of up to eight steps are in flight together,
+        // whatever rows they belong to; after every L consumed steps a row is complete and stored
+        ShortRowState st{C, N, feat, L, 0, 0};
         const int steps = R * L;
-        int k = 0, rq = 0;
-        for (int j0 = 0; j0 < steps; j0 += 8) {
-            const int nb = min(8, steps - j0);
-            Pack16 b[8];
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (u < nb) {
-                    const int c = shfl_i32(my_col, team_base + j0 + u);
-                    v[u] = shfl_f32(my_val, team_base + j0 + u);
-                    b[u].u = *reinterpret_cast<const uint4*>(Bp + (size_t)c * N);
-                }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (u < nb) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[i] = fmaf(v[u], __half2float(b[u].h[i]), acc[i]);
-                    if (++k == L) {   // a row is complete (same step for every team of the wave)
-                        k = 0;
-                        const int row = shfl_i32(my_row, team_base + rq);
-                        ++rq;
-                        if (row >= 0) {
-                            float* out = C + (size_t)row * N + feat;
-                            *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-                            *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-                        }
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-                    }
-                }
+        int j = 0;
+        for (; j + 8 <= steps; j += 8) short_rows_group<8>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+        if (steps & 4) {
+            short_rows_group<4>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+            j += 4;
         }
+        if (steps & 2) {
+            short_rows_group<2>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+            j += 2;
+        }
+        if (steps & 1) short_rows_group<1>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
         return;
     }
 
@@ -173,7 +221,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
             nxt_val = p < len ? __half2float(__ushort_as_half(irr_val[pb + p])) : 0.f;
         }
         const int steps = (int)min((uint32_t)TPR, max_len - base);
-        for (int j0 = 0; j0 < steps; j0 += U) gather_fma<TPR, U>(Bp, N, my_col, my_val, team_base, j0, min(U, steps - j0), acc);
+        gather_steps(Bp, N, my_col, my_val, team_base, steps, acc);
     }
 #pragma unroll
     for (int off = TPR; off < 64; off <<= 1)
@@ -451,8 +499,7 @@ static inline uint32_t grid_for(const XcdSplit& xs) {
 template <int TPR>
 static void launch_irregular_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
     dim3 grid(grid_for(d.irr_split), (unsigned)(d.geo.N / d.geo.irr_panel));
-    // up to eight B-row loads in flight per team (4 and 8 measure the same, 16 spills)
-    hipLaunchKernelGGL((rsh_irregular_kernel<TPR, (TPR >= 8 ? 8 : TPR)>), grid, dim3(64 * kWavesPerBlock), 0, st,
+    hipLaunchKernelGGL(rsh_irregular_kernel<TPR>, grid, dim3(64 * kWavesPerBlock), 0, st,
                        (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, (float*)C,
                        d.scratch, d.geo.N);
 }

@@ -429,7 +429,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     // rows grouped by exact length, longest first, so that every wave of the short-row kind
     // runs rows of one length and its teams stay in lock step.
     const int G = geo.irr_teams, TPR = geo.irr_tpr;
-    const int64_t slice_max = plan.opts.max_nnz_per_slice > 0 ? plan.opts.max_nnz_per_slice : 256;
+    const int64_t slice_max = plan.opts.max_nnz_per_slice > 0 ? plan.opts.max_nnz_per_slice : 512;
     const int64_t n_irr = (int64_t)part.irregular.size();
     std::vector<std::vector<int32_t>> by_len((size_t)TPR + 1);   // by_len[L] = short rows with L entries
     std::vector<int32_t> long_rows;
@@ -454,7 +454,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     // the piece of group g is scheduled on XCD g.  An XCD then gathers only its eighth of the
     // columns of B for this part of the work, which shortens the reuse distance of hot B rows
     // eightfold.  The pieces are partial sums that the combine pass adds up.
-    const int64_t xp_min = plan.opts.xcd_partition_nnz == 0 ? 512 : plan.opts.xcd_partition_nnz;
+    const int64_t xp_min = plan.opts.xcd_partition_nnz == 0 ? 256 : plan.opts.xcd_partition_nnz;
     const int64_t n_long = (int64_t)long_rows.size();
     std::vector<uint8_t> col_group;
     bool any_partitioned = false;

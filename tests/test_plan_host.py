@@ -288,7 +288,7 @@ def test_long_rows_are_split_into_bounded_slices_and_windows_into_bounded_items(
     st = p.stats()
     assert st["n_split_rows"] == 1 and st["n_scratch_slots"] == 10 and st["n_combine"] == 1
     waves = p.array(B_.RSH_ARR_IRR_WAVE).reshape(-1, 4)
-    assert waves[(waves[:, 3] & 3) == 1][:, 1].max() <= 256
+    assert waves[(waves[:, 3] & 3) == 1][:, 1].max() <= 256   # max_nnz_per_slice given above
     p2 = host_plan(A, 128, force_path=2, max_tiles_per_item=8)
     items = p2.array(B_.RSH_ARR_TILE_ITEM).reshape(-1, 4)
     assert (items[:, 2] - items[:, 1]).max() <= 8 and p2.stats()["n_split_windows"] == 1
