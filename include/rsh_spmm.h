@@ -63,7 +63,7 @@ typedef struct {
                                  first, the rest is grouped W eligible rows at a time, and a window
                                  whose column reuse nnz/|U| is below min_reuse is dissolved        */
     int32_t reorder;      /* 0 = keep the given row order, 1 (default) = locality-aware reordering
-                             (Section 3.4); the found order is used only if it lowers the objective */
+                             (Section 3.4); the found order is used only if it lowers the objective by 3 % */
     int32_t knn_k;        /* neighbours kept per row in the kNN graph (Algorithm 3, step II)     */
     float alpha;          /* exponent of the column weight w_j = d_j^-alpha (Section 3.4)        */
     int32_t max_tiles_per_item; /* bound on fragments per tile work item; 0 = auto              */
@@ -72,6 +72,9 @@ typedef struct {
                              row in a window (tests compare the three)                          */
     float min_reuse;      /* partition == 1: dissolve windows with nnz/|U| below this           */
     int32_t long_row_nnz; /* partition == 1: rows longer than this go to the irregular path; 0 = auto */
+    int32_t window_schedule; /* 1 (default) = windows are issued in breadth-first clusters of windows that
+                             read each other's rows (square matrices only), when that lowers the distinct
+                             columns per run of consecutive windows by a tenth; 0 = plan order       */
     int32_t hub_windows;  /* partition == 1: 1 = long rows are grouped among themselves, longest first, and a
                              group whose reuse reaches min_reuse becomes a window; 0 = all long rows go
                              to the irregular path                                                 */
@@ -99,6 +102,8 @@ typedef struct {
     int64_t cols_all, cols_tile, cols_irregular;   /* distinct columns referenced overall / per part */
     int64_t rows_tile, rows_irregular;         /* rows of C each kernel writes directly or via scratch */
     int32_t tau_nnz, tau_inc;                  /* thresholds actually used                       */
+    int64_t schedule_cols_given, schedule_cols_found; /* distinct columns per run of 256 consecutive windows,
+                                                  summed, in plan order and in clustered order (0 = not tried) */
     double reorder_cost_given, reorder_cost_found; /* Section 3.4 objective of the given order and of the
                                                   order the heuristic found (the lower one is used) */
     double ms_validate, ms_reorder, ms_partition, ms_pack, ms_worklist, ms_upload, ms_total;
@@ -212,6 +217,10 @@ int rsh_plan_array(const rsh_plan_t *plan, int32_t which, const void **ptr, int6
 
 /* Number of lane teams in one wave of the irregular kernel for this plan's N (64 / lanes per team). */
 int rsh_plan_teams_per_wave(const rsh_plan_t *plan, int32_t *teams);
+
+/* sizeof(rsh_plan_opts_t), sizeof(rsh_plan_stats_t) as compiled into the library, so that a
+ * binding can check its own struct declarations. */
+int rsh_struct_sizes(int32_t *opts_bytes, int32_t *stats_bytes);
 
 const char *rsh_status_string(int status);
 /* Text of the last HIP error seen by the calling thread inside this library ("" if none). */

@@ -31,7 +31,7 @@ _ARRAY_DTYPES = {
 EXPORTED_SYMBOLS = [
     "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_profile", "rsh_copy_probe", "rsh_plan_destroy", "rsh_plan_stats",
     "rsh_plan_decode", "rsh_plan_row_order", "rsh_plan_array", "rsh_plan_teams_per_wave",
-    "rsh_status_string", "rsh_last_hip_error",
+    "rsh_struct_sizes", "rsh_status_string", "rsh_last_hip_error",
 ]
 
 
@@ -46,7 +46,7 @@ class rsh_plan_opts_t(ctypes.Structure):
                 ("knn_k", ctypes.c_int32), ("alpha", ctypes.c_float), ("max_tiles_per_item", ctypes.c_int32),
                 ("max_nnz_per_slice", ctypes.c_int32), ("force_path", ctypes.c_int32),
                 ("min_reuse", ctypes.c_float), ("long_row_nnz", ctypes.c_int32),
-                ("hub_windows", ctypes.c_int32), ("xcd_partition_nnz", ctypes.c_int32), ("upload", ctypes.c_int32),
+                ("window_schedule", ctypes.c_int32), ("hub_windows", ctypes.c_int32), ("xcd_partition_nnz", ctypes.c_int32), ("upload", ctypes.c_int32),
                 ("threads", ctypes.c_int32)]
 
 
@@ -64,6 +64,7 @@ class rsh_plan_stats_t(ctypes.Structure):
                     "tile_part_bytes", "irregular_part_bytes", "cols_all", "cols_tile", "cols_irregular",
                     "rows_tile", "rows_irregular")] +
                 [("tau_nnz", ctypes.c_int32), ("tau_inc", ctypes.c_int32)] +
+                [(n, ctypes.c_int64) for n in ("schedule_cols_given", "schedule_cols_found")] +
                 [(n, ctypes.c_double) for n in ("reorder_cost_given", "reorder_cost_found", "ms_validate", "ms_reorder", "ms_partition", "ms_pack",
                                                 "ms_worklist", "ms_upload", "ms_total")])
 
@@ -94,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.rsh_plan_row_order.argtypes = [vp, vp]
         L.rsh_plan_array.argtypes = [vp, i32, ctypes.POINTER(vp), i64p]
         L.rsh_plan_teams_per_wave.argtypes = [vp, ctypes.POINTER(i32)]
+        L.rsh_struct_sizes.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.rsh_status_string.argtypes = [ctypes.c_int]
         L.rsh_status_string.restype = ctypes.c_char_p
         L.rsh_last_hip_error.argtypes = []
@@ -101,6 +103,10 @@ def lib() -> ctypes.CDLL:
         for name in EXPORTED_SYMBOLS:
             if name not in ("rsh_status_string", "rsh_last_hip_error"):
                 getattr(L, name).restype = ctypes.c_int
+        a, b = i32(), i32()
+        L.rsh_struct_sizes(ctypes.byref(a), ctypes.byref(b))
+        if (a.value, b.value) != (ctypes.sizeof(rsh_plan_opts_t), ctypes.sizeof(rsh_plan_stats_t)):
+            raise ImportError("librsh.so was built from a different rsh_spmm.h than this binding describes")
         _lib = L
     return _lib
 

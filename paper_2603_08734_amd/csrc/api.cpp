@@ -98,6 +98,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->force_path = 0;
     o->min_reuse = 1.25f;
     o->long_row_nnz = 0;
+    o->window_schedule = 1;
     o->hub_windows = 0;
     o->xcd_partition_nnz = 0;
     o->upload = 1;
@@ -297,6 +298,13 @@ int rsh_plan_array(const rsh_plan_t* plan, int32_t which, const void** ptr, int6
 int rsh_plan_teams_per_wave(const rsh_plan_t* plan, int32_t* teams) {
     if (!plan || !teams) return RSH_ERR_NULL;
     *teams = plan->host.geo.irr_teams;
+    return RSH_OK;
+}
+
+int rsh_struct_sizes(int32_t* opts_bytes, int32_t* stats_bytes) {
+    if (!opts_bytes || !stats_bytes) return RSH_ERR_NULL;
+    *opts_bytes = (int32_t)sizeof(rsh_plan_opts_t);
+    *stats_bytes = (int32_t)sizeof(rsh_plan_stats_t);
     return RSH_OK;
 }
 

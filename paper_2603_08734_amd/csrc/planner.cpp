@@ -278,6 +278,72 @@ static void gather_window(const rsh_csr_t& a, const int32_t* rows, int W, std::v
 
 static inline int popc64(uint64_t x) { return __builtin_popcountll(x); }
 
+// Order in which windows are issued.  Windows that run at the same time on one XCD should
+// gather overlapping B rows, so that a row fetched for one is an L2 hit for the others.  For a
+// square matrix the window holding row j is a natural neighbour of every window that reads
+// column j (a mesh or graph neighbourhood); windows are therefore collected in breadth-first
+// clusters of kClusterWindows over that relation, clusters seeded in the given order.  The
+// result is kept only if it lowers the distinct columns per run of kClusterWindows consecutive
+// windows by at least a tenth (the quantity L2 has to hold); otherwise the given order stays.
+static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan& plan, int64_t n_win,
+                                             int64_t* cols_given, int64_t* cols_found) {
+    constexpr int64_t kClusterWindows = 256;
+    std::vector<int64_t> order((size_t)n_win);
+    std::iota(order.begin(), order.end(), (int64_t)0);
+    *cols_given = *cols_found = 0;
+    if (!plan.opts.window_schedule || a.n_rows != a.n_cols || n_win < 4 * kClusterWindows) return order;
+    const int W = plan.geo.win_rows;
+    std::vector<int32_t> row_win((size_t)a.n_rows, -1);
+    for (int64_t w = 0; w < n_win; ++w)
+        for (int r = 0; r < W; ++r)
+            if (plan.win_row[(size_t)(w * W + r)] >= 0) row_win[(size_t)plan.win_row[(size_t)(w * W + r)]] = (int32_t)w;
+    auto footprint = [&](const std::vector<int64_t>& ord) {
+        std::vector<int64_t> stamp((size_t)a.n_cols, -1);
+        int64_t total = 0;
+        for (int64_t i = 0; i < n_win; ++i) {
+            const int64_t chunk = i / kClusterWindows, w = ord[(size_t)i];
+            for (size_t q = (size_t)plan.win_tile_off[w] * kK; q < (size_t)plan.win_tile_off[w + 1] * kK; ++q) {
+                const int32_t c = plan.tile_colid[q];
+                if (stamp[(size_t)c] != chunk) {
+                    stamp[(size_t)c] = chunk;
+                    ++total;
+                }
+            }
+        }
+        return total;
+    };
+    std::vector<int64_t> found;
+    found.reserve((size_t)n_win);
+    std::vector<uint8_t> state((size_t)n_win, 0);   // 0 free, 1 queued, 2 placed
+    std::vector<int64_t> queue;
+    for (int64_t seed = 0; seed < n_win; ++seed) {
+        if (state[(size_t)seed] == 2) continue;
+        queue.clear();
+        queue.push_back(seed);
+        state[(size_t)seed] = 1;
+        int64_t placed = 0;
+        for (size_t head = 0; head < queue.size() && placed < kClusterWindows; ++head) {
+            const int64_t w = queue[head];
+            state[(size_t)w] = 2;
+            found.push_back(w);
+            ++placed;
+            for (size_t q = (size_t)plan.win_tile_off[w] * kK; q < (size_t)plan.win_tile_off[w + 1] * kK; ++q) {
+                const int32_t w2 = row_win[(size_t)plan.tile_colid[q]];
+                if (w2 >= 0 && state[(size_t)w2] == 0) {
+                    state[(size_t)w2] = 1;
+                    queue.push_back(w2);
+                }
+            }
+        }
+        for (int64_t w : queue)
+            if (state[(size_t)w] == 1) state[(size_t)w] = 0;   // still queued: free for later clusters
+    }
+    *cols_given = footprint(order);
+    *cols_found = footprint(found);
+    if ((int64_t)found.size() == n_win && *cols_found * 10 <= *cols_given * 9) return found;
+    return order;
+}
+
 int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads) {
     const Geometry& geo = plan.geo;
     const int W = geo.win_rows, NW = geo.nw;
@@ -397,7 +463,9 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     plan.tile_item.clear();
     plan.combine.clear();
     int64_t slots = 0, n_split_windows = 0;
-    for (int64_t w = 0; w < n_win; ++w) {
+    const std::vector<int64_t> worder = schedule_windows(a, plan, n_win, &plan.stats.schedule_cols_given, &plan.stats.schedule_cols_found);
+    for (int64_t wi = 0; wi < n_win; ++wi) {
+        const int64_t w = worder[(size_t)wi];
         const uint32_t t0 = plan.win_tile_off[w], nt = plan.win_tile_off[w + 1] - t0;
         if (nt <= (uint32_t)t_max) {
             // a window without fragments (only absent/empty rows) still zero-fills its rows

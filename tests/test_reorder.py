@@ -29,8 +29,12 @@ def test_order_is_a_bijection_and_objective_matches_the_oracle(k):
     given = osim.path_cost(A.row_ptr, A.col_idx, A.n_cols, np.arange(A.n_rows), 0.5)
     assert abs(st["reorder_cost_given"] - given) <= 1e-9 * max(1.0, given)
     used = osim.path_cost(A.row_ptr, A.col_idx, A.n_cols, order, 0.5)
-    assert abs(min(st["reorder_cost_given"], st["reorder_cost_found"]) - used) <= 1e-9 * max(1.0, used)
+    accepted = st["reorder_cost_found"] <= 0.97 * st["reorder_cost_given"]
+    want = st["reorder_cost_found"] if accepted else st["reorder_cost_given"]
+    assert abs(want - used) <= 1e-9 * max(1.0, used)
     assert used <= given + 1e-9
+    if not accepted:
+        assert np.array_equal(order, np.arange(A.n_rows))
 
 
 def test_planted_communities_are_recovered():
@@ -81,7 +85,7 @@ def test_rows_without_entries_go_last_and_decode_survives_reordering():
     A = from_coo(r, c, rng.standard_normal(r.size), 60, 30)
     p = host_plan(A, 32, reorder=1)
     st = p.stats()
-    if st["reorder_cost_found"] < st["reorder_cost_given"]:
+    if st["reorder_cost_found"] <= 0.97 * st["reorder_cost_given"]:
         assert set(p.row_order()[-3:].tolist()) == {3, 17, 40}
     row_ptr, col_idx, val, _ = p.decode()
     assert np.array_equal(row_ptr, A.row_ptr) and np.array_equal(col_idx, A.col_idx)
