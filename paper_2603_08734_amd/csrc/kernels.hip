@@ -314,7 +314,13 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
         ld_on[j] = ld_row[j] < 16;
     }
     const int m = lane & 15, kg = lane >> 4;
-    const __half* Bp = B + panel;
+    // B rows are addressed as a wave-uniform base plus a 32-bit byte offset (the plan guarantees
+    // n_cols * 2N < 2^32), which leaves the address arithmetic at one multiply-add per load
+    const char* Bbytes = reinterpret_cast<const char*>(B + panel);
+    const uint32_t row_bytes = 2u * (uint32_t)N;
+    uint32_t ld_byte[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) ld_byte[j] = 2u * (uint32_t)ld_col[j];
     const int tr_off = (4 * kg + (m >> 2)) * LDB + 4 * (m & 3);   // this lane's run for the transposing read
 
     float4_t acc[NCH];
@@ -345,7 +351,7 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 #pragma unroll
                 for (int j = 0; j < NLD; ++j) {
                     const int c = shfl_i32(colid, ld_row[j] & 15);
-                    if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N + ld_col[j]);
+                    if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
                 }
                 if ((uint32_t)lane * 4u < vend - voff) vreg[d] = *reinterpret_cast<const uint2_t*>(tile_val + voff + lane * 4);
             }
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 #pragma unroll
                         for (int j = 0; j < NLD; ++j) {
                             const int c = shfl_i32(colid_n[d], ld_row[j] & 15);
-                            if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N + ld_col[j]);
+                            if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
                         }
                         vreg[d] = (uint2_t){0u, 0u};
                         if ((uint32_t)lane * 4u < vend_n[d] - voff_n[d])
