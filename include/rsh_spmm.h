@@ -54,8 +54,11 @@ typedef struct {
 typedef struct {
     int32_t window_rows;  /* W of Algorithm 1: 16, 32 or 64.  A window is W/16 sub-windows of 16 rows (one
                              MFMA N-extent each) that share one condensed column space; the W/16 waves
-                             of a workgroup share each staged B tile                              */
-    int32_t tile_k;       /* condensed columns per fragment; 16 is the only supported value     */
+                             of a workgroup share each staged B tile.  0 (default) = choose: starting
+                             from 16, W doubles while merging neighbouring windows (a sample of them)
+                             keeps the merged windows' distinct columns within 0.6 of the sum        */
+    int32_t tile_k;       /* K, condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16) or 32
+                             (v_mfma_f32_16x16x32_f16); 0 (default) = 16 for 16-row windows, else 32 */
     int32_t tau_nnz;      /* Algorithm 1 row-length threshold; -1 = estimate from the matrix     */
     int32_t tau_inc;      /* Algorithm 1 column-gain threshold; -1 = estimate                    */
     int32_t partition;    /* 0 = Algorithm 1 exactly as printed (contiguous windows, head-row test);
@@ -102,6 +105,7 @@ typedef struct {
     int64_t cols_all, cols_tile, cols_irregular;   /* distinct columns referenced overall / per part */
     int64_t rows_tile, rows_irregular;         /* rows of C each kernel writes directly or via scratch */
     int32_t tau_nnz, tau_inc;                  /* thresholds actually used                       */
+    int32_t window_rows, tile_k;               /* W and K actually used                          */
     int64_t schedule_cols_given, schedule_cols_found; /* distinct columns per run of 256 consecutive windows,
                                                   summed, in plan order and in clustered order (0 = not tried) */
     double reorder_cost_given, reorder_cost_found; /* Section 3.4 objective of the given order and of the
@@ -174,19 +178,20 @@ int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
  * device holds).  *count is the number of elements.
  *
  * Dense-fragment part (RS-Tile "TC block part", Section 3.2).  W = window_rows, NW = W/16,
- * fragment = 16 condensed columns; fragment t has NW sub-fragments, sub-fragment s covering
- * window rows 16s .. 16s+15:
+ * K = tile_k (both as reported by rsh_plan_stats), Q = K/4; a fragment is K condensed columns;
+ * fragment t has NW sub-fragments, sub-fragment s covering window rows 16s .. 16s+15:
  *   RSH_ARR_WIN_ROW      int32  [n_windows*W]   original row id of each window row, -1 = absent
  *   RSH_ARR_WIN_TILE_OFF uint32 [n_windows+1]   prefix sum of fragments per window
- *   RSH_ARR_TILE_COLID   int32  [n_tiles*16]    original column of fragment column k; padding
+ *   RSH_ARR_TILE_COLID   int32  [n_tiles*K]     original column of fragment column k; padding
  *                                               columns repeat the last valid one
- *   RSH_ARR_TILE_MASK    uint64 [n_tiles*NW*4]  bitmap of sub-fragment (t, s) at (t*NW+s)*4: cell
+ *   RSH_ARR_TILE_MASK    uint64 [n_tiles*NW*Q]  bitmap of sub-fragment (t, s) at (t*NW+s)*Q: cell
  *                                               (row r of the sub-window, column k) is bit
- *                                               (k/4)*16 + r of word k%4; padding cells are 0
+ *                                               (k/Q)*16 + r of word k%Q (bit = MFMA lane, word =
+ *                                               the lane's operand element); padding cells are 0
  *   RSH_ARR_TILE_VAL_OFF uint32 [n_tiles*NW+1]  start of each sub-fragment's values in TILE_VAL,
- *                                               in elements, always a multiple of 4
+ *                                               in elements, always a multiple of Q
  *   RSH_ARR_TILE_VAL     uint16 []              binary16 values, per sub-fragment ordered by
- *                                               ((k/4)*16 + r, k%4) ascending; pad elements are 0
+ *                                               ((k/Q)*16 + r, k%Q) ascending; pad elements are 0
  *   RSH_ARR_TILE_ITEM    uint32 [n_items*4]     {window, first tile, end tile, dst}: dst ==
  *                                               0xffffffff -> rows of C; else first scratch slot
  *                                               of a W-slot partial block

@@ -6,11 +6,11 @@ the list of stored entries (row, column, binary16 bits, path) with plain Python 
 numpy, following only the layout documented in the public header:
 
 * a window has W = 16 * NW rows; window w owns fragments win_tile_off[w] ..
-  win_tile_off[w+1]; fragment t has 16 column ids and NW sub-fragments (rows
-  16 s .. 16 s + 15 of the window); sub-fragment (t, s) has a 256-bit map (four 64-bit
-  words at index (t * NW + s) * 4; cell (row r, column k) is bit (k // 4) * 16 + r of
-  word k % 4) and a run of values that starts at tile_val_off[t * NW + s] and is
-  ordered by ((k // 4) * 16 + r, k % 4);
+  win_tile_off[w+1]; fragment t has K (16 or 32) column ids and NW sub-fragments (rows
+  16 s .. 16 s + 15 of the window); with Q = K / 4, sub-fragment (t, s) has a 16 x K bit
+  map (Q 64-bit words at index (t * NW + s) * Q; cell (row r, column k) is bit
+  (k // Q) * 16 + r of word k % Q) and a run of values that starts at
+  tile_val_off[t * NW + s] and is ordered by ((k // Q) * 16 + r, k % Q);
 * an irregular wave (start, count, dst, info) is, by info & 3: kind 0 -- count rows
   of exactly L = (info >> 8) & 255 entries each, back to back from start, whose row
   ids are irr_row[dst .. dst+count); kind 1 -- count consecutive entries of one row,
@@ -23,25 +23,26 @@ import numpy as np
 
 
 def entries_from_arrays(win_row, win_tile_off, tile_colid, tile_mask, tile_val_off, tile_val,
-                        irr_col, irr_val, irr_wave, irr_row, combine, n_scratch_slots, window_rows=16):
+                        irr_col, irr_val, irr_wave, irr_row, combine, n_scratch_slots, window_rows=16, tile_k=16):
     rows, cols, vals, paths = [], [], [], []
     W, NW = window_rows, window_rows // 16
+    K, Q = tile_k, tile_k // 4
     n_win = len(win_row) // W
     for w in range(n_win):
         for t in range(int(win_tile_off[w]), int(win_tile_off[w + 1])):
             for s in range(NW):
                 cells = []
-                for k in range(16):
-                    word = int(tile_mask[4 * (t * NW + s) + (k % 4)])
+                for k in range(K):
+                    word = int(tile_mask[Q * (t * NW + s) + (k % Q)])
                     for r in range(16):
-                        if (word >> ((k // 4) * 16 + r)) & 1:
-                            cells.append(((k // 4) * 16 + r, k % 4, r, k))
+                        if (word >> ((k // Q) * 16 + r)) & 1:
+                            cells.append(((k // Q) * 16 + r, k % Q, r, k))
                 cells.sort()
                 for pos, (_, _, r, k) in enumerate(cells):
                     row = int(win_row[W * w + 16 * s + r])
                     assert row >= 0, "a set bit in an absent window row"
                     rows.append(row)
-                    cols.append(int(tile_colid[16 * t + k]))
+                    cols.append(int(tile_colid[K * t + k]))
                     vals.append(int(tile_val[int(tile_val_off[t * NW + s]) + pos]))
                     paths.append(0)
     slot_row = {}

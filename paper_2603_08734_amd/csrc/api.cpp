@@ -85,8 +85,8 @@ extern "C" {
 int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     if (!o) return RSH_ERR_NULL;
     std::memset(o, 0, sizeof(*o));
-    o->window_rows = rsh::kW;
-    o->tile_k = rsh::kK;
+    o->window_rows = 0;
+    o->tile_k = 0;
     o->tau_nnz = -1;
     o->tau_inc = -1;
     o->partition = 1;
@@ -113,7 +113,9 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     rsh_plan_opts_t o;
     rsh_plan_opts_default(&o);
     if (opts) o = *opts;
-    if ((o.window_rows != 16 && o.window_rows != 32 && o.window_rows != 64) || o.tile_k != rsh::kK) return RSH_ERR_BAD_OPTION;
+    if ((o.window_rows != 0 && o.window_rows != 16 && o.window_rows != 32 && o.window_rows != 64) ||
+        (o.tile_k != 0 && o.tile_k != 16 && o.tile_k != 32))
+        return RSH_ERR_BAD_OPTION;
     if (o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2) return RSH_ERR_BAD_OPTION;
     if (o.reorder < 0 || o.reorder > 1 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
@@ -134,8 +136,8 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         h.n_rows = csr->n_rows;
         h.n_cols = csr->n_cols;
         h.nnz = csr->nnz;
-        h.geo = rsh::make_geometry(N, o.window_rows);
-        h.opts = o;
+        const bool choose_w = o.window_rows == 0;
+        if (choose_w) o.window_rows = rsh::kW;   // reordering and the first partition work on 16-row windows
         std::vector<int32_t> col_deg;
         rsh::column_degrees(*csr, col_deg, threads);
         h.stats.ms_validate = ms_since(t0);
@@ -157,6 +159,13 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         if (o.tau_inc >= 0) tau_inc = o.tau_inc;
         rsh::Partition part;
         rsh::partition_rows(*csr, o, h.order, tau_nnz, tau_inc, part, threads);
+        if (choose_w) {
+            o.window_rows = rsh::choose_window_rows(*csr, part);
+            if (o.window_rows != rsh::kW) rsh::partition_rows(*csr, o, h.order, tau_nnz, tau_inc, part, threads);
+        }
+        if (o.tile_k == 0) o.tile_k = o.window_rows == rsh::kW ? 16 : 32;
+        h.geo = rsh::make_geometry(N, o.window_rows, o.tile_k);
+        h.opts = o;
         const double ms_partition = ms_since(t0);
 
         t0 = std::chrono::steady_clock::now();

@@ -9,12 +9,14 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "launch.hpp"
 
 namespace rsh {
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
@@ -256,33 +258,39 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
 // at features 16c+4s.. of staged row 4*(l/16)+r.  The LDS row stride is chosen so that
 // the 16 addresses of a group fall in distinct banks.
 // ---------------------------------------------------------------------------
-template <int NCH, int NW>
+template <int NCH, int NW, int KT>
 struct TileGeom {
     static constexpr int P = 16 * NCH;                      // features per panel
     static constexpr int TPR = P / 8;                       // lanes per B row (16 bytes each)
     static constexpr int THREADS = 64 * NW;                 // threads that share one staged B tile
-    static constexpr int NLD = (16 * TPR + THREADS - 1) / THREADS;   // 16-byte loads per thread per fragment
+    static constexpr int NLD = (KT * TPR + THREADS - 1) / THREADS;   // 16-byte loads per thread per fragment
     static constexpr int LDB = P == 16 ? 16 : (P == 32 ? 80 : P + 16);   // LDS row stride, halves
     static constexpr int ITEMS_PER_BLOCK = NW == 1 ? kWavesPerBlock : 1;
     static constexpr int NBUF = NW == 1 ? 1 : 2;            // shared tiles are double-buffered
+    static constexpr int CPL = KT / 4;                      // cells per lane = bitmap words per sub-fragment
 };
 
 // NW = sub-windows (waves) per window.  With NW == 1 a block runs four independent items,
 // one per wave, and needs no barrier (LDS operations of one wave complete in order).  With
-// NW > 1 the NW waves of a block share one item: they load the fragment's 16 B rows together,
+// NW > 1 the NW waves of a block share one item: they load the fragment's B rows together,
 // once, into a double-buffered LDS tile, meet at one barrier per fragment, and each wave
 // multiplies its own 16 rows of the window against the shared tile.
-template <int NCH, int NW, int D>
+// KT = condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16, 4 cells per lane) or 32
+// (v_mfma_f32_16x16x32_f16, 8 cells per lane: lane l holds k = 8*(l/16) .. 8*(l/16)+7, fed by two
+// transposing reads four staged rows apart).
+template <int NCH, int NW, int D, int KT>
 __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_tile_kernel(
     const uint4* __restrict__ items, XcdSplit xs,
     const int32_t* __restrict__ win_row, const int32_t* __restrict__ tile_colid,
     const uint64_t* __restrict__ tile_mask, const uint32_t* __restrict__ tile_val_off,
     const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, float* __restrict__ C,
     float* __restrict__ scratch, int N) {
-    using Gm = TileGeom<NCH, NW>;
-    constexpr int P = Gm::P, TPR = Gm::TPR, NLD = Gm::NLD, LDB = Gm::LDB, THREADS = Gm::THREADS;
-    __shared__ __attribute__((aligned(16))) _Float16 lds_b[Gm::ITEMS_PER_BLOCK][Gm::NBUF][16 * LDB];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWavesPerBlock > NW ? kWavesPerBlock : NW][256 + 8];
+    using Gm = TileGeom<NCH, NW, KT>;
+    constexpr int P = Gm::P, TPR = Gm::TPR, NLD = Gm::NLD, LDB = Gm::LDB, THREADS = Gm::THREADS, CPL = Gm::CPL;
+    using vals_t = typename std::conditional<KT == 16, uint2_t, uint4_t>::type;   // CPL halves per lane
+    using frag_t = typename std::conditional<KT == 16, half4_t, half8_t>::type;
+    __shared__ __attribute__((aligned(16))) _Float16 lds_b[Gm::ITEMS_PER_BLOCK][Gm::NBUF][KT * LDB];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWavesPerBlock > NW ? kWavesPerBlock : NW][16 * KT + 16];
 
     const int lane = threadIdx.x & 63;
     const int wib = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave in block
@@ -302,7 +310,7 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     uint16_t* sv = lds_v[wib];
 
     // cooperative staging: thread `tix` of the THREADS sharing the tile takes 16-byte piece
-    // j*THREADS + tix of the 16 x TPR pieces of a fragment's B rows
+    // j*THREADS + tix of the KT x TPR pieces of a fragment's B rows
     const int tix = NW == 1 ? lane : (int)threadIdx.x;
     int ld_row[NLD], ld_col[NLD];
     bool ld_on[NLD];
@@ -311,9 +319,10 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
         const int piece = j * THREADS + tix;
         ld_row[j] = piece / TPR;
         ld_col[j] = (piece % TPR) * 8;
-        ld_on[j] = ld_row[j] < 16;
+        ld_on[j] = ld_row[j] < KT;   // pieces past the fragment (narrow panels) are loaded but not staged
     }
     const int m = lane & 15, kg = lane >> 4;
+    const int cid_lane = lane & (KT - 1);   // lane that fetches the id of fragment column (lane mod KT)
     // B rows are addressed as a wave-uniform base plus a 32-bit byte offset (the plan guarantees
     // n_cols * 2N < 2^32), which leaves the address arithmetic at one multiply-add per load
     const char* Bbytes = reinterpret_cast<const char*>(B + panel);
@@ -321,7 +330,7 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     uint32_t ld_byte[NLD];
 #pragma unroll
     for (int j = 0; j < NLD; ++j) ld_byte[j] = 2u * (uint32_t)ld_col[j];
-    const int tr_off = (4 * kg + (m >> 2)) * LDB + 4 * (m & 3);   // this lane's run for the transposing read
+    const int tr_off = (CPL * kg + (m >> 2)) * LDB + 4 * (m & 3);   // this lane's run for the transposing read
 
     float4_t acc[NCH];
 #pragma unroll
@@ -330,31 +339,28 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     if (t_begin < t_end) {
         const uint32_t t_last = t_end - 1;
         // Ring of D fragments in flight per thread: slot d holds the staged B pieces and values
-        // of fragment base+d; the metadata ring holds column ids / value ranges of base+D+d.
+        // of fragment base+d; the metadata ring holds column ids / value offsets of base+D+d.
+        // Every global load in the loop is unconditional (fragment indices are clamped to the last
+        // fragment of the item, value loads may run past a fragment's values into the padded
+        // stream).
         uint4_t breg[D][NLD];
-        uint2_t vreg[D];
+        vals_t vreg[D];
         int colid_n[D];
-        uint32_t voff_n[D], vend_n[D];
+        uint32_t voff_n[D];
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const uint32_t t = min(t_begin + (uint32_t)d, t_last);
-            const int colid = tile_colid[(size_t)t * 16 + m];
-            const uint32_t voff = tile_val_off[(size_t)t * NW + sub], vend = tile_val_off[(size_t)t * NW + sub + 1];
-            const uint32_t tn = min(t_begin + (uint32_t)(D + d), t_last);
-            colid_n[d] = tile_colid[(size_t)tn * 16 + m];
-            voff_n[d] = tile_val_off[(size_t)tn * NW + sub];
-            vend_n[d] = tile_val_off[(size_t)tn * NW + sub + 1];
-            vreg[d] = (uint2_t){0u, 0u};
+            const int colid = tile_colid[(size_t)t * KT + cid_lane];
+            const uint32_t voff = tile_val_off[(size_t)t * NW + sub];
 #pragma unroll
-            for (int j = 0; j < NLD; ++j) breg[d][j] = (uint4_t){0u, 0u, 0u, 0u};
-            if (t_begin + (uint32_t)d < t_end) {
-#pragma unroll
-                for (int j = 0; j < NLD; ++j) {
-                    const int c = shfl_i32(colid, ld_row[j] & 15);
-                    if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
-                }
-                if ((uint32_t)lane * 4u < vend - voff) vreg[d] = *reinterpret_cast<const uint2_t*>(tile_val + voff + lane * 4);
+            for (int j = 0; j < NLD; ++j) {
+                const int c = shfl_i32(colid, ld_row[j] & (KT - 1));
+                breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
             }
+            vreg[d] = *reinterpret_cast<const vals_t*>(tile_val + voff + lane * CPL);
+            const uint32_t tn = min(t_begin + (uint32_t)(D + d), t_last);
+            colid_n[d] = tile_colid[(size_t)tn * KT + cid_lane];
+            voff_n[d] = tile_val_off[(size_t)tn * NW + sub];
         }
 
         int buf = 0;
@@ -362,62 +368,75 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 const uint32_t t = base + (uint32_t)d;
-                if (t < t_end) {   // uniform
-                    // bitmaps of this wave's sub-fragment (wave-uniform)
-                    const uint64_t* mk = tile_mask + ((size_t)t * NW + sub) * 4;
-                    const uint64_t m0 = mk[0], m1 = mk[1], m2 = mk[2], m3 = mk[3];
+                const bool live = t < t_end;                     // uniform; dead steps only refill
+                const uint32_t tc = min(t, t_last);
+                // bitmaps of this wave's sub-fragment (wave-uniform)
+                const uint64_t* mk = tile_mask + ((size_t)tc * NW + sub) * CPL;
+                uint64_t mw[CPL];
+                uint64_t any = 0;
+#pragma unroll
+                for (int w = 0; w < CPL; ++w) {
+                    mw[w] = mk[w];
+                    any |= mw[w];
+                }
 
-                    // staged registers -> LDS
-                    _Float16* sb = sb0 + buf * (16 * LDB);
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                // staged registers -> LDS
+                _Float16* sb = sb0 + buf * (KT * LDB);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int j = 0; j < NLD; ++j)
+                    if (ld_on[j]) *reinterpret_cast<uint4_t*>(sb + ld_row[j] * LDB + ld_col[j]) = breg[d][j];
+                *reinterpret_cast<vals_t*>(sv + lane * CPL) = vreg[d];
+                if (NW > 1) __syncthreads();
+                else {
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                     __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                    for (int j = 0; j < NLD; ++j)
-                        if (ld_on[j]) *reinterpret_cast<uint4_t*>(sb + ld_row[j] * LDB + ld_col[j]) = breg[d][j];
-                    *reinterpret_cast<uint2_t*>(sv + lane * 4) = vreg[d];
-                    if (NW > 1) __syncthreads();
-                    else {
-                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                    }
+                }
 
-                    // refill slot d with fragment t+D, whose metadata arrived one round ago
-                    if (t + D < t_end) {
+                // refill slot d with fragment t+D (its metadata arrived one round ago), then fetch
+                // the metadata of fragment t+2D
 #pragma unroll
-                        for (int j = 0; j < NLD; ++j) {
-                            const int c = shfl_i32(colid_n[d], ld_row[j] & 15);
-                            if (ld_on[j]) breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
-                        }
-                        vreg[d] = (uint2_t){0u, 0u};
-                        if ((uint32_t)lane * 4u < vend_n[d] - voff_n[d])
-                            vreg[d] = *reinterpret_cast<const uint2_t*>(tile_val + voff_n[d] + lane * 4);
-                    }
-                    // metadata of fragment t+2D
-                    const uint32_t t2 = min(t + 2u * D, t_last);
-                    colid_n[d] = tile_colid[(size_t)t2 * 16 + m];
-                    voff_n[d] = tile_val_off[(size_t)t2 * NW + sub];
-                    vend_n[d] = tile_val_off[(size_t)t2 * NW + sub + 1];
+                for (int j = 0; j < NLD; ++j) {
+                    const int c = shfl_i32(colid_n[d], ld_row[j] & (KT - 1));
+                    breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
+                }
+                vreg[d] = *reinterpret_cast<const vals_t*>(tile_val + voff_n[d] + lane * CPL);
+                const uint32_t t2 = min(t + 2u * D, t_last);
+                colid_n[d] = tile_colid[(size_t)t2 * KT + cid_lane];
+                voff_n[d] = tile_val_off[(size_t)t2 * NW + sub];
 
-                    if (NW == 1 || (m0 | m1 | m2 | m3) != 0ull) {
-                        // expand this lane's four cells (window row m, fragment columns 4kg..4kg+3)
-                        const uint32_t bit0 = (uint32_t)(m0 >> lane) & 1u, bit1 = (uint32_t)(m1 >> lane) & 1u;
-                        const uint32_t bit2 = (uint32_t)(m2 >> lane) & 1u, bit3 = (uint32_t)(m3 >> lane) & 1u;
-                        const uint32_t i0 = bits_below_lane(m0) + bits_below_lane(m1) + bits_below_lane(m2) + bits_below_lane(m3);
-                        const uint32_t i1 = i0 + bit0, i2 = i1 + bit1, i3 = i2 + bit2;
-                        half4_t a_frag;
-                        a_frag[0] = bit0 ? __builtin_bit_cast(_Float16, sv[i0]) : (_Float16)0;
-                        a_frag[1] = bit1 ? __builtin_bit_cast(_Float16, sv[i1]) : (_Float16)0;
-                        a_frag[2] = bit2 ? __builtin_bit_cast(_Float16, sv[i2]) : (_Float16)0;
-                        a_frag[3] = bit3 ? __builtin_bit_cast(_Float16, sv[i3]) : (_Float16)0;
+                if (live && (NW == 1 || any != 0ull)) {
+                    // expand this lane's CPL cells (window row m, fragment columns CPL*kg .. CPL*kg+CPL-1):
+                    // the lane's stored values are consecutive, starting at the number of set bits of
+                    // lower lanes over all words
+                    uint32_t idx = 0;
 #pragma unroll
-                        for (int c = 0; c < NCH; ++c) {
+                    for (int w = 0; w < CPL; ++w) idx += bits_below_lane(mw[w]);
+                    frag_t a_frag;
+#pragma unroll
+                    for (int w = 0; w < CPL; ++w) {
+                        const uint32_t bit = (uint32_t)(mw[w] >> lane) & 1u;
+                        a_frag[w] = bit ? __builtin_bit_cast(_Float16, sv[idx]) : (_Float16)0;
+                        idx += bit;
+                    }
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) {
+                        if constexpr (KT == 16) {
                             const half4_t b_frag = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                                 (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 16 * c)));
                             acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
+                        } else {
+                            const half4_t lo = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 16 * c)));
+                            const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                                (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 4 * LDB + 16 * c)));
+                            const half8_t b_frag = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(b_frag, a_frag, acc[c], 0, 0, 0);
                         }
                     }
-                    if (NW > 1) buf ^= 1;
                 }
+                if (NW > 1) buf ^= 1;
             }
         }
     }
@@ -510,22 +529,25 @@ static void launch_irregular_t(const DevicePlan& d, const void* B, void* C, hipS
                        d.scratch, d.geo.N);
 }
 
-template <int NCH, int NW, int D>
+template <int NCH, int NW, int D, int KT>
 static void launch_tile_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
     constexpr int items_per_block = NW == 1 ? kWavesPerBlock : 1;
     uint32_t longest = 0;
     for (int x = 0; x < 8; ++x) longest = std::max(longest, d.tile_split.start[x + 1] - d.tile_split.start[x]);
     dim3 grid(8u * ((longest + items_per_block - 1) / items_per_block), (unsigned)(d.geo.N / d.geo.tile_panel));
-    hipLaunchKernelGGL((rsh_tile_kernel<NCH, NW, D>), grid, dim3(NW == 1 ? 64 * kWavesPerBlock : 64 * NW), 0, st,
+    hipLaunchKernelGGL((rsh_tile_kernel<NCH, NW, D, KT>), grid, dim3(NW == 1 ? 64 * kWavesPerBlock : 64 * NW), 0, st,
                        (const uint4*)d.tile_item, d.tile_split, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off,
                        d.tile_val, (const __half*)B, (float*)C, d.scratch, d.geo.N);
 }
 
-// Fragments in flight per thread: one for 16-row windows (each thread stages four 16-byte pieces
-// of a fragment), two when the waves of a window share the staging (measured best of 1, 2, 4, 8).
+// Fragments in flight per thread: one for 16-row windows, two when the waves of a window share
+// the staging (measured best of 1, 2, 4).
 template <int NCH, int NW>
 static int launch_tile_d(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
-    launch_tile_t<NCH, NW, (NW == 1 ? 1 : 2)>(d, B, C, st);
+    constexpr int D = NW == 1 ? 1 : 2;
+    if (d.geo.tile_k == 16) launch_tile_t<NCH, NW, D, 16>(d, B, C, st);
+    else if (d.geo.tile_k == 32) launch_tile_t<NCH, NW, D, 32>(d, B, C, st);
+    else return RSH_ERR_BAD_OPTION;
     return RSH_OK;
 }
 

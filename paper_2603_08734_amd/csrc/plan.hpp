@@ -9,7 +9,7 @@ namespace rsh {
 
 constexpr int kW = 16;  // rows per sub-window (MFMA N extent); a window is nw of them
 constexpr int kMaxWindowRows = 64;
-constexpr int kK = 16;  // condensed columns per fragment (MFMA K extent)
+constexpr int kK = 16;  // default condensed columns per fragment (MFMA K extent); 32 is the other choice
 constexpr uint32_t kNoDst = 0xffffffffu;
 // irregular wave descriptor {start, count, dst, info}; info = kind | flags | L << 8 | R << 16
 constexpr uint32_t kWaveShortRows = 0u;  // `count` rows of L entries each, R rows per team; dst indexes irr_row
@@ -28,8 +28,10 @@ struct Geometry {
     int tile_nch = 0;   // 16-feature MFMA chunks per panel
     int win_rows = 16;  // rows per window (16, 32 or 64)
     int nw = 1;         // sub-windows (waves) per window = win_rows / 16
+    int tile_k = 16;    // condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16) or 32 (..._16x16x32_f16)
+    int cpl = 4;        // cells per MFMA lane = bitmap words per sub-fragment = tile_k / 4
 };
-Geometry make_geometry(int N, int window_rows);
+Geometry make_geometry(int N, int window_rows, int tile_k);
 
 // Work lists are cut into 8 contiguous parts of equal estimated cost, one per XCD:
 // part x is items [start[x], start[x+1]).
@@ -80,6 +82,8 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
                  std::vector<int32_t>& order, int threads, double* cost_given, double* cost_found);
 void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
                     int32_t tau_nnz, int32_t tau_inc, Partition& out, int threads);
+// Window height for a partition made with 16-row windows: 16, 32 or 64 (see rsh_plan_opts_t::window_rows).
+int choose_window_rows(const rsh_csr_t& a, const Partition& part16);
 int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads);
 int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t* val, uint8_t* path);
 

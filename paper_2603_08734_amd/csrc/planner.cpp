@@ -21,11 +21,13 @@ int hardware_threads() {
 
 static int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
 
-Geometry make_geometry(int N, int window_rows) {
+Geometry make_geometry(int N, int window_rows, int tile_k) {
     Geometry g;
     g.N = N;
     g.win_rows = window_rows;
     g.nw = window_rows / kW;
+    g.tile_k = tile_k;
+    g.cpl = tile_k / 4;
     g.irr_panel = gcd_int(N, 512);
     g.irr_tpr = g.irr_panel / 8;
     g.irr_teams = 64 / g.irr_tpr;
@@ -102,6 +104,35 @@ static int64_t union_size(const rsh_csr_t& a, const int32_t* rows, int n, std::v
     return std::unique(tmp.begin(), tmp.end()) - tmp.begin();
 }
 
+// Sampled test of whether taller windows pay.  Taller windows share one staged B tile among
+// more MFMA waves, which helps only when the merged windows name mostly the same columns.  Up
+// to 512 groups of four consecutive 16-row windows are measured: distinct columns of the single
+// windows (u1), of the two pairs (u2) and of the group (u4).
+int choose_window_rows(const rsh_csr_t& a, const Partition& part16) {
+    const int64_t n_win = (int64_t)part16.win_row.size() / kW;
+    if (n_win < 64) return kW;
+    const int64_t n_groups = n_win / 4, n_samples = std::min<int64_t>(512, n_groups);
+    // seen[c] = last (sample, unit) stamp under which column c was counted, per merge level
+    std::vector<int64_t> seen1((size_t)a.n_cols, -1), seen2((size_t)a.n_cols, -1), seen4((size_t)a.n_cols, -1);
+    int64_t u1 = 0, u2 = 0, u4 = 0;
+    for (int64_t s = 0; s < n_samples; ++s) {
+        const int32_t* rows = &part16.win_row[(size_t)((s * n_groups / n_samples) * 4 * kW)];
+        for (int i = 0; i < 4 * kW; ++i) {
+            const int32_t r = rows[i];
+            if (r < 0) continue;
+            const int64_t s1 = 4 * s + i / kW, s2 = 2 * s + i / (2 * kW);
+            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
+                const size_t c = (size_t)a.col_idx[p];
+                if (seen1[c] != s1) seen1[c] = s1, ++u1;
+                if (seen2[c] != s2) seen2[c] = s2, ++u2;
+                if (seen4[c] != s) seen4[c] = s, ++u4;
+            }
+        }
+    }
+    if (u2 * 10 > u1 * 6) return kW;
+    return u4 * 10 > u2 * 6 ? 2 * kW : 4 * kW;
+}
+
 void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
                     int32_t tau_nnz, int32_t tau_inc, Partition& out, int threads) {
     const int64_t n = a.n_rows;
@@ -155,7 +186,7 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
     enum : uint8_t { kEmpty = 0, kIrr = 1, kWinCls = 2, kLong = 3 };
     std::vector<uint8_t> cls((size_t)n, kWinCls);
     const double mean = n > 0 ? (double)a.nnz / (double)n : 0.0;
-    const int64_t long_thr = o.long_row_nnz > 0 ? o.long_row_nnz : (int64_t)std::max(4.0 * mean, 4.0 * kK);
+    const int64_t long_thr = o.long_row_nnz > 0 ? o.long_row_nnz : (int64_t)std::max(4.0 * mean, 64.0);
     parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
         int32_t others[kMaxWindowRows];
         for (int64_t i = b; i < e; ++i) {
@@ -258,7 +289,7 @@ XcdSplit split_by_cost(const std::vector<uint32_t>& cost) {
     return s;
 }
 
-static inline uint32_t round_up4(uint32_t x) { return (x + 3u) & ~3u; }
+static inline uint32_t round_up_to(uint32_t x, uint32_t m) { return (x + m - 1u) / m * m; }   // m = 4 or 8
 
 struct WinEntry {
     uint64_t key;  // col << 6 | window row
@@ -293,6 +324,7 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
     *cols_given = *cols_found = 0;
     if (!plan.opts.window_schedule || a.n_rows != a.n_cols || n_win < 4 * kClusterWindows) return order;
     const int W = plan.geo.win_rows;
+    const size_t K = (size_t)plan.geo.tile_k;
     std::vector<int32_t> row_win((size_t)a.n_rows, -1);
     for (int64_t w = 0; w < n_win; ++w)
         for (int r = 0; r < W; ++r)
@@ -302,7 +334,7 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
         int64_t total = 0;
         for (int64_t i = 0; i < n_win; ++i) {
             const int64_t chunk = i / kClusterWindows, w = ord[(size_t)i];
-            for (size_t q = (size_t)plan.win_tile_off[w] * kK; q < (size_t)plan.win_tile_off[w + 1] * kK; ++q) {
+            for (size_t q = (size_t)plan.win_tile_off[w] * K; q < (size_t)plan.win_tile_off[w + 1] * K; ++q) {
                 const int32_t c = plan.tile_colid[q];
                 if (stamp[(size_t)c] != chunk) {
                     stamp[(size_t)c] = chunk;
@@ -327,7 +359,7 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
             state[(size_t)w] = 2;
             found.push_back(w);
             ++placed;
-            for (size_t q = (size_t)plan.win_tile_off[w] * kK; q < (size_t)plan.win_tile_off[w + 1] * kK; ++q) {
+            for (size_t q = (size_t)plan.win_tile_off[w] * K; q < (size_t)plan.win_tile_off[w + 1] * K; ++q) {
                 const int32_t w2 = row_win[(size_t)plan.tile_colid[q]];
                 if (w2 >= 0 && state[(size_t)w2] == 0) {
                     state[(size_t)w2] = 1;
@@ -347,6 +379,7 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
 int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads) {
     const Geometry& geo = plan.geo;
     const int W = geo.win_rows, NW = geo.nw;
+    const uint32_t K = (uint32_t)geo.tile_k, CPL = (uint32_t)geo.cpl;   // fragment columns; cells per lane = bitmap words
     const int64_t n_win = (int64_t)part.win_row.size() / W;
     plan.win_row = part.win_row;
 
@@ -367,13 +400,13 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 const uint64_t c = x.key >> 6;
                 if (c != prev_col) {
                     prev_col = c;
-                    if (u % kK == 0) cnt.insert(cnt.end(), (size_t)NW, 0u);
+                    if (u % K == 0) cnt.insert(cnt.end(), (size_t)NW, 0u);
                     ++u;
                 }
                 ++cnt[cnt.size() - (size_t)NW + (size_t)((x.key & 63) >> 4)];
             }
             uint32_t v = 0;
-            for (uint32_t c : cnt) v += round_up4(c);
+            for (uint32_t c : cnt) v += round_up_to(c, CPL);
             win_tiles[w] = (uint32_t)(cnt.size() / (size_t)NW);
             win_vals[w] = v;
             win_cols[w] = u;
@@ -391,10 +424,10 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     }
     const int64_t n_tiles = plan.win_tile_off[n_win];
     if (win_val_off[n_win] >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
-    plan.tile_colid.assign((size_t)n_tiles * kK, 0);
-    plan.tile_mask.assign((size_t)n_tiles * NW * 4, 0);
+    plan.tile_colid.assign((size_t)n_tiles * K, 0);
+    plan.tile_mask.assign((size_t)n_tiles * NW * CPL, 0);
     plan.tile_val_off.assign((size_t)n_tiles * NW + 1, 0);
-    plan.tile_val.assign((size_t)win_val_off[n_win] + 8, 0);  // tail pad: kernels read 4 elements per lane
+    plan.tile_val.assign((size_t)win_val_off[n_win] + 520, 0);  // tail pad: every lane reads CPL elements, unconditionally
 
     // ---- pass 2: fill -------------------------------------------------------------------
     std::vector<int64_t> win_nnz((size_t)n_win, 0);
@@ -415,35 +448,35 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 if (c != prev_col) {
                     prev_col = c;
                     ++u;
-                    plan.tile_colid[(size_t)t0 * kK + (size_t)u] = (int32_t)c;
+                    plan.tile_colid[(size_t)t0 * K + (size_t)u] = (int32_t)c;
                 }
                 ucol[i] = (uint32_t)u;
-                const uint32_t t = (uint32_t)u / kK, k = (uint32_t)u % kK, r = (uint32_t)(ent[i].key & 63);
-                plan.tile_mask[((size_t)(t0 + t) * NW + (r >> 4)) * 4 + (k & 3)] |= 1ull << ((k >> 2) * 16 + (r & 15));
+                const uint32_t t = (uint32_t)u / K, k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 63);
+                plan.tile_mask[((size_t)(t0 + t) * NW + (r >> 4)) * CPL + (k % CPL)] |= 1ull << ((k / CPL) * 16 + (r & 15));
             }
             // padding columns of the last fragment repeat its last valid column
             if (nt > 0) {
                 const int64_t n_u = u + 1;
-                for (int64_t k = n_u; k < (int64_t)nt * kK; ++k)
-                    plan.tile_colid[(size_t)t0 * kK + (size_t)k] = plan.tile_colid[(size_t)t0 * kK + (size_t)(n_u - 1)];
+                for (int64_t k = n_u; k < (int64_t)nt * K; ++k)
+                    plan.tile_colid[(size_t)t0 * K + (size_t)k] = plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)];
             }
             // value offsets of every sub-fragment
             uint64_t off = win_val_off[w];
             for (uint32_t q = 0; q < nt * (uint32_t)NW; ++q) {
                 plan.tile_val_off[(size_t)t0 * NW + q] = (uint32_t)off;
                 uint32_t c = 0;
-                for (int j = 0; j < 4; ++j) c += (uint32_t)popc64(plan.tile_mask[((size_t)t0 * NW + q) * 4 + j]);
-                off += round_up4(c);
+                for (uint32_t j = 0; j < CPL; ++j) c += (uint32_t)popc64(plan.tile_mask[((size_t)t0 * NW + q) * CPL + j]);
+                off += round_up_to(c, CPL);
             }
             // values: position = (entries of lower lanes) + (entries of this lane in lower words)
             for (size_t i = 0; i < ent.size(); ++i) {
-                const uint32_t t = ucol[i] / kK, k = ucol[i] % kK, r = (uint32_t)(ent[i].key & 63);
-                const uint32_t lane = (k >> 2) * 16 + (r & 15), word = k & 3;
+                const uint32_t t = ucol[i] / K, k = ucol[i] % K, r = (uint32_t)(ent[i].key & 63);
+                const uint32_t lane = (k / CPL) * 16 + (r & 15), word = k % CPL;
                 const size_t sub = (size_t)(t0 + t) * NW + (r >> 4);
-                const uint64_t* m = &plan.tile_mask[sub * 4];
+                const uint64_t* m = &plan.tile_mask[sub * CPL];
                 const uint64_t below = lane ? (~0ull >> (64 - lane)) : 0ull;
                 uint32_t pos = 0;
-                for (uint32_t q = 0; q < 4; ++q) pos += (uint32_t)popc64(m[q] & below);
+                for (uint32_t q = 0; q < CPL; ++q) pos += (uint32_t)popc64(m[q] & below);
                 for (uint32_t q = 0; q < word; ++q) pos += (uint32_t)((m[q] >> lane) & 1ull);
                 plan.tile_val[plan.tile_val_off[sub] + pos] = ent[i].val;
             }
@@ -458,7 +491,9 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     if (t_max <= 0) {
         int64_t per = (n_tiles + 4095) / 4096, p2 = 1;
         while (p2 < per) p2 <<= 1;
-        t_max = std::max<int64_t>(32, std::min<int64_t>(64, p2));
+        // 512 .. 1024 condensed columns per item: the upper end keeps the fp32 accumulation chain of
+        // an output at 1024 products, the lower end amortises the item's stores of C
+        t_max = std::max<int64_t>(512 / K, std::min<int64_t>(1024 / K, p2));
     }
     plan.tile_item.clear();
     plan.combine.clear();
@@ -651,32 +686,65 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     }
     plan.irr_row.resize(plan.irr_row.size() + 64, 0);   // tail pad for lane-wise reads
     {
-        // Assemble the wave list: XCD x runs its column-group pieces, then a contiguous run of
-        // the remaining waves sized so that all eight parts cost about the same.  Cost is in
-        // units of one gathered B row: entries + two per stored row of C + a fixed share.
+        // Assemble the wave list.  The kinds of wave stress different parts of the memory system
+        // (column-group pieces mostly hit in L2, rows of a few dozen entries miss to the fabric,
+        // very short rows are bound by the stores of C), so every XCD receives the same mix and
+        // runs it interleaved: the free waves are binned into classes by kind and length, dealt
+        // to the XCDs in runs of kDealRun (always to the XCD with the least cost so far, its
+        // column-group pieces included), and each XCD's lists are merged so that all of them
+        // advance at the same fraction of their cost.  Cost is in units of one gathered B row:
+        // entries + two per stored row of C + a fixed share.
+        constexpr size_t kDealRun = 8;
+        constexpr int kClasses = 7;
         auto wave_cost = [](const uint32_t* w) -> uint64_t {
             const uint32_t count = w[1], info = w[3], kind = info & kWaveKindMask;
             return 32u + (kind == kWaveSlice ? count : kind == kWaveShortRows ? count * (((info >> 8) & 0xffu) + 2u) : count * 2u);
         };
-        uint64_t total = 0, bucket_cost[8];
-        for (int g = 0; g < 8; ++g) {
-            bucket_cost[g] = 0;
-            for (size_t i = 0; i < bucket[g].size(); i += 4) bucket_cost[g] += wave_cost(&bucket[g][i]);
-            total += bucket_cost[g];
+        auto wave_class = [](const uint32_t* w) -> int {
+            const uint32_t kind = w[3] & kWaveKindMask;
+            if (kind == kWaveSlice) return w[1] >= 64 ? 0 : 1;
+            if (kind == kWaveZeroRows) return 6;
+            const uint32_t L = (w[3] >> 8) & 0xffu;
+            return L > 8 ? 2 : L > 4 ? 3 : L > 2 ? 4 : L > 1 ? 5 : 6;
+        };
+        std::vector<uint32_t> lists[8][kClasses + 1];   // per XCD: list 0 = column-group pieces, then the classes
+        uint64_t list_cost[8][kClasses + 1] = {}, xcd_cost[8];
+        for (int x = 0; x < 8; ++x) {
+            lists[x][0].swap(bucket[x]);
+            for (size_t i = 0; i < lists[x][0].size(); i += 4) list_cost[x][0] += wave_cost(&lists[x][0][i]);
+            xcd_cost[x] = list_cost[x][0];
         }
-        for (size_t i = 0; i < free_waves.size(); i += 4) total += wave_cost(&free_waves[i]);
-        const uint64_t target = (total + 7) / 8;
+        const size_t n_free = free_waves.size() / 4;
+        for (size_t i = 0; i < n_free; i += kDealRun) {
+            int x = 0;
+            for (int q = 1; q < 8; ++q)
+                if (xcd_cost[q] < xcd_cost[x]) x = q;
+            for (size_t w = i; w < std::min(n_free, i + kDealRun); ++w) {
+                const uint32_t* d = &free_waves[4 * w];
+                const int c = 1 + wave_class(d);
+                lists[x][c].insert(lists[x][c].end(), d, d + 4);
+                list_cost[x][c] += wave_cost(d);
+                xcd_cost[x] += wave_cost(d);
+            }
+        }
         plan.irr_wave.clear();
         plan.irr_wave.reserve(free_waves.size() + 4 * (size_t)n_slice_waves);
-        size_t next_free = 0;
         for (int x = 0; x < 8; ++x) {
             plan.irr_split.start[x] = (uint32_t)(plan.irr_wave.size() / 4);
-            plan.irr_wave.insert(plan.irr_wave.end(), bucket[x].begin(), bucket[x].end());
-            uint64_t acc = bucket_cost[x];
-            while (next_free < free_waves.size() && (x == 7 || acc < target)) {
-                acc += wave_cost(&free_waves[next_free]);
-                plan.irr_wave.insert(plan.irr_wave.end(), free_waves.begin() + (long)next_free, free_waves.begin() + (long)next_free + 4);
-                next_free += 4;
+            size_t at[kClasses + 1] = {};
+            uint64_t done[kClasses + 1] = {};
+            for (;;) {
+                int best = -1;
+                for (int l = 0; l <= kClasses; ++l) {   // the list that is furthest behind: done/cost smallest
+                    if (at[l] >= lists[x][l].size()) continue;
+                    if (best < 0 || (unsigned __int128)done[l] * list_cost[x][best] < (unsigned __int128)done[best] * list_cost[x][l]) best = l;
+                }
+                if (best < 0) break;
+                for (size_t k = 0; k < kDealRun && at[best] < lists[x][best].size(); ++k, at[best] += 4) {
+                    const uint32_t* d = lists[x][best].data() + at[best];
+                    plan.irr_wave.insert(plan.irr_wave.end(), d, d + 4);
+                    done[best] += wave_cost(d);
+                }
             }
         }
         plan.irr_split.start[8] = (uint32_t)(plan.irr_wave.size() / 4);
@@ -690,6 +758,8 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     st.n_cols = a.n_cols;
     st.nnz = a.nnz;
     st.N = geo.N;
+    st.window_rows = geo.win_rows;
+    st.tile_k = geo.tile_k;
     st.n_windows = n_win;
     st.n_tiles = n_tiles;
     st.nnz_tile = nnz_tile;
@@ -752,20 +822,20 @@ int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t*
     std::vector<Ent> ent;
     ent.reserve((size_t)p.nnz);
     // dense-fragment part
-    const int W = p.geo.win_rows, NW = p.geo.nw;
+    const int W = p.geo.win_rows, NW = p.geo.nw, K = p.geo.tile_k, CPL = p.geo.cpl;
     const int64_t n_win = (int64_t)p.win_row.size() / W;
     for (int64_t w = 0; w < n_win; ++w) {
         for (uint32_t t = p.win_tile_off[w]; t < p.win_tile_off[w + 1]; ++t)
             for (int sw = 0; sw < NW; ++sw) {
-                const uint64_t* m = &p.tile_mask[((size_t)t * NW + sw) * 4];
+                const uint64_t* m = &p.tile_mask[((size_t)t * NW + sw) * CPL];
                 uint32_t pos = p.tile_val_off[(size_t)t * NW + sw];
                 for (int lane = 0; lane < 64; ++lane)
-                    for (int word = 0; word < 4; ++word)
+                    for (int word = 0; word < CPL; ++word)
                         if ((m[word] >> lane) & 1ull) {
-                            const int r = sw * 16 + (lane & 15), k = (lane >> 4) * 4 + word;
+                            const int r = sw * 16 + (lane & 15), k = (lane >> 4) * CPL + word;
                             const int32_t row = p.win_row[(size_t)w * W + r];
                             if (row < 0) return RSH_ERR_INVALID_CSR;
-                            ent.push_back({row, p.tile_colid[(size_t)t * kK + k], p.tile_val[pos++], 0});
+                            ent.push_back({row, p.tile_colid[(size_t)t * K + k], p.tile_val[pos++], 0});
                         }
             }
     }

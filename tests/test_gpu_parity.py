@@ -53,6 +53,9 @@ OPTION_SETS = {
     "w64": dict(window_rows=64),
     "w64_all_tile": dict(window_rows=64, force_path=2, max_tiles_per_item=5),
     "w32_all_tile": dict(window_rows=32, force_path=2),
+    "k32": dict(tile_k=32),
+    "k32_all_tile": dict(tile_k=32, force_path=2, max_tiles_per_item=3),
+    "k32_w64_all_tile": dict(tile_k=32, window_rows=64, force_path=2),
     "all_irregular": dict(force_path=1),
     "all_tile": dict(force_path=2),
     "alg1_literal": dict(partition=0),
@@ -233,7 +236,7 @@ def test_random_matrices_with_random_options():
         r, c = np.nonzero(mask)
         A = from_coo(r, c, rng.standard_normal(r.size), n_rows, n_cols)
         N = int(rng.choice([16, 32, 64, 80, 128, 256]))
-        opts = dict(window_rows=int(rng.choice([16, 32, 64])), partition=int(rng.integers(0, 2)),
+        opts = dict(window_rows=int(rng.choice([16, 32, 64])), tile_k=int(rng.choice([16, 32])), partition=int(rng.integers(0, 2)),
                     reorder=int(rng.integers(0, 2)), force_path=int(rng.choice([0, 0, 1, 2])),
                     max_tiles_per_item=int(rng.choice([0, 1, 4])), max_nnz_per_slice=int(rng.choice([0, 20, 70])),
                     xcd_partition_nnz=int(rng.choice([0, -1, 30])), hub_windows=int(rng.integers(0, 2)),

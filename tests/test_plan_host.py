@@ -17,6 +17,8 @@ MODES = {
     "hybrid": dict(),
     "w64": dict(window_rows=64),
     "w32_all_tile": dict(window_rows=32, force_path=2, max_tiles_per_item=3),
+    "k32": dict(tile_k=32),
+    "k32_w32_all_tile": dict(tile_k=32, window_rows=32, force_path=2, max_tiles_per_item=3),
     "all_irregular": dict(force_path=1),
     "all_tile": dict(force_path=2),
     "alg1_literal": dict(partition=0),
@@ -66,7 +68,7 @@ def test_decode_is_bit_exact_and_paths_are_disjoint(k, mode):
         assert st["nnz_irregular"] == 0
 
 
-@pytest.mark.parametrize("mode", ["hybrid", "alg1_literal", "tiny_items", "tiny_slices", "w64", "w32_all_tile"])
+@pytest.mark.parametrize("mode", ["hybrid", "alg1_literal", "tiny_items", "tiny_slices", "w64", "w32_all_tile", "k32", "k32_w32_all_tile"])
 @pytest.mark.parametrize("k", [2, 4, 5])
 def test_independent_reader_rebuilds_A_from_raw_arrays(k, mode):
     A, N, _ = make_config(k, small=True)
@@ -78,7 +80,7 @@ def test_independent_reader_rebuilds_A_from_raw_arrays(k, mode):
     rows, cols, vals, paths = rstile.entries_from_arrays(
         a["WIN_ROW"], a["WIN_TILE_OFF"], a["TILE_COLID"], a["TILE_MASK"], a["TILE_VAL_OFF"], a["TILE_VAL"],
         a["IRR_COL"], a["IRR_VAL"], a["IRR_WAVE"], a["IRR_ROW"], a["COMBINE"], st["n_scratch_slots"],
-        window_rows=MODES[mode].get("window_rows", 16))
+        window_rows=st["window_rows"], tile_k=st["tile_k"])
     assert rows.size == A.nnz           # every stored entry once ...
     row_ptr, col_idx, val, _ = rstile.csr_from_entries(rows, cols, vals, paths, A.n_rows, A.n_cols)  # ... and only once
     assert np.array_equal(row_ptr, A.row_ptr)
@@ -93,8 +95,9 @@ def test_plan_structure_invariants(k, mode):
     p = host_plan(A, N, **MODES[mode])
     a, st = arrays_of(p), p.stats()
     n_win, n_tiles = st["n_windows"], st["n_tiles"]
-    W = MODES[mode].get("window_rows", 16)
+    W, K = st["window_rows"], st["tile_k"]
     NW = W // 16
+    Q = K // 4
     win_row = a["WIN_ROW"].reshape(n_win, W)
     # rows: windows + irregular + empty partition the row set
     in_win = win_row[win_row >= 0]
@@ -111,13 +114,13 @@ def test_plan_structure_invariants(k, mode):
     # fragments: offsets, bitmap popcounts, padding
     off = a["WIN_TILE_OFF"]
     assert off[0] == 0 and off[-1] == n_tiles and np.all(np.diff(off.astype(np.int64)) >= 0)
-    mask = a["TILE_MASK"].reshape(n_tiles * NW, 4)
+    mask = a["TILE_MASK"].reshape(n_tiles * NW, Q)
     pop = np.array([[bin(int(x)).count("1") for x in row] for row in mask]).sum(axis=1) if n_tiles else np.zeros(0, int)
     voff = a["TILE_VAL_OFF"].astype(np.int64)
-    assert np.all(voff % 4 == 0)
-    assert np.all(np.diff(voff) == (pop + 3) // 4 * 4)
+    assert np.all(voff % Q == 0)
+    assert np.all(np.diff(voff) == (pop + Q - 1) // Q * Q)
     assert int(pop.sum()) == st["nnz_tile"]
-    colid = a["TILE_COLID"].reshape(n_tiles, 16)
+    colid = a["TILE_COLID"].reshape(n_tiles, K)
     assert colid.size == 0 or (colid.min() >= 0 and colid.max() < A.n_cols)
     for w in range(n_win):
         cols_w = colid[off[w]:off[w + 1]].reshape(-1)
@@ -129,16 +132,16 @@ def test_plan_structure_invariants(k, mode):
         assert np.all(cols_w[n_u:] == distinct[-1]), "padding repeats the last valid column"
         # padding cells carry no bits: fragment column k >= n_u - 16*(tiles-1) of the last fragment
         last = off[w + 1] - 1
-        first_pad = n_u - 16 * (off[w + 1] - off[w] - 1)
-        for k in range(first_pad, 16):
+        first_pad = n_u - K * (off[w + 1] - off[w] - 1)
+        for k in range(first_pad, K):
             for sw in range(NW):
-                word = int(mask[last * NW + sw, k % 4])
-                assert (word >> ((k // 4) * 16)) & 0xFFFF == 0
+                word = int(mask[last * NW + sw, k % Q])
+                assert (word >> ((k // Q) * 16)) & 0xFFFF == 0
         # absent rows carry no bits
         for r in np.nonzero(win_row[w] < 0)[0]:
             for t in range(off[w], off[w + 1]):
                 for word in mask[t * NW + int(r) // 16]:
-                    assert all(((int(word) >> (g * 16 + int(r) % 16)) & 1) == 0 for g in range(4))
+                    assert all(((int(word) >> (g * 16 + int(r) % 16)) & 1) == 0 for g in range(4))   # four lane groups per word
     # tile items cover each window's fragments exactly once, in order
     items = a["TILE_ITEM"].reshape(-1, 4)
     assert items.shape[0] == st["n_tile_items"]

@@ -24,6 +24,7 @@ def matrices(draw):
 
 options = st.fixed_dictionaries({
     "window_rows": st.sampled_from([16, 32, 64]),
+    "tile_k": st.sampled_from([16, 32]),
     "partition": st.sampled_from([0, 1]),
     "reorder": st.sampled_from([0, 1]),
     "force_path": st.sampled_from([0, 0, 1, 2]),
