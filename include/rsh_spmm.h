@@ -83,7 +83,7 @@ typedef struct {
                              to the irregular path                                                 */
     int32_t xcd_partition_nnz; /* irregular rows with at least this many entries are cut by column group,
                              one group per XCD, so that each XCD gathers one eighth of B's columns for
-                             them; 0 = auto (256), negative = off                                 */
+                             them; 0 = auto (128), negative = off                                 */
     int32_t upload;       /* 1 = copy the plan to the current HIP device; 0 = host-only plan    */
     int32_t threads;      /* host threads used for planning; 0 = all available                  */
 } rsh_plan_opts_t;

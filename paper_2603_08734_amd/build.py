@@ -12,6 +12,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 VALU forms are switched off for device code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA accumulators stay in ordinary VGPRs: with the AGPR form the register allocator
+         # copies the accumulators of the unrolled fragment ring back and forth on every round
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wextra", "-Wno-unused-command-line-argument"]
 
 

@@ -45,6 +45,17 @@ __device__ __forceinline__ uint32_t bits_below_lane(uint64_t m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
+// Rows of C are written once and never read back by these kernels.  Stored the ordinary way
+// they pass through the XCD's L2 and displace the rows of B that the gathers reuse; the
+// streaming (nontemporal) form keeps them from doing so.  Partial results that the combine
+// pass reads next are stored the ordinary way.  Where a streaming store and an ordinary one sit
+// on sibling paths, the streaming path ends in keep_streaming_hint(): the compiler otherwise
+// folds the two stores into one and drops the hint.
+__device__ __forceinline__ void store_c_streaming(float* p, float4_t v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<float4_t*>(p));
+}
+__device__ __forceinline__ void keep_streaming_hint() { asm volatile("" ::: "memory"); }
+
 union Pack16 {
     uint4 u;
     __half h[8];
@@ -123,8 +134,8 @@ __device__ __forceinline__ void short_rows_group(const __half* __restrict__ Bp, 
             ++st.rq;
             if (row >= 0) {
                 float* out = st.C + (size_t)row * st.N + st.feat;
-                *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-                *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+                store_c_streaming(out, (float4_t){acc[0], acc[1], acc[2], acc[3]});
+                store_c_streaming(out + 4, (float4_t){acc[4], acc[5], acc[6], acc[7]});
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -174,8 +185,8 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
     if (kind == kWaveZeroRows) {
         for (uint32_t q = team; q < count; q += G) {
             float* out = C + (size_t)irr_row[dst + q] * N + feat;
-            *reinterpret_cast<float4*>(out) = make_float4(0.f, 0.f, 0.f, 0.f);
-            *reinterpret_cast<float4*>(out + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            store_c_streaming(out, (float4_t){0.f, 0.f, 0.f, 0.f});
+            store_c_streaming(out + 4, (float4_t){0.f, 0.f, 0.f, 0.f});
         }
         return;
     }
@@ -230,19 +241,29 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] += shfl_f32(acc[i], lane ^ off);
     if (team != 0) return;
-    float* out = ((info & kWaveToScratch) ? scratch : C) + (size_t)dst * N + feat;
-    *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    if (info & kWaveToScratch) {
+        float* out = scratch + (size_t)dst * N + feat;
+        *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    } else {
+        float* out = C + (size_t)dst * N + feat;
+        store_c_streaming(out, (float4_t){acc[0], acc[1], acc[2], acc[3]});
+        store_c_streaming(out + 4, (float4_t){acc[4], acc[5], acc[6], acc[7]});
+        keep_streaming_hint();
+    }
 }
 
 // ---------------------------------------------------------------------------
 // Dense fragments.  One wave per work item (a window or a bounded run of its
-// fragments).  Per fragment the wave gathers the 16 B rows named by the fragment's
-// column ids with coalesced 16-byte loads and stages them in LDS, expands the bitmap-
-// compressed 16x16 piece of A into an MFMA operand with popcount prefixes, and issues
-// one v_mfma_f32_16x16x16_f16 per 16-feature chunk.  The loop is software-pipelined:
-// while fragment t is decoded and multiplied out of LDS, the global loads of fragment
-// t+1 are in flight into registers and the metadata of fragment t+2 is being fetched.
+// fragments) and 16-row sub-window.  Per fragment the wave gathers the K (16 or 32) B rows
+// named by the fragment's column ids with coalesced 16-byte loads and stages them in LDS,
+// expands the bitmap-compressed 16 x K piece of A into an MFMA operand with popcount
+// prefixes, and issues one MFMA per 16-feature chunk (v_mfma_f32_16x16x16_f16 for K = 16,
+// v_mfma_f32_16x16x32_f16 for K = 32).  The loop is software-pipelined: while fragment t is
+// decoded and multiplied out of LDS, the global loads of the next D fragments are in flight
+// into registers and the column ids of the D after those are being fetched.  Nothing in the
+// loop is conditional: a step past the item's last fragment multiplies by an all-zero
+// fragment, so the accumulators stay in place and the waits stay exact.
 //
 // The product is formed transposed (features along M, window rows along N), so a lane
 // ends up with four consecutive features of one output row per chunk (16-byte stores).
@@ -332,6 +353,10 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     for (int j = 0; j < NLD; ++j) ld_byte[j] = 2u * (uint32_t)ld_col[j];
     const int tr_off = (CPL * kg + (m >> 2)) * LDB + 4 * (m & 3);   // this lane's run for the transposing read
 
+    // the output row id is fetched up front so that its latency is hidden behind the fragments
+    const int r = sub * 16 + (lane & 15), q = lane >> 4;
+    const int row = win_row[(size_t)win * (16 * NW) + r];
+
     float4_t acc[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) acc[c] = (float4_t){0.f, 0.f, 0.f, 0.f};
@@ -339,28 +364,42 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     if (t_begin < t_end) {
         const uint32_t t_last = t_end - 1;
         // Ring of D fragments in flight per thread: slot d holds the staged B pieces and values
-        // of fragment base+d; the metadata ring holds column ids / value offsets of base+D+d.
-        // Every global load in the loop is unconditional (fragment indices are clamped to the last
-        // fragment of the item, value loads may run past a fragment's values into the padded
-        // stream).
+        // of fragment base+d and the column ids of fragment base+D+d.  Every global load in the
+        // loop is unconditional (fragment indices are clamped to the last fragment of the item,
+        // value loads may run past a fragment's values into the padded stream), and the prologue
+        // issues its vector loads in the order of a loop round -- per slot: B pieces, values,
+        // next column ids -- so that the wait before slot d is staged leaves the loads of the
+        // other D-1 slots in flight on the first round as on every later one.
         uint4_t breg[D][NLD];
         vals_t vreg[D];
         int colid_n[D];
         uint32_t voff_n[D];
+        uint64_t mw_ring[D][CPL];   // bitmaps of this wave's sub-fragment of fragment base+d (wave-uniform)
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            const uint32_t t = min(t_begin + (uint32_t)d, t_last);
-            const int colid = tile_colid[(size_t)t * KT + cid_lane];
-            const uint32_t voff = tile_val_off[(size_t)t * NW + sub];
+            const uint64_t* mk = tile_mask + ((size_t)min(t_begin + (uint32_t)d, t_last) * NW + sub) * CPL;
 #pragma unroll
-            for (int j = 0; j < NLD; ++j) {
-                const int c = shfl_i32(colid, ld_row[j] & (KT - 1));
-                breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
+            for (int w = 0; w < CPL; ++w) mw_ring[d][w] = mk[w];
+        }
+        {
+            int colid_c[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) colid_c[d] = tile_colid[(size_t)min(t_begin + (uint32_t)d, t_last) * KT + cid_lane];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const uint32_t voff = tile_val_off[(size_t)min(t_begin + (uint32_t)d, t_last) * NW + sub];
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) {
+                    const int c = shfl_i32(colid_c[d], ld_row[j] & (KT - 1));
+                    breg[d][j] = *reinterpret_cast<const uint4_t*>(Bbytes + ((uint32_t)c * row_bytes + ld_byte[j]));
+                }
+                vreg[d] = *reinterpret_cast<const vals_t*>(tile_val + voff + lane * CPL);
+                const uint32_t tn = min(t_begin + (uint32_t)(D + d), t_last);
+                colid_n[d] = tile_colid[(size_t)tn * KT + cid_lane];
+                voff_n[d] = tile_val_off[(size_t)tn * NW + sub];
+                __builtin_amdgcn_sched_barrier(0);
             }
-            vreg[d] = *reinterpret_cast<const vals_t*>(tile_val + voff + lane * CPL);
-            const uint32_t tn = min(t_begin + (uint32_t)(D + d), t_last);
-            colid_n[d] = tile_colid[(size_t)tn * KT + cid_lane];
-            voff_n[d] = tile_val_off[(size_t)tn * NW + sub];
         }
 
         int buf = 0;
@@ -368,34 +407,30 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 const uint32_t t = base + (uint32_t)d;
-                const bool live = t < t_end;                     // uniform; dead steps only refill
-                const uint32_t tc = min(t, t_last);
-                // bitmaps of this wave's sub-fragment (wave-uniform)
-                const uint64_t* mk = tile_mask + ((size_t)tc * NW + sub) * CPL;
+                const bool live = t < t_end;                     // uniform; a dead step multiplies by an all-zero fragment
+                const uint64_t live_mask = 0ull - (uint64_t)live;
                 uint64_t mw[CPL];
-                uint64_t any = 0;
 #pragma unroll
-                for (int w = 0; w < CPL; ++w) {
-                    mw[w] = mk[w];
-                    any |= mw[w];
-                }
+                for (int w = 0; w < CPL; ++w) mw[w] = mw_ring[d][w] & live_mask;
 
-                // staged registers -> LDS
+                // staged registers -> LDS.  Only LDS traffic is ordered here: the waits must not
+                // cover the global loads of the other slots.
                 _Float16* sb = sb0 + buf * (KT * LDB);
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
                 for (int j = 0; j < NLD; ++j)
                     if (ld_on[j]) *reinterpret_cast<uint4_t*>(sb + ld_row[j] * LDB + ld_col[j]) = breg[d][j];
                 *reinterpret_cast<vals_t*>(sv + lane * CPL) = vreg[d];
-                if (NW > 1) __syncthreads();
-                else {
-                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                if (NW > 1) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                    __builtin_amdgcn_s_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+                } else {
                     __builtin_amdgcn_wave_barrier();
                 }
 
-                // refill slot d with fragment t+D (its metadata arrived one round ago), then fetch
-                // the metadata of fragment t+2D
+                // refill slot d with fragment t+D (its column ids arrived one round ago), then fetch
+                // the column ids of fragment t+2D
 #pragma unroll
                 for (int j = 0; j < NLD; ++j) {
                     const int c = shfl_i32(colid_n[d], ld_row[j] & (KT - 1));
@@ -404,56 +439,66 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
                 vreg[d] = *reinterpret_cast<const vals_t*>(tile_val + voff_n[d] + lane * CPL);
                 const uint32_t t2 = min(t + 2u * D, t_last);
                 colid_n[d] = tile_colid[(size_t)t2 * KT + cid_lane];
-                voff_n[d] = tile_val_off[(size_t)t2 * NW + sub];
 
-                if (live && (NW == 1 || any != 0ull)) {
-                    // expand this lane's CPL cells (window row m, fragment columns CPL*kg .. CPL*kg+CPL-1):
-                    // the lane's stored values are consecutive, starting at the number of set bits of
-                    // lower lanes over all words
-                    uint32_t idx = 0;
+                // expand this lane's CPL cells (window row m, fragment columns CPL*kg .. CPL*kg+CPL-1):
+                // the lane's stored values are consecutive, starting at the number of set bits of
+                // lower lanes over all words.  Reads are unconditional (the index never passes the
+                // sub-fragment's value count); cells without a bit become zero.
+                uint32_t idx = 0;
 #pragma unroll
-                    for (int w = 0; w < CPL; ++w) idx += bits_below_lane(mw[w]);
-                    frag_t a_frag;
+                for (int w = 0; w < CPL; ++w) idx += bits_below_lane(mw[w]);
+                frag_t a_frag;
 #pragma unroll
-                    for (int w = 0; w < CPL; ++w) {
-                        const uint32_t bit = (uint32_t)(mw[w] >> lane) & 1u;
-                        a_frag[w] = bit ? __builtin_bit_cast(_Float16, sv[idx]) : (_Float16)0;
-                        idx += bit;
-                    }
+                for (int w = 0; w < CPL; ++w) {
+                    const bool bit = __builtin_amdgcn_inverse_ballot_w64(mw[w]);
+                    const uint16_t raw = sv[idx];
+                    a_frag[w] = __builtin_bit_cast(_Float16, (uint16_t)(bit ? raw : (uint16_t)0));
+                    idx += bit ? 1u : 0u;
+                }
 #pragma unroll
-                    for (int c = 0; c < NCH; ++c) {
-                        if constexpr (KT == 16) {
-                            const half4_t b_frag = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 16 * c)));
-                            acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
-                        } else {
-                            const half4_t lo = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 16 * c)));
-                            const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                                (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 4 * LDB + 16 * c)));
-                            const half8_t b_frag = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(b_frag, a_frag, acc[c], 0, 0, 0);
-                        }
+                for (int c = 0; c < NCH; ++c) {
+                    if constexpr (KT == 16) {
+                        const half4_t b_frag = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 16 * c)));
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x16f16(b_frag, a_frag, acc[c], 0, 0, 0);
+                    } else {
+                        const half4_t lo = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 16 * c)));
+                        const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4_t __attribute__((address_space(3)))*)(sb + tr_off + 4 * LDB + 16 * c)));
+                        const half8_t b_frag = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(b_frag, a_frag, acc[c], 0, 0, 0);
                     }
                 }
                 if (NW > 1) buf ^= 1;
+                // Scalar loads for later steps go last: every LDS wait also waits for outstanding
+                // scalar loads (one counter, no ordering between the two), so they are issued
+                // after the step's last LDS wait and return while the next step waits for its
+                // global loads.
+                __builtin_amdgcn_sched_barrier(0);
+                {
+                    const uint64_t* mk = tile_mask + ((size_t)min(t + (uint32_t)D, t_last) * NW + sub) * CPL;
+#pragma unroll
+                    for (int w = 0; w < CPL; ++w) mw_ring[d][w] = mk[w];
+                    voff_n[d] = tile_val_off[(size_t)t2 * NW + sub];
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
 
     // lane (q = lane/16, r = lane%16) owns features 16c + 4q .. 16c + 4q + 3 of the wave's row r
-    const int r = sub * 16 + (lane & 15), q = lane >> 4;
-    float* out;
     if (dst == kNoDst) {
-        const int row = win_row[(size_t)win * (16 * NW) + r];
         if (row < 0) return;
-        out = C + (size_t)row * N;
-    } else {
-        out = scratch + ((size_t)dst + r) * N;
-    }
-    out += panel + 4 * q;
+        float* out = C + (size_t)row * N + panel + 4 * q;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(out + 16 * c) = acc[c];
+        for (int c = 0; c < NCH; ++c) store_c_streaming(out + 16 * c, acc[c]);
+        keep_streaming_hint();
+    } else {
+        float* out = scratch + ((size_t)dst + r) * N + panel + 4 * q;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(out + 16 * c) = acc[c];
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -490,7 +535,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_combine_kernel(
         o.y = (s0.y + s1.y) + (s2.y + s3.y);
         o.z = (s0.z + s1.z) + (s2.z + s3.z);
         o.w = (s0.w + s1.w) + (s2.w + s3.w);
-        *reinterpret_cast<float4*>(C + (size_t)row * N + f) = o;
+        store_c_streaming(C + (size_t)row * N + f, (float4_t){o.x, o.y, o.z, o.w});
     }
 }
 
@@ -541,7 +586,7 @@ static void launch_tile_t(const DevicePlan& d, const void* B, void* C, hipStream
 }
 
 // Fragments in flight per thread: one for 16-row windows, two when the waves of a window share
-// the staging (measured best of 1, 2, 4).
+// the staging (measured best of 1, 2, 3).
 template <int NCH, int NW>
 static int launch_tile_d(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
     constexpr int D = NW == 1 ? 1 : 2;

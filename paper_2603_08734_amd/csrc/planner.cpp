@@ -557,7 +557,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     // the piece of group g is scheduled on XCD g.  An XCD then gathers only its eighth of the
     // columns of B for this part of the work, which shortens the reuse distance of hot B rows
     // eightfold.  The pieces are partial sums that the combine pass adds up.
-    const int64_t xp_min = plan.opts.xcd_partition_nnz == 0 ? 256 : plan.opts.xcd_partition_nnz;
+    const int64_t xp_min = plan.opts.xcd_partition_nnz == 0 ? 128 : plan.opts.xcd_partition_nnz;
     const int64_t n_long = (int64_t)long_rows.size();
     std::vector<uint8_t> col_group;
     bool any_partitioned = false;
