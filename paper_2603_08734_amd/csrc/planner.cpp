@@ -528,7 +528,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     }
 
     // ---- irregular rows -> wave work items ------------------------------------------------
-    // Stream layout: rows longer than one team pass first (processing order), then the short
+    // Stream layout: rows longer than one team pass first, then the short
     // rows grouped by exact length, longest first, so that every wave of the short-row kind
     // runs rows of one length and its teams stay in lock step.
     const int G = geo.irr_teams, TPR = geo.irr_tpr;
@@ -545,6 +545,11 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         else long_rows.push_back(r);
     }
     if (nnz_irr >= (1ll << 31)) return RSH_ERR_TOO_LARGE;
+    // Residual rows run in ascending row id whatever the reordering found: they share no
+    // window, and consecutive rows of C (and consecutive combine entries) written by
+    // neighbouring waves measured faster than the reordered sequence.
+    for (auto& v : by_len) std::sort(v.begin(), v.end());
+    std::sort(long_rows.begin(), long_rows.end());
     std::vector<int32_t> stream_rows;                 // rows in stream order
     stream_rows.reserve((size_t)n_irr);
     stream_rows.insert(stream_rows.end(), long_rows.begin(), long_rows.end());
