@@ -40,6 +40,9 @@ __device__ __forceinline__ float shfl_f32(float v, int src_lane) {
     return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
 }
 
+// Value held by lane (l ^ 8): rotation by 8 inside each row of 16 lanes.
+__device__ __forceinline__ int swap_lane8(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false); }
+
 // Number of set bits of a 64-bit wave-uniform mask below this lane.
 __device__ __forceinline__ uint32_t bits_below_lane(uint64_t m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
@@ -55,6 +58,20 @@ __device__ __forceinline__ void store_c_streaming(float* p, float4_t v) {
     __builtin_nontemporal_store(v, reinterpret_cast<float4_t*>(p));
 }
 __device__ __forceinline__ void keep_streaming_hint() { asm volatile("" ::: "memory"); }
+
+// A team's finished row of the panel -- lane t holds features 8t .. 8t+7 -- leaves as two streaming
+// stores of consecutive 16-byte pieces (lane t writes pieces t and TPR + t), i.e. whole lines, after
+// a turn through the team's LDS stage; lane-owned pieces would make every store a half-written
+// 32-byte sector, which the streaming path handles at a third of the rate.
+template <int TPR>
+__device__ __forceinline__ void store_row_streaming(float* out_row, const float (&acc)[8], float* stage, int tl) {
+    *reinterpret_cast<float4_t*>(stage + 8 * tl) = (float4_t){acc[0], acc[1], acc[2], acc[3]};
+    *reinterpret_cast<float4_t*>(stage + 8 * tl + 4) = (float4_t){acc[4], acc[5], acc[6], acc[7]};
+    const float4_t v0 = *reinterpret_cast<const float4_t*>(stage + 4 * tl);
+    const float4_t v1 = *reinterpret_cast<const float4_t*>(stage + 4 * TPR + 4 * tl);
+    store_c_streaming(out_row + 4 * tl, v0);
+    store_c_streaming(out_row + 4 * TPR + 4 * tl, v1);
+}
 
 union Pack16 {
     uint4 u;
@@ -104,11 +121,12 @@ __device__ __forceinline__ void gather_group(const __half* __restrict__ Bp, int 
 // Short-row variant of a group: the same U back-to-back loads, but a row of C is stored
 // whenever L steps have been consumed (the step counter is uniform over the wave).
 struct ShortRowState {
-    float* C;
-    int N, feat, L, k, rq;
+    float* C;        // C + first feature of the panel
+    float* stage;    // the team's LDS stage
+    int N, tl, L, k, rq;
 };
 
-template <int U>
+template <int U, int TPR>
 __device__ __forceinline__ void short_rows_group(const __half* __restrict__ Bp, int my_col, float my_val, int my_row,
                                                  int team_base, int j0, float (&acc)[8], ShortRowState& st) {
     uint4_t b[U];
@@ -132,11 +150,7 @@ __device__ __forceinline__ void short_rows_group(const __half* __restrict__ Bp, 
             st.k = 0;
             const int row = shfl_i32(my_row, team_base + st.rq);
             ++st.rq;
-            if (row >= 0) {
-                float* out = st.C + (size_t)row * st.N + st.feat;
-                store_c_streaming(out, (float4_t){acc[0], acc[1], acc[2], acc[3]});
-                store_c_streaming(out + 4, (float4_t){acc[4], acc[5], acc[6], acc[7]});
-            }
+            if (row >= 0) store_row_streaming<TPR>(st.C + (size_t)row * st.N, acc, st.stage, st.tl);
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = 0.f;
         }
@@ -166,11 +180,14 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
     const uint16_t* __restrict__ irr_val, const __half* __restrict__ B, float* __restrict__ C,
     float* __restrict__ scratch, int N) {
     constexpr int G = 64 / TPR;
+    __shared__ __attribute__((aligned(16))) float lds_stage[kWavesPerBlock][64 * 8];
     const int lane = threadIdx.x & 63;
     uint32_t wave;
     if (!xcd_work_item(xs, &wave)) return;
     const int team = lane / TPR, tl = lane % TPR, team_base = team * TPR;
-    const int feat = blockIdx.y * (TPR * 8) + tl * 8;
+    const int panel = blockIdx.y * (TPR * 8);
+    const int feat = panel + tl * 8;
+    float* stage = lds_stage[threadIdx.x >> 6] + team * (TPR * 8);
 
     const uint4 d = waves[wave];
     const uint32_t start = __builtin_amdgcn_readfirstlane(d.x), count = __builtin_amdgcn_readfirstlane(d.y);
@@ -184,9 +201,9 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
 
     if (kind == kWaveZeroRows) {
         for (uint32_t q = team; q < count; q += G) {
-            float* out = C + (size_t)irr_row[dst + q] * N + feat;
-            store_c_streaming(out, (float4_t){0.f, 0.f, 0.f, 0.f});
-            store_c_streaming(out + 4, (float4_t){0.f, 0.f, 0.f, 0.f});
+            float* out = C + (size_t)irr_row[dst + q] * N + panel;
+            store_c_streaming(out + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
+            store_c_streaming(out + 4 * TPR + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
         }
         return;
     }
@@ -202,19 +219,19 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
         const int my_row = tl < n_rows_mine ? irr_row[dst + q0 + tl] : -1;
         // R rows of L entries back to back: the loads of up to eight steps are in flight together,
         // whatever rows they belong to; after every L consumed steps a row is complete and stored
-        ShortRowState st{C, N, feat, L, 0, 0};
+        ShortRowState st{C + panel, stage, N, tl, L, 0, 0};
         const int steps = R * L;
         int j = 0;
-        for (; j + 8 <= steps; j += 8) short_rows_group<8>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+        for (; j + 8 <= steps; j += 8) short_rows_group<8, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
         if (steps & 4) {
-            short_rows_group<4>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+            short_rows_group<4, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
             j += 4;
         }
         if (steps & 2) {
-            short_rows_group<2>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+            short_rows_group<2, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
             j += 2;
         }
-        if (steps & 1) short_rows_group<1>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+        if (steps & 1) short_rows_group<1, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
         return;
     }
 
@@ -246,9 +263,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
         *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
         *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
     } else {
-        float* out = C + (size_t)dst * N + feat;
-        store_c_streaming(out, (float4_t){acc[0], acc[1], acc[2], acc[3]});
-        store_c_streaming(out + 4, (float4_t){acc[4], acc[5], acc[6], acc[7]});
+        store_row_streaming<TPR>(C + (size_t)dst * N + panel, acc, stage, tl);
         keep_streaming_hint();
     }
 }
@@ -489,10 +504,37 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 
     // lane (q = lane/16, r = lane%16) owns features 16c + 4q .. 16c + 4q + 3 of the wave's row r
     if (dst == kNoDst) {
-        if (row < 0) return;
-        float* out = C + (size_t)row * N + panel + 4 * q;
+        if constexpr (NCH % 2 == 0) {
+            // Stores of whole 128-byte lines: lanes r and r^8 trade halves of a pair of chunks,
+            // so that one instruction writes 32 consecutive features of rows 0..7 and the next
+            // those of rows 8..15 (a streaming store of a half line is much slower).
+            const bool low = (lane & 8) == 0;
+            const int row_other = swap_lane8(row);
+            const int row_a = low ? row : row_other, row_b = low ? row_other : row;
+            float* out_a = C + (size_t)row_a * N + panel + 4 * q + (low ? 0 : 16);
+            float* out_b = C + (size_t)row_b * N + panel + 4 * q + (low ? 0 : 16);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) store_c_streaming(out + 16 * c, acc[c]);
+            for (int c = 0; c < NCH; c += 2) {
+                float4_t send, recv;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) send[i] = low ? acc[c + 1][i] : acc[c][i];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) recv[i] = __int_as_float(swap_lane8(__float_as_int(send[i])));
+                float4_t va, vb;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    va[i] = low ? acc[c][i] : recv[i];
+                    vb[i] = low ? recv[i] : acc[c + 1][i];
+                }
+                if (row_a >= 0) store_c_streaming(out_a + 16 * c, va);
+                if (row_b >= 0) store_c_streaming(out_b + 16 * c, vb);
+            }
+        } else {
+            if (row < 0) return;
+            float* out = C + (size_t)row * N + panel + 4 * q;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) store_c_streaming(out + 16 * c, acc[c]);
+        }
         keep_streaming_hint();
     } else {
         float* out = scratch + ((size_t)dst + r) * N + panel + 4 * q;
