@@ -212,11 +212,14 @@ int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
  *   RSH_ARR_IRR_ROW      int32  []              row ids named by kind-0 and kind-2 waves
  * Combine:
  *   RSH_ARR_COMBINE      uint32 [n_combine*4]   {row, first slot, parts, slot stride}
+ * Work split over the eight XCDs (workgroup b serves XCD b mod 8):
+ *   RSH_ARR_TILE_XCD     uint32 [9]             XCD x runs tile items [v[x], v[x+1])
+ *   RSH_ARR_IRR_XCD      uint32 [9]             XCD x runs irregular waves [v[x], v[x+1])
  */
 enum {
     RSH_ARR_WIN_ROW = 0, RSH_ARR_WIN_TILE_OFF, RSH_ARR_TILE_COLID, RSH_ARR_TILE_MASK,
     RSH_ARR_TILE_VAL_OFF, RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL,
-    RSH_ARR_IRR_WAVE, RSH_ARR_IRR_ROW, RSH_ARR_COMBINE, RSH_ARR_COUNT
+    RSH_ARR_IRR_WAVE, RSH_ARR_IRR_ROW, RSH_ARR_COMBINE, RSH_ARR_TILE_XCD, RSH_ARR_IRR_XCD, RSH_ARR_COUNT
 };
 int rsh_plan_array(const rsh_plan_t *plan, int32_t which, const void **ptr, int64_t *count);
 

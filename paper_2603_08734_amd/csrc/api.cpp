@@ -299,6 +299,14 @@ int rsh_plan_array(const rsh_plan_t* plan, int32_t which, const void** ptr, int6
         RSH_CASE(RSH_ARR_IRR_WAVE, h.irr_wave)
         RSH_CASE(RSH_ARR_IRR_ROW, h.irr_row)
         RSH_CASE(RSH_ARR_COMBINE, h.combine)
+        case RSH_ARR_TILE_XCD:
+            *ptr = h.tile_split.start;
+            *count = 9;
+            return RSH_OK;
+        case RSH_ARR_IRR_XCD:
+            *ptr = h.irr_split.start;
+            *count = 9;
+            return RSH_OK;
         default: return RSH_ERR_BAD_OPTION;
     }
 #undef RSH_CASE

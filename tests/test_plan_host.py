@@ -341,3 +341,32 @@ def test_very_long_rows_are_cut_by_column_group_one_group_per_xcd():
     assert np.array_equal(row_ptr, A.row_ptr) and np.array_equal(col_idx, A.col_idx)
     assert np.array_equal(val, A.val.view(np.uint16))
     assert st["n_scratch_slots"] == len(slices) + 0 or st["n_scratch_slots"] >= len(slices)
+
+
+@pytest.mark.parametrize("k", [2, 3, 5])
+def test_xcd_parts_cover_the_work_lists_and_every_xcd_gets_the_same_mix(k):
+    """Each work list is cut into eight runs, one per XCD.  Column-group pieces of group g lie in
+    part g; the other irregular waves are dealt so that the parts cost about the same and hold the
+    same kinds of wave."""
+    A, N, _ = make_config(k, small=True)
+    p = host_plan(A, N, xcd_partition_nnz=64)
+    st = p.stats()
+    for which, n in ((B_.RSH_ARR_TILE_XCD, st["n_tile_items"]), (B_.RSH_ARR_IRR_XCD, st["n_irregular_waves"])):
+        split = p.array(which).astype(np.int64)
+        assert split.shape == (9,) and split[0] == 0 and split[8] == n and np.all(np.diff(split) >= 0)
+    waves = p.array(B_.RSH_ARR_IRR_WAVE).reshape(-1, 4)
+    if waves.shape[0] < 64:
+        return
+    split = p.array(B_.RSH_ARR_IRR_XCD).astype(np.int64)
+    cost = np.array([32 + (int(c) if (int(i) & 3) == 1 else int(c) * (((int(i) >> 8) & 255) + 2) if (int(i) & 3) == 0 else 2 * int(c))
+                     for _, c, _, i in waves], dtype=np.int64)
+    per_xcd = np.array([cost[split[x]:split[x + 1]].sum() for x in range(8)])
+    assert per_xcd.max() <= 1.25 * per_xcd.mean() + 2 * cost.max()
+    # a column of a scratch-bound slice (a column-group piece) is gathered by one XCD only
+    irr_col = p.array(B_.RSH_ARR_IRR_COL)
+    owner = {}
+    for x in range(8):
+        for start, count, dst, info in waves[split[x]:split[x + 1]]:
+            if (int(info) & 7) == 5 and st["n_split_rows"] and int(count) <= 64 * 8:
+                for c in irr_col[int(start):int(start) + int(count)].tolist():
+                    assert owner.setdefault(c, x) == x
