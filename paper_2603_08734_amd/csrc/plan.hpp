@@ -92,12 +92,44 @@ int hardware_threads();
 // Simple static-chunk parallel loop: fn(begin, end, thread_index).
 template <class F>
 void parallel_chunks(int64_t n, int threads, F fn);
+// Same call shape, but the range is handed out in pieces of `grain` on demand: for loops whose
+// cost per index is very uneven (rows of a heavy-tailed matrix).
+template <class F>
+void parallel_dynamic(int64_t n, int threads, int64_t grain, F fn);
+
+// Rows longer than this leave for the residual path under the cost-guided partition
+// (rsh_plan_opts_t::long_row_nnz, 0 = max(4 * mean row length, 64)).
+inline int64_t long_row_threshold(const rsh_csr_t& a, const rsh_plan_opts_t& o) {
+    const double mean = a.n_rows > 0 ? (double)a.nnz / (double)a.n_rows : 0.0;
+    return o.long_row_nnz > 0 ? o.long_row_nnz : (int64_t)(4.0 * mean > 64.0 ? 4.0 * mean : 64.0);
+}
 
 }  // namespace rsh
 
 #include <algorithm>
+#include <atomic>
 #include <thread>
 namespace rsh {
+template <class F>
+void parallel_dynamic(int64_t n, int threads, int64_t grain, F fn) {
+    if (threads <= 1 || n <= grain) {
+        fn((int64_t)0, n, 0);
+        return;
+    }
+    threads = (int)std::min<int64_t>(threads, (n + grain - 1) / grain);
+    std::atomic<int64_t> next{0};
+    std::vector<std::thread> pool;
+    pool.reserve(threads);
+    for (int t = 0; t < threads; ++t)
+        pool.emplace_back([&, t]() {
+            for (;;) {
+                const int64_t b = next.fetch_add(grain);
+                if (b >= n) break;
+                fn(b, std::min(n, b + grain), t);
+            }
+        });
+    for (auto& th : pool) th.join();
+}
 template <class F>
 void parallel_chunks(int64_t n, int threads, F fn) {
     if (threads <= 1 || n < 2) {

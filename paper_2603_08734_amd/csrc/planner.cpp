@@ -185,8 +185,7 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
     // if staging its distinct columns once beats gathering per stored entry.
     enum : uint8_t { kEmpty = 0, kIrr = 1, kWinCls = 2, kLong = 3 };
     std::vector<uint8_t> cls((size_t)n, kWinCls);
-    const double mean = n > 0 ? (double)a.nnz / (double)n : 0.0;
-    const int64_t long_thr = o.long_row_nnz > 0 ? o.long_row_nnz : (int64_t)std::max(4.0 * mean, 64.0);
+    const int64_t long_thr = long_row_threshold(a, o);
     parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
         int32_t others[kMaxWindowRows];
         for (int64_t i = b; i < e; ++i) {

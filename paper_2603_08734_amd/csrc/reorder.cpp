@@ -16,6 +16,10 @@
 //   * a row is isolated when its affinity to both neighbours in the order is below 0.05;
 //     it moves behind its most similar kNN neighbour that is not isolated, else to the tail;
 //   * rows without stored entries go last;
+//   * under the cost-guided partition, rows longer than its long-row threshold go to the residual
+//     path wherever they stand, so they get no neighbours and are no one's candidate (they end up
+//     among the isolated rows at the tail); scoring them was most of the cost on heavy-tailed
+//     matrices and changed nothing;
 //   * the found order replaces the given one only if it lowers the objective by >= 3 %.
 #include "plan.hpp"
 
@@ -108,6 +112,8 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
         }
     });
     const Sim sim{a, w, row_w};
+    const int64_t skip_above = (o.partition == 1 && o.force_path == 0) ? long_row_threshold(a, o) : a.n_cols;
+    auto takes_part = [&](int64_t r) { return a.row_ptr[r + 1] - a.row_ptr[r] <= skip_above; };
 
     // ---- step I: inverted index (column -> rows) over feature columns ----------------------
     // column-major copy of the pattern, restricted to columns that may serve as features
@@ -117,24 +123,30 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
         col_ptr[(size_t)j + 1] = col_ptr[(size_t)j] + ((d >= 2 && d <= kMaxFeatureDegree) ? d : 0);
     }
     std::vector<int32_t> col_rows((size_t)col_ptr[(size_t)a.n_cols]);
+    std::vector<int64_t> col_end((size_t)a.n_cols, 0);   // end of the filled part of each posting list
     {
         std::vector<int64_t> fill(col_ptr.begin(), col_ptr.end() - 1);
-        for (int64_t r = 0; r < n; ++r)
+        for (int64_t r = 0; r < n; ++r) {
+            if (!takes_part(r)) continue;
             for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
                 const int32_t j = a.col_idx[p];
                 const int32_t d = col_deg[(size_t)j];
                 if (d >= 2 && d <= kMaxFeatureDegree) col_rows[(size_t)fill[(size_t)j]++] = (int32_t)r;
             }
+        }
+        // posting lists of columns that lost rows are shorter than their slot: close the gaps
+        for (int64_t j = 0; j < a.n_cols; ++j) col_end[(size_t)j] = fill[(size_t)j];
     }
 
     // ---- step II: top-k neighbours per row ---------------------------------------------------
     std::vector<int32_t> nbr((size_t)n * (size_t)K, -1);
     std::vector<float> nbr_sim((size_t)n * (size_t)K, 0.f);
-    parallel_chunks(n, threads, [&](int64_t b, int64_t e, int) {
+    parallel_dynamic(n, threads, 1024, [&](int64_t b, int64_t e, int) {
         std::vector<int32_t> cand;
         std::vector<std::pair<int32_t, int32_t>> counted;   // (-shared features, row)
         std::vector<std::pair<double, int32_t>> scored;
         for (int64_t r = b; r < e; ++r) {
+            if (!takes_part(r)) continue;
             // the row's lowest-degree eligible columns
             std::pair<int32_t, int32_t> feat[kMaxFeatures];
             int nf = 0;
@@ -153,7 +165,7 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
             cand.clear();
             for (int i = 0; i < nf; ++i) {
                 const int32_t j = feat[i].second;
-                const int64_t cb = col_ptr[(size_t)j], ce = col_ptr[(size_t)j + 1];
+                const int64_t cb = col_ptr[(size_t)j], ce = col_end[(size_t)j];
                 // scan at most kScanPerFeature rows of the posting list, centred on r's own position
                 const int64_t len = ce - cb;
                 int64_t lo = cb;
@@ -270,31 +282,48 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
 
     // ---- step IV a: 2-opt inside blocks of window_rows positions -----------------------------------------
     const int64_t m = (int64_t)seq.size();
-    auto dist = [&](int64_t i, int64_t j) -> double {   // positions; out-of-range = no edge
-        if (i < 0 || j < 0 || i >= m || j >= m) return 0.0;
-        return 1.0 - sim(seq[(size_t)i], seq[(size_t)j]);
-    };
     const int64_t BW = o.window_rows;   // 2-opt works inside each prospective window
     const int64_t n_blocks = (m + BW - 1) / BW;
     for (int parity = 0; parity < 2; ++parity) {
         const int64_t cnt = (n_blocks - parity + 1) / 2;
-        parallel_chunks(cnt, threads, [&](int64_t b, int64_t e, int) {
+        parallel_dynamic(cnt, threads, 64, [&](int64_t b, int64_t e, int) {
+            // The rows of a block and its two outer neighbours never change during the block's
+            // sweeps, only their order does: pair costs are looked up by row slot and computed once.
+            const int L = (int)BW + 2;
+            std::vector<double> memo((size_t)L * (size_t)L);
+            std::vector<int32_t> slot_row((size_t)L);
+            std::vector<int> at((size_t)L);   // at[position - (s - 1)] = slot of the row now at that position
             for (int64_t h = b; h < e; ++h) {
                 const int64_t s = (2 * h + parity) * BW, t = std::min(m, s + BW);
+                const int len = (int)(t - s) + 2;
+                for (int x = 0; x < len; ++x) {
+                    const int64_t pos = s - 1 + x;
+                    slot_row[(size_t)x] = (pos < 0 || pos >= m) ? -1 : seq[(size_t)pos];
+                    at[(size_t)x] = x;
+                }
+                std::fill(memo.begin(), memo.begin() + (long)((size_t)len * (size_t)L), -1.0);
+                auto dist = [&](int x, int y) -> double {   // positions relative to s - 1; a missing neighbour = no edge
+                    const int u = at[(size_t)x], v = at[(size_t)y];
+                    if (slot_row[(size_t)u] < 0 || slot_row[(size_t)v] < 0) return 0.0;
+                    double& d = memo[(size_t)std::min(u, v) * (size_t)L + (size_t)std::max(u, v)];
+                    if (d < 0.0) d = 1.0 - sim(slot_row[(size_t)u], slot_row[(size_t)v]);
+                    return d;
+                };
                 for (int sweep = 0; sweep < kTwoOptSweeps; ++sweep) {
                     bool improved = false;
-                    for (int64_t i = s; i < t - 1; ++i)
-                        for (int64_t j = i + 1; j < t; ++j) {
-                            // reversing seq[i..j] replaces edges (i-1,i),(j,j+1) by (i-1,j),(i,j+1)
+                    for (int i = 1; i < len - 2; ++i)
+                        for (int j = i + 1; j < len - 1; ++j) {
+                            // reversing positions i..j replaces edges (i-1,i),(j,j+1) by (i-1,j),(i,j+1)
                             const double before = dist(i - 1, i) + dist(j, j + 1);
                             const double after = dist(i - 1, j) + dist(i, j + 1);
                             if (after + 1e-12 < before) {
-                                std::reverse(seq.begin() + i, seq.begin() + j + 1);
+                                std::reverse(at.begin() + i, at.begin() + j + 1);
                                 improved = true;
                             }
                         }
                     if (!improved) break;
                 }
+                for (int x = 1; x < len - 1; ++x) seq[(size_t)(s - 1 + x)] = slot_row[(size_t)at[(size_t)x]];
             }
         });
     }
