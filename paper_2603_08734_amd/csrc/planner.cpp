@@ -264,6 +264,21 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
             }
         }
     }
+    // A dense-fragment part that holds under a hundredth of the stored entries returns less than
+    // the launch of its kernel costs: its rows join the residual path.
+    {
+        int64_t nnz_win = 0;
+        for (int32_t r : out.win_row)
+            if (r >= 0) nnz_win += row_len(a, r);
+        if (nnz_win * 100 < a.nnz) {
+            std::vector<uint8_t> in_win((size_t)n, 0);
+            for (int32_t r : out.win_row)
+                if (r >= 0) in_win[(size_t)r] = 1;
+            for (int64_t i = 0; i < n; ++i)
+                if (in_win[(size_t)order[i]]) cls[i] = kIrr;
+            out.win_row.clear();
+        }
+    }
     for (int64_t i = 0; i < n; ++i) {
         if (cls[i] == kEmpty) out.empty.push_back(order[i]);
         else if (cls[i] == kIrr || cls[i] == kLong) out.irregular.push_back(order[i]);
