@@ -95,8 +95,19 @@ union Pack16 {
 // pairs held by the team's lanes.  Straight-line code on purpose: all U row loads are issued
 // back to back and only then consumed (a branch between two loads makes the compiler wait for
 // the first before it issues the second).
+// B rows are addressed as a wave-uniform base plus a 32-bit byte offset (the plan guarantees
+// n_cols * 2N < 2^32): one address register per load in flight instead of two.
+struct BRows {
+    const char* base;      // B + first feature of the panel (wave-uniform)
+    uint32_t row_bytes;    // 2N
+    uint32_t lane_byte;    // 16 * lane-in-team
+    __device__ __forceinline__ const uint4_t* row(int c) const {
+        return reinterpret_cast<const uint4_t*>(base + ((uint32_t)c * row_bytes + lane_byte));
+    }
+};
+
 template <int U>
-__device__ __forceinline__ void gather_group(const __half* __restrict__ Bp, int N, int my_col, float my_val,
+__device__ __forceinline__ void gather_group(const BRows& Bp, int my_col, float my_val,
                                              int src_lane0, float (&acc)[8]) {
     uint4_t b[U];
     float v[U];
@@ -104,7 +115,7 @@ __device__ __forceinline__ void gather_group(const __half* __restrict__ Bp, int 
     for (int u = 0; u < U; ++u) {
         const int c = shfl_i32(my_col, src_lane0 + u);
         v[u] = shfl_f32(my_val, src_lane0 + u);
-        b[u] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * N);
+        b[u] = *Bp.row(c);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -127,7 +138,7 @@ struct ShortRowState {
 };
 
 template <int U, int TPR>
-__device__ __forceinline__ void short_rows_group(const __half* __restrict__ Bp, int my_col, float my_val, int my_row,
+__device__ __forceinline__ void short_rows_group(const BRows& Bp, int my_col, float my_val, int my_row,
                                                  int team_base, int j0, float (&acc)[8], ShortRowState& st) {
     uint4_t b[U];
     float v[U];
@@ -135,7 +146,7 @@ __device__ __forceinline__ void short_rows_group(const __half* __restrict__ Bp, 
     for (int u = 0; u < U; ++u) {
         const int c = shfl_i32(my_col, team_base + j0 + u);
         v[u] = shfl_f32(my_val, team_base + j0 + u);
-        b[u] = *reinterpret_cast<const uint4_t*>(Bp + (size_t)c * st.N);
+        b[u] = *Bp.row(c);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -158,23 +169,23 @@ __device__ __forceinline__ void short_rows_group(const __half* __restrict__ Bp, 
 }
 
 // `steps` gather steps starting at entry j0, as groups of 8, 4, 2, 1.
-__device__ __forceinline__ void gather_steps(const __half* __restrict__ Bp, int N, int my_col, float my_val,
+__device__ __forceinline__ void gather_steps(const BRows& Bp, int my_col, float my_val,
                                              int team_base, int steps, float (&acc)[8]) {
     int j = 0;
-    for (; j + 8 <= steps; j += 8) gather_group<8>(Bp, N, my_col, my_val, team_base + j, acc);
+    for (; j + 8 <= steps; j += 8) gather_group<8>(Bp, my_col, my_val, team_base + j, acc);
     if (steps & 4) {
-        gather_group<4>(Bp, N, my_col, my_val, team_base + j, acc);
+        gather_group<4>(Bp, my_col, my_val, team_base + j, acc);
         j += 4;
     }
     if (steps & 2) {
-        gather_group<2>(Bp, N, my_col, my_val, team_base + j, acc);
+        gather_group<2>(Bp, my_col, my_val, team_base + j, acc);
         j += 2;
     }
-    if (steps & 1) gather_group<1>(Bp, N, my_col, my_val, team_base + j, acc);
+    if (steps & 1) gather_group<1>(Bp, my_col, my_val, team_base + j, acc);
 }
 
 template <int TPR>
-__global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
+__global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void rsh_irregular_kernel(
     const uint4* __restrict__ waves, XcdSplit xs,
     const int32_t* __restrict__ irr_row, const int32_t* __restrict__ irr_col,
     const uint16_t* __restrict__ irr_val, const __half* __restrict__ B, float* __restrict__ C,
@@ -193,7 +204,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
     const uint32_t start = __builtin_amdgcn_readfirstlane(d.x), count = __builtin_amdgcn_readfirstlane(d.y);
     const uint32_t dst = __builtin_amdgcn_readfirstlane(d.z), info = __builtin_amdgcn_readfirstlane(d.w);
     const uint32_t kind = info & kWaveKindMask;
-    const __half* Bp = B + feat;
+    const BRows Bp{reinterpret_cast<const char*>(B + panel), 2u * (uint32_t)N, 16u * (uint32_t)tl};
 
     float acc[8];
 #pragma unroll
@@ -251,7 +262,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_irregular_kernel(
             nxt_val = p < len ? __half2float(__ushort_as_half(irr_val[pb + p])) : 0.f;
         }
         const int steps = (int)min((uint32_t)TPR, max_len - base);
-        gather_steps(Bp, N, my_col, my_val, team_base, steps, acc);
+        gather_steps(Bp, my_col, my_val, team_base, steps, acc);
     }
 #pragma unroll
     for (int off = TPR; off < 64; off <<= 1)
