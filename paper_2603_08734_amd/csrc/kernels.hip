@@ -50,10 +50,11 @@ __device__ __forceinline__ uint32_t bits_below_lane(uint64_t m) {
 
 // Rows of C are written once and never read back by these kernels.  Stored the ordinary way
 // they pass through the XCD's L2 and displace the rows of B that the gathers reuse; the
-// streaming (nontemporal) form keeps them from doing so.  Partial results that the combine
-// pass reads next are stored the ordinary way.  Where a streaming store and an ordinary one sit
-// on sibling paths, the streaming path ends in keep_streaming_hint(): the compiler otherwise
-// folds the two stores into one and drops the hint.
+// streaming (nontemporal) form keeps them from doing so.  Partial sums for the combine pass:
+// the irregular kernel streams them too (measured faster), the tile kernel stores them the
+// ordinary way (measured faster for the combine pass that follows).  A streaming store and an
+// ordinary one must not sit on sibling paths that end alike (the compiler folds the two into one
+// store and drops the hint): the streaming path then ends in keep_streaming_hint().
 __device__ __forceinline__ void store_c_streaming(float* p, float4_t v) {
     __builtin_nontemporal_store(v, reinterpret_cast<float4_t*>(p));
 }
@@ -197,7 +198,6 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
     if (!xcd_work_item(xs, &wave)) return;
     const int team = lane / TPR, tl = lane % TPR, team_base = team * TPR;
     const int panel = blockIdx.y * (TPR * 8);
-    const int feat = panel + tl * 8;
     float* stage = lds_stage[threadIdx.x >> 6] + team * (TPR * 8);
 
     const uint4 d = waves[wave];
@@ -269,14 +269,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] += shfl_f32(acc[i], lane ^ off);
     if (team != 0) return;
-    if (info & kWaveToScratch) {
-        float* out = scratch + (size_t)dst * N + feat;
-        *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    } else {
-        store_row_streaming<TPR>(C + (size_t)dst * N + panel, acc, stage, tl);
-        keep_streaming_hint();
-    }
+    store_row_streaming<TPR>(((info & kWaveToScratch) ? scratch : C) + (size_t)dst * N + panel, acc, stage, tl);
 }
 
 // ---------------------------------------------------------------------------
@@ -514,44 +507,46 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     }
 
     // lane (q = lane/16, r = lane%16) owns features 16c + 4q .. 16c + 4q + 3 of the wave's row r
-    if (dst == kNoDst) {
-        if constexpr (NCH % 2 == 0) {
-            // Stores of whole 128-byte lines: lanes r and r^8 trade halves of a pair of chunks,
-            // so that one instruction writes 32 consecutive features of rows 0..7 and the next
-            // those of rows 8..15 (a streaming store of a half line is much slower).
-            const bool low = (lane & 8) == 0;
-            const int row_other = swap_lane8(row);
-            const int row_a = low ? row : row_other, row_b = low ? row_other : row;
-            float* out_a = C + (size_t)row_a * N + panel + 4 * q + (low ? 0 : 16);
-            float* out_b = C + (size_t)row_b * N + panel + 4 * q + (low ? 0 : 16);
-#pragma unroll
-            for (int c = 0; c < NCH; c += 2) {
-                float4_t send, recv;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) send[i] = low ? acc[c + 1][i] : acc[c][i];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) recv[i] = __int_as_float(swap_lane8(__float_as_int(send[i])));
-                float4_t va, vb;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    va[i] = low ? acc[c][i] : recv[i];
-                    vb[i] = low ? recv[i] : acc[c + 1][i];
-                }
-                if (row_a >= 0) store_c_streaming(out_a + 16 * c, va);
-                if (row_b >= 0) store_c_streaming(out_b + 16 * c, vb);
-            }
-        } else {
-            if (row < 0) return;
-            float* out = C + (size_t)row * N + panel + 4 * q;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) store_c_streaming(out + 16 * c, acc[c]);
-        }
-        keep_streaming_hint();
-    } else {
+    if (dst != kNoDst) {
+        // partial sums of a split window: ordinary stores (measured: the combine pass is faster
+        // when these went through L2)
         float* out = scratch + ((size_t)dst + r) * N + panel + 4 * q;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(out + 16 * c) = acc[c];
+        return;
     }
+    if constexpr (NCH % 2 == 0) {
+        // Stores of whole 128-byte lines: lanes r and r^8 trade halves of a pair of chunks,
+        // so that one instruction writes 32 consecutive features of rows 0..7 and the next
+        // those of rows 8..15 (a streaming store of a half line is much slower).
+        const bool low = (lane & 8) == 0;
+        const int row_other = swap_lane8(row);
+        const int row_a = low ? row : row_other, row_b = low ? row_other : row;
+        float* out_a = C + (size_t)row_a * N + panel + 4 * q + (low ? 0 : 16);
+        float* out_b = C + (size_t)row_b * N + panel + 4 * q + (low ? 0 : 16);
+#pragma unroll
+        for (int c = 0; c < NCH; c += 2) {
+            float4_t send, recv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) send[i] = low ? acc[c + 1][i] : acc[c][i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) recv[i] = __int_as_float(swap_lane8(__float_as_int(send[i])));
+            float4_t va, vb;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                va[i] = low ? acc[c][i] : recv[i];
+                vb[i] = low ? recv[i] : acc[c + 1][i];
+            }
+            if (row_a >= 0) store_c_streaming(out_a + 16 * c, va);
+            if (row_b >= 0) store_c_streaming(out_b + 16 * c, vb);
+        }
+    } else {
+        if (row < 0) return;
+        float* out = C + (size_t)row * N + panel + 4 * q;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) store_c_streaming(out + 16 * c, acc[c]);
+    }
+    keep_streaming_hint();
 }
 
 // ---------------------------------------------------------------------------
