@@ -28,6 +28,55 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+ABLATIONS = {
+    # Section 4.3.2: the row-length threshold of Algorithm 1 decides what leaves for the residual path
+    "thresholds": [dict(tau_nnz=t) for t in (0, 1, 2, 4, 6, 8, 12, 16)] + [dict(min_reuse=m) for m in (0.0, 1.0, 1.25, 1.5, 2.0, 3.0)],
+    # Section 4.3.3: identity -> spanning-tree walk -> + 2-opt -> + relocation of isolated rows
+    "reorder": [dict(reorder=0), dict(reorder=2), dict(reorder=3), dict(reorder=1)],
+    # window height and fragment width (the paper fixes 16 x 8 for its MMA shape)
+    "shape": [dict(window_rows=w, tile_k=k) for w in (16, 32, 64) for k in (16, 32)],
+}
+
+
+def ablation(args, A, N, B_np) -> int:
+    """One plan + timed SpMM per setting; everything else at its default."""
+    import numpy as np
+    import torch
+    from paper_2603_08734_amd import Plan
+
+    B = torch.from_numpy(B_np.view(np.int16)).cuda().view(torch.float16)
+    C = torch.empty((A.n_rows, N), dtype=torch.float32, device="cuda")
+    rows = []
+    for setting in ABLATIONS[args.ablation]:
+        t0 = time.perf_counter()
+        plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, **setting)
+        plan_s = time.perf_counter() - t0
+        st = plan.stats()
+        for _ in range(args.warmup):
+            plan.spmm(B, C)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            plan.spmm(B, C)
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        rows.append({
+            "setting": setting, "ms_per_step": round(ms, 4), "gflops": round(2.0 * A.nnz * N / ms / 1e6, 1),
+            "plan_s": round(plan_s, 2), "window_rows": st["window_rows"], "tile_k": st["tile_k"],
+            "tau_nnz": st["tau_nnz"], "windows": st["n_windows"], "fragments": st["n_tiles"],
+            "nnz_tile_share": round(st["nnz_tile"] / max(1, A.nnz), 4),
+            "mean_nnz_per_fragment": round(st["nnz_tile"] / max(1, st["n_tiles"]), 2),
+            "mean_nnz_per_window": round(st["nnz_tile"] / max(1, st["n_windows"]), 1),
+            "distinct_columns_per_window": round(st["sum_window_cols"] / max(1, st["n_windows"]), 1),
+            "objective_given": round(st["reorder_cost_given"], 1), "objective_found": round(st["reorder_cost_found"], 1),
+        })
+        plan.destroy()
+        print("ablation %s %s: %.4f ms" % (args.ablation, setting, ms), file=sys.stderr, flush=True)
+    print(json.dumps({"ablation": args.ablation, "config": {"workload": A.meta["name"], "nnz": A.nnz, "N": N},
+                      "steps": args.steps, "warmup": args.warmup, "rows": rows}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -37,6 +86,9 @@ def main() -> int:
     ap.add_argument("--reorder", type=int, default=-1, help="override the plan's reorder option")
     ap.add_argument("--opt", action="append", default=[], help="plan option override name=value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ablation", choices=["thresholds", "reorder", "shape"], default=None,
+                    help="instead of the benchmark line: sweep one planning knob on --config and print one JSON "
+                         "line with a row per setting (the paper's Sections 4.3.2 and 4.3.3 on synthetic data)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB (for scaling profiler traffic counters)")
     args = ap.parse_args()
@@ -56,6 +108,9 @@ def main() -> int:
     A, N, dist = make_config(args.config)
     B_np = dense_B(A.n_cols, N, dist, seed=1)
     gen_s = time.perf_counter() - t0
+
+    if args.ablation:
+        return ablation(args, A, N, B_np)
 
     opts = {}
     if args.reorder >= 0:

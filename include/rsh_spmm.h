@@ -66,7 +66,9 @@ typedef struct {
                                  first, the rest is grouped W eligible rows at a time, and a window
                                  whose column reuse nnz/|U| is below min_reuse is dissolved        */
     int32_t reorder;      /* 0 = keep the given row order, 1 (default) = locality-aware reordering
-                             (Section 3.4); the found order is used only if it lowers the objective by 3 % */
+                             (Section 3.4); the found order is used only if it lowers the objective by 3 %.
+                             For the stage-by-stage comparison of Section 4.3.3: 2 = stop after the
+                             spanning-tree walk, 3 = tree walk + 2-opt (no relocation of isolated rows) */
     int32_t knn_k;        /* neighbours kept per row in the kNN graph (Algorithm 3, step II)     */
     float alpha;          /* exponent of the column weight w_j = d_j^-alpha (Section 3.4)        */
     int32_t max_tiles_per_item; /* bound on fragments per tile work item; 0 = auto              */

@@ -117,7 +117,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         (o.tile_k != 0 && o.tile_k != 16 && o.tile_k != 32))
         return RSH_ERR_BAD_OPTION;
     if (o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2) return RSH_ERR_BAD_OPTION;
-    if (o.reorder < 0 || o.reorder > 1 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
+    if (o.reorder < 0 || o.reorder > 3 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.threads < 0) return RSH_ERR_BAD_OPTION;
 

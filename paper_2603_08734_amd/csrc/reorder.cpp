@@ -284,7 +284,7 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     const int64_t m = (int64_t)seq.size();
     const int64_t BW = o.window_rows;   // 2-opt works inside each prospective window
     const int64_t n_blocks = (m + BW - 1) / BW;
-    for (int parity = 0; parity < 2; ++parity) {
+    for (int parity = 0; parity < 2 && o.reorder != 2; ++parity) {   // reorder == 2 stops after the tree walk
         const int64_t cnt = (n_blocks - parity + 1) / 2;
         parallel_dynamic(cnt, threads, 64, [&](int64_t b, int64_t e, int) {
             // The rows of a block and its two outer neighbours never change during the block's
@@ -330,6 +330,7 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
 
     // ---- step IV b: isolated rows move next to their best non-isolated neighbour ----------------
     std::vector<uint8_t> isolated((size_t)n, 0);
+    if (o.reorder == 1)   // reorder == 2, 3 stop before this step (stage-by-stage comparison, Section 4.3.3)
     parallel_chunks(m, threads, [&](int64_t b, int64_t e, int) {
         for (int64_t i = b; i < e; ++i) {
             const double left = i > 0 ? sim(seq[(size_t)i - 1], seq[(size_t)i]) : 0.0;
