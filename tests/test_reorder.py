@@ -90,3 +90,25 @@ def test_rows_without_entries_go_last_and_decode_survives_reordering():
     row_ptr, col_idx, val, _ = p.decode()
     assert np.array_equal(row_ptr, A.row_ptr) and np.array_equal(col_idx, A.col_idx)
     assert np.array_equal(val, A.val.view(np.uint16))
+
+
+def test_stages_of_the_reordering_can_be_stopped_early():
+    """reorder = 2 stops after the spanning-tree walk, 3 after the 2-opt pass, 1 runs all stages
+    (Section 4.3.3 compares them).  2-opt only ever lowers the objective; every stage yields a
+    permutation and a plan that decodes to the input."""
+    A = hidden_communities(n_comm=48, seed=7)
+    cost = {}
+    for level in (2, 3, 1):
+        p = host_plan(A, 64, reorder=level, force_path=2)
+        order = p.row_order()
+        assert np.array_equal(np.sort(order), np.arange(A.n_rows))
+        st = p.stats()
+        cost[level] = st["reorder_cost_found"]
+        if st["reorder_cost_found"] <= 0.97 * st["reorder_cost_given"]:
+            used = osim.path_cost(A.row_ptr, A.col_idx, A.n_cols, order, 0.5)
+            assert abs(used - st["reorder_cost_found"]) <= 1e-9 * max(1.0, used)
+        row_ptr, col_idx, val, _ = p.decode()
+        assert np.array_equal(row_ptr, A.row_ptr) and np.array_equal(col_idx, A.col_idx)
+    assert cost[3] <= cost[2] + 1e-9
+    with pytest.raises(Exception):
+        host_plan(A, 64, reorder=4)
