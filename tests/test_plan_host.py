@@ -268,6 +268,11 @@ def test_abi_error_codes():
     assert create(rp, ci, v, A.n_rows, A.n_cols, o=o2) == B_.RSH_ERR_BAD_OPTION
     o3 = binding.rsh_plan_opts_default(); o3.upload = 0; o3.alpha = 0.0
     assert create(rp, ci, v, A.n_rows, A.n_cols, o=o3) == B_.RSH_ERR_BAD_OPTION
+    # the kernels address B with 32-bit byte offsets: n_cols * 2N must stay below 2^32
+    one = np.array([0, 1], dtype=np.int64)
+    c0, v0 = np.zeros(1, np.int32), np.ones(1, np.uint16)
+    assert create(one, c0, v0, 1, 1 << 22, N=512) == B_.RSH_ERR_TOO_LARGE
+    assert create(one, c0, v0, 1, (1 << 22) - 1, N=512) == B_.RSH_OK
     # empty matrices are legal
     z = np.zeros(1, dtype=np.int64)
     assert create(z, np.zeros(0, np.int32), np.zeros(0, np.uint16), 0, 0) == B_.RSH_OK
