@@ -165,6 +165,11 @@ def main() -> int:
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dominant)),
                 "algorithmic_bytes": int(alg_bytes), "kernel_ms": round(kernel_ms[dominant], 4)}
+    if roofline["traffic"] and kernel_ms[dominant] > 0:
+        # what the memory system actually moved per launch (counters, profiles/) over this run's kernel time
+        moved = roofline["traffic"] / (kernel_ms[dominant] * 1e-3) / 1e9
+        roofline["traffic_GBps"] = round(moved, 1)
+        roofline["traffic_frac"] = round(moved / HBM_PEAK_GBPS, 4)
 
     out = {
         "metric": "SpMM GFLOP/s (2*nnz*N/t), N=%d, 1 MI355X" % N, "value": round(gflops, 1), "unit": "GFLOP/s",
