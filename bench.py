@@ -83,6 +83,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline R-MAT graph)")
+    ap.add_argument("--features", type=int, default=0,
+                    help="override the configuration's feature width N (the paper sweeps 64..512); 0 = as configured")
     ap.add_argument("--reorder", type=int, default=-1, help="override the plan's reorder option")
     ap.add_argument("--opt", action="append", default=[], help="plan option override name=value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -106,6 +108,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     t0 = time.perf_counter()
     A, N, dist = make_config(args.config)
+    if args.features:
+        N = args.features
     B_np = dense_B(A.n_cols, N, dist, seed=1)
     gen_s = time.perf_counter() - t0
 

@@ -28,7 +28,11 @@ Geometry make_geometry(int N, int window_rows, int tile_k) {
     g.nw = window_rows / kW;
     g.tile_k = tile_k;
     g.cpl = tile_k / 4;
-    g.irr_panel = gcd_int(N, 512);
+    // Feature panels run one after the other (gridDim.y).  The irregular kernel takes 128 features
+    // per panel: a gathered row of B then occupies 256 bytes of L2 whatever N is, and measured on
+    // the R-MAT case 128 beats both wider panels (N = 512: 2.9 ms against 3.4 at 256 and 4.0 at 512)
+    // and narrower ones (N = 128: 0.94 ms at 64 against 0.69).  The tile kernel measures best at 256.
+    g.irr_panel = gcd_int(N, 128);
     g.irr_tpr = g.irr_panel / 8;
     g.irr_teams = 64 / g.irr_tpr;
     g.tile_panel = gcd_int(N, 256);
