@@ -246,3 +246,42 @@ def test_random_matrices_with_random_options():
         (C,), _ = gpu_spmm(A, B, N, **opts)
         C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
         assert_parity(C, C_ref, S, f"random case {case}")
+
+
+@pytest.mark.gpu
+def test_spmm_can_be_captured_in_a_graph_and_replayed():
+    """rsh_spmm only launches kernels on the given stream (no allocation, no memset, no host wait),
+    so it can be recorded into a HIP graph.  Every replay -- with the operand changed and eager
+    work and synchronisations in between -- must give what an eager call gives."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, N, dist = make_config(2, small=True)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, xcd_partition_nnz=32, max_tiles_per_item=3)
+    st = plan.stats()
+    assert st["nnz_tile"] > 0 and st["nnz_irregular"] > 0 and st["n_combine"] > 0     # all three kernels run
+    Bs = torch.zeros((A.n_cols, N), dtype=torch.float16, device="cuda")
+    Cs = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.spmm(Bs, Cs)                     # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.spmm(Bs, Cs)
+    for seed in (5, 6, 7):
+        B = dense_B(A.n_cols, N, dist, seed=seed)
+        Bs.copy_(torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16))
+        Cs.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Cs.cpu().numpy()
+        C_eager = torch.full_like(Cs, float("nan"))
+        plan.spmm(Bs, C_eager)
+        torch.cuda.synchronize()
+        assert np.array_equal(got, C_eager.cpu().numpy()), "a replay differs from the eager call"
+        R, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+        assert_parity(got, R, S, f"graph replay, seed {seed}")
+    plan.destroy()
