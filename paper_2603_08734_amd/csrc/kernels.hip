@@ -74,11 +74,6 @@ __device__ __forceinline__ void store_row_streaming(float* out_row, const float 
     store_c_streaming(out_row + 4 * TPR + 4 * tl, v1);
 }
 
-union Pack16 {
-    uint4 u;
-    __half h[8];
-};
-
 // ---------------------------------------------------------------------------
 // Irregular rows.  A wave is G = 64/TPR teams of TPR lanes; lane t of a team owns
 // features [8t, 8t+8) of the current panel, so a team reads one B row segment as TPR

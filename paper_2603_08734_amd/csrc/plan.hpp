@@ -9,7 +9,6 @@ namespace rsh {
 
 constexpr int kW = 16;  // rows per sub-window (MFMA N extent); a window is nw of them
 constexpr int kMaxWindowRows = 64;
-constexpr int kK = 16;  // default condensed columns per fragment (MFMA K extent); 32 is the other choice
 constexpr uint32_t kNoDst = 0xffffffffu;
 // irregular wave descriptor {start, count, dst, info}; info = kind | flags | L << 8 | R << 16
 constexpr uint32_t kWaveShortRows = 0u;  // `count` rows of L entries each, R rows per team; dst indexes irr_row
