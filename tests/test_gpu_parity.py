@@ -149,17 +149,28 @@ def test_row_permutation_metamorphic():
     assert_parity(C, C_ref, S, "original rows")
 
 
-@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
-def test_full_size_configs_on_sampled_rows(k):
-    """The five named workloads at full size, in the plan configuration the benchmark times;
-    the oracle recomputes a sample of output rows (random rows, the longest rows, the first
-    and last rows) one by one."""
+FULL_SIZE_CASES = [
+    (1, 0, {}), (2, 0, {}), (3, 0, {}), (4, 0, {}), (5, 0, {}),                       # as the benchmark times them
+    (2, 0, dict(reorder=0, hub_windows=1, min_reuse=1.5)),                             # hub rows in windows: all three kernels, split windows
+    (2, 512, dict(reorder=0)),                                                        # four feature panels in the irregular kernel
+    (3, 0, dict(window_rows=64, tile_k=32)),                                          # 64-row windows on 32-column fragments
+    (4, 0, dict(reorder=2, window_rows=32, tile_k=16)),                               # tree walk only, two waves per window
+    (5, 0, dict(window_rows=16, tile_k=32, max_tiles_per_item=7)),                    # many partial blocks per window
+]
+
+
+@pytest.mark.parametrize("k,features,opts", FULL_SIZE_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_full_size_configs_on_sampled_rows(k, features, opts):
+    """The five named workloads at full size, in the plan configuration the benchmark times and
+    in a few others that exercise the remaining kernel variants at scale; the oracle recomputes a
+    sample of output rows (random rows, the longest rows, the first and last rows) one by one."""
     torch = _torch()
     from paper_2603_08734_amd import Plan
     A, N, dist = make_config(k)
+    N = features or N
     B = dense_B(A.n_cols, N, dist, seed=1)
-    print(f"case full config={k} rows={A.n_rows} nnz={A.nnz} N={N}", flush=True)
-    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N)
+    print(f"case full config={k} rows={A.n_rows} nnz={A.nnz} N={N} opts={opts}", flush=True)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, **opts)
     Bd = torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16)
     C = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
     plan.spmm(Bd, C)
