@@ -674,8 +674,6 @@ int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void*
             case 4: launch_irregular_t<4>(d, B, C, st); break;
             case 8: launch_irregular_t<8>(d, B, C, st); break;
             case 16: launch_irregular_t<16>(d, B, C, st); break;
-            case 32: launch_irregular_t<32>(d, B, C, st); break;
-            case 64: launch_irregular_t<64>(d, B, C, st); break;
             default: return RSH_ERR_UNSUPPORTED_N;
         }
     }
