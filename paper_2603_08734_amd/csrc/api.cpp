@@ -101,6 +101,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->window_schedule = 1;
     o->hub_windows = 0;
     o->xcd_partition_nnz = 0;
+    o->transpose = 0;
     o->upload = 1;
     o->threads = 0;
     return RSH_OK;
@@ -119,12 +120,44 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     if (o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2) return RSH_ERR_BAD_OPTION;
     if (o.reorder < 0 || o.reorder > 3 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
-    if (o.threads < 0) return RSH_ERR_BAD_OPTION;
+    if (o.threads < 0 || o.transpose < 0 || o.transpose > 1) return RSH_ERR_BAD_OPTION;
 
     const auto t_all = std::chrono::steady_clock::now();
     auto t0 = t_all;
     int rc = rsh::validate_csr(*csr);
     if (rc) return rc;
+    // A^T: counting sort by column; rows are visited in ascending order, so the columns of every
+    // row of A^T come out ascending and the result is canonical CSR again
+    std::vector<int64_t> t_row_ptr;
+    std::vector<int32_t> t_col_idx;
+    std::vector<uint16_t> t_val;
+    rsh_csr_t transposed;
+    if (o.transpose) {
+        if (csr->n_rows >= (1ll << 31)) return RSH_ERR_TOO_LARGE;
+        try {
+            t_row_ptr.assign((size_t)csr->n_cols + 1, 0);
+            t_col_idx.resize((size_t)csr->nnz);
+            t_val.resize((size_t)csr->nnz);
+        } catch (const std::bad_alloc&) {
+            return RSH_ERR_OOM;
+        }
+        for (int64_t p = 0; p < csr->nnz; ++p) ++t_row_ptr[(size_t)csr->col_idx[p] + 1];
+        for (int64_t j = 0; j < csr->n_cols; ++j) t_row_ptr[(size_t)j + 1] += t_row_ptr[(size_t)j];
+        std::vector<int64_t> fill(t_row_ptr.begin(), t_row_ptr.end() - 1);
+        for (int64_t i = 0; i < csr->n_rows; ++i)
+            for (int64_t p = csr->row_ptr[i]; p < csr->row_ptr[i + 1]; ++p) {
+                const int64_t at = fill[(size_t)csr->col_idx[p]]++;
+                t_col_idx[(size_t)at] = (int32_t)i;
+                t_val[(size_t)at] = csr->val_f16[p];
+            }
+        transposed.n_rows = csr->n_cols;
+        transposed.n_cols = csr->n_rows;
+        transposed.nnz = csr->nnz;
+        transposed.row_ptr = t_row_ptr.data();
+        transposed.col_idx = t_col_idx.data();
+        transposed.val_f16 = t_val.data();
+        csr = &transposed;
+    }
     if (csr->nnz >= (1ll << 31) || csr->n_rows >= (1ll << 31) - 1 || csr->n_cols >= (1ll << 31) ||
         csr->n_cols * 2 * (int64_t)N >= (1ll << 31) * 2)
         return RSH_ERR_TOO_LARGE;

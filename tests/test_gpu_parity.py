@@ -296,3 +296,24 @@ def test_spmm_can_be_captured_in_a_graph_and_replayed():
         R, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
         assert_parity(got, R, S, f"graph replay, seed {seed}")
     plan.destroy()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("k", [2, 5])
+def test_transposed_product(k):
+    """transpose = 1: C = A^T B against the oracle run on a transposition made by scipy."""
+    import scipy.sparse as sp
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, N, dist = make_config(k, small=True)
+    At = sp.csr_matrix((A.val.view(np.uint16), A.col_idx, A.row_ptr), shape=(A.n_rows, A.n_cols)).T.tocsr()
+    At.sort_indices()
+    B = dense_B(A.n_rows, N, dist, seed=40 + k)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, transpose=1)
+    Bd = torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16)
+    C = torch.full((A.n_cols, N), float("nan"), dtype=torch.float32, device="cuda")
+    plan.spmm(Bd, C)
+    torch.cuda.synchronize()
+    C_ref, S, _ = oracle.spmm(At.indptr.astype(np.int64), At.indices.astype(np.int32), At.data.view(np.float16), B)
+    assert_parity(C.cpu().numpy(), C_ref, S, f"transposed config {k}")
+    plan.destroy()

@@ -375,3 +375,22 @@ def test_xcd_parts_cover_the_work_lists_and_every_xcd_gets_the_same_mix(k):
             if (int(info) & 7) == 5 and st["n_split_rows"] and int(count) <= 64 * 8:
                 for c in irr_col[int(start):int(start) + int(count)].tolist():
                     assert owner.setdefault(c, x) == x
+
+
+@pytest.mark.parametrize("k", [2, 4, 5])
+def test_transposed_plan_decodes_to_the_transpose(k):
+    """transpose = 1 plans C = A^T B: the plan's decode is the canonical CSR of A^T (checked against a
+    transposition written out entry by entry), values bit for bit."""
+    A, N, _ = make_config(k, small=True)
+    p = host_plan(A, N, transpose=1)
+    st = p.stats()
+    assert (st["n_rows"], st["n_cols"], st["nnz"]) == (A.n_cols, A.n_rows, A.nnz)
+    row_ptr, col_idx, val, _ = p.decode()
+    rows = np.repeat(np.arange(A.n_rows), A.row_nnz())
+    order = np.lexsort((rows, A.col_idx))                 # by column, then by row
+    want_ptr = np.zeros(A.n_cols + 1, dtype=np.int64)
+    np.cumsum(np.bincount(A.col_idx, minlength=A.n_cols), out=want_ptr[1:])
+    assert np.array_equal(row_ptr, want_ptr)
+    assert np.array_equal(col_idx, rows[order].astype(np.int32))
+    assert np.array_equal(val, A.val.view(np.uint16)[order])
+    assert np.array_equal(np.sort(p.row_order()), np.arange(A.n_cols))
