@@ -43,6 +43,21 @@ __device__ __forceinline__ float shfl_f32(float v, int src_lane) {
 // Value held by lane (l ^ 8): rotation by 8 inside each row of 16 lanes.
 __device__ __forceinline__ int swap_lane8(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false); }
 
+// Sum of v over the lanes that differ from this one by a multiple of TPR (TPR = 2, 4, 8, 16):
+// after the call every lane holds the sum of its counterparts in all 64 / TPR teams.  Inside a
+// row of 16 lanes v += v rotated by 8, 4, ... TPR lanes (DPP row_ror); across rows a cross-lane
+// read of lane ^ 16 and lane ^ 32.  (v_permlane16_swap / v_permlane32_swap do the second part in
+// registers as well, and measured 6 % slower on the 16-lane teams of N >= 128.)
+template <int TPR>
+__device__ __forceinline__ float sum_over_teams(float v, int lane) {
+    if constexpr (TPR <= 8) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));
+    if constexpr (TPR <= 4) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xf, 0xf, false));
+    if constexpr (TPR <= 2) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x122, 0xf, 0xf, false));
+    v += shfl_f32(v, lane ^ 16);
+    v += shfl_f32(v, lane ^ 32);
+    return v;
+}
+
 // Number of set bits of a 64-bit wave-uniform mask below this lane.
 __device__ __forceinline__ uint32_t bits_below_lane(uint64_t m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
@@ -260,9 +275,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
         gather_steps(Bp, my_col, my_val, team_base, steps, acc);
     }
 #pragma unroll
-    for (int off = TPR; off < 64; off <<= 1)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] += shfl_f32(acc[i], lane ^ off);
+    for (int i = 0; i < 8; ++i) acc[i] = sum_over_teams<TPR>(acc[i], lane);
     if (team != 0) return;
     store_row_streaming<TPR>(((info & kWaveToScratch) ? scratch : C) + (size_t)dst * N + panel, acc, stage, tl);
 }
