@@ -85,7 +85,8 @@ typedef struct {
                              to the irregular path                                                 */
     int32_t xcd_partition_nnz; /* irregular rows with at least this many entries are cut by column group,
                              one group per XCD, so that each XCD gathers one eighth of B's columns for
-                             them; 0 = auto (128), negative = off                                 */
+                             them; 0 = auto (128 for feature panels of 128 columns, 16384 / panel
+                             columns for narrower ones), negative = off                            */
     int32_t transpose;    /* 1 = plan C = A^T * B instead (the product a backward pass needs): the CSR is
                              transposed on the host first, and everything the plan reports (rows, columns,
                              decode, row order) then refers to A^T; B has n_rows rows, C has n_cols rows */

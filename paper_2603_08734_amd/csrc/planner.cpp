@@ -579,8 +579,12 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     // column group -- one group per XCD, groups balanced by the entries they receive -- and
     // the piece of group g is scheduled on XCD g.  An XCD then gathers only its eighth of the
     // columns of B for this part of the work, which shortens the reuse distance of hot B rows
-    // eightfold.  The pieces are partial sums that the combine pass adds up.
-    const int64_t xp_min = plan.opts.xcd_partition_nnz == 0 ? 128 : plan.opts.xcd_partition_nnz;
+    // eightfold.  The pieces are partial sums that the combine pass adds up.  The automatic
+    // threshold keeps the bytes a row gathers per panel at 32 KB or more (128 entries of a
+    // 128-column panel, 256 of a 64-column one): below that the fixed cost of eight small
+    // waves outweighs the better hit rate (measured at 32, 64 and 128 features).
+    const int64_t xp_auto = std::max<int64_t>(128, 16384 / geo.irr_panel);
+    const int64_t xp_min = plan.opts.xcd_partition_nnz == 0 ? xp_auto : plan.opts.xcd_partition_nnz;
     const int64_t n_long = (int64_t)long_rows.size();
     std::vector<uint8_t> col_group;
     bool any_partitioned = false;
