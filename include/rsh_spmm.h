@@ -145,6 +145,20 @@ int rsh_plan_create(const rsh_csr_t *csr, int32_t N, const rsh_plan_opts_t *opts
 int rsh_spmm(const rsh_plan_t *plan, const void *B_dev, void *C_dev, void *hip_stream);
 
 /*
+ * The product with the epilogue of a GCN layer fused into the kernels that finish a row
+ * (paper, Section 4.4: H' = sigma(A H W); the sparse product is either A H, whose result the
+ * dense product consumes in binary16, or A (H W), followed by bias and activation):
+ *   C16 = binary16( act( A * B + bias ) ),   act = max(x, 0) if relu == 1, identity if relu == 0.
+ *   C16_dev  : device, binary16 [n_rows][N] row-major, 16-byte aligned, every element overwritten;
+ *              a row of A with no stored entry becomes act(bias).  The fp32 sum is rounded once,
+ *              to nearest even; magnitudes above 65504 become infinity.
+ *   bias_dev : device, fp32 [N], 16-byte aligned, or NULL for no bias.
+ * Everything else (B_dev, stream, scratch, determinism, errors) as for rsh_spmm.
+ */
+int rsh_spmm_f16(const rsh_plan_t *plan, const void *B_dev, void *C16_dev, const float *bias_dev, int32_t relu,
+                 void *hip_stream);
+
+/*
  * Same work as rsh_spmm, but brackets each kernel with HIP events on hip_stream,
  * waits for the stream, and reports the elapsed milliseconds of the tile kernel,
  * the irregular kernel and the combine kernel (0 for a kernel that was not

@@ -30,7 +30,7 @@ _ARRAY_DTYPES = {
 }
 
 EXPORTED_SYMBOLS = [
-    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_profile", "rsh_copy_probe", "rsh_plan_destroy", "rsh_plan_stats",
+    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_f16", "rsh_spmm_profile", "rsh_copy_probe", "rsh_plan_destroy", "rsh_plan_stats",
     "rsh_plan_decode", "rsh_plan_row_order", "rsh_plan_array", "rsh_plan_teams_per_wave",
     "rsh_struct_sizes", "rsh_status_string", "rsh_last_hip_error",
 ]
@@ -88,6 +88,7 @@ def lib() -> ctypes.CDLL:
         L.rsh_plan_create.argtypes = [ctypes.POINTER(rsh_csr_t), i32, ctypes.POINTER(rsh_plan_opts_t),
                                       ctypes.POINTER(vp)]
         L.rsh_spmm.argtypes = [vp, vp, vp, vp]
+        L.rsh_spmm_f16.argtypes = [vp, vp, vp, vp, i32, vp]
         L.rsh_spmm_profile.argtypes = [vp, vp, vp, vp, ctypes.POINTER(rsh_kernel_times_t)]
         L.rsh_copy_probe.argtypes = [vp, vp, ctypes.c_int64, vp]
         L.rsh_plan_destroy.argtypes = [vp]
@@ -176,6 +177,19 @@ class Plan:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
         _check(lib().rsh_spmm(self._h, ctypes.c_void_p(b_ptr), ctypes.c_void_p(c_ptr), ctypes.c_void_p(stream)))
+
+    def spmm_f16(self, B, C16, bias=None, relu: bool = False, stream=None) -> None:
+        """Enqueue C16 = binary16(act(A @ B + bias)) (rsh_spmm_f16); bias: fp32 device tensor [N] or None."""
+        if hasattr(B, "shape"):
+            assert tuple(B.shape) == (self.n_cols, self.N) and B.is_contiguous() and B.element_size() == 2
+            assert tuple(C16.shape) == (self.n_rows, self.N) and C16.is_contiguous() and C16.element_size() == 2
+            assert bias is None or (tuple(bias.shape) == (self.N,) and bias.is_contiguous() and bias.element_size() == 4)
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        _check(lib().rsh_spmm_f16(self._h, ctypes.c_void_p(B.data_ptr()), ctypes.c_void_p(C16.data_ptr()),
+                                  ctypes.c_void_p(bias.data_ptr() if bias is not None else None),
+                                  1 if relu else 0, ctypes.c_void_p(stream)))
 
     def spmm_profile(self, B, C, stream=None) -> dict:
         """rsh_spmm_profile: same work, returns per-kernel milliseconds (synchronises)."""

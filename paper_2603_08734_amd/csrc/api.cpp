@@ -249,6 +249,19 @@ int rsh_spmm(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_s
     return rc;
 }
 
+int rsh_spmm_f16(const rsh_plan_t* plan, const void* B_dev, void* C16_dev, const float* bias_dev, int32_t relu,
+                 void* hip_stream) {
+    if (!plan) return RSH_ERR_NULL;
+    if (!plan->uploaded) return RSH_ERR_NOT_UPLOADED;
+    if (relu != 0 && relu != 1) return RSH_ERR_BAD_OPTION;
+    if (plan->host.n_rows == 0) return RSH_OK;
+    if (!C16_dev || (!B_dev && plan->host.nnz > 0)) return RSH_ERR_NULL;
+    if (((uintptr_t)B_dev & 15u) || ((uintptr_t)C16_dev & 15u) || ((uintptr_t)bias_dev & 15u)) return RSH_ERR_BAD_OPTION;
+    const int rc = rsh::launch_spmm_f16(plan->dev, B_dev, C16_dev, bias_dev, relu, hip_stream, nullptr);
+    if (rc == RSH_ERR_HIP) g_hip_error = "kernel launch failed";
+    return rc;
+}
+
 int rsh_spmm_profile(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_stream, rsh_kernel_times_t* out) {
     if (!plan || !out) return RSH_ERR_NULL;
     out->ms_tile = out->ms_irregular = out->ms_combine = 0.f;

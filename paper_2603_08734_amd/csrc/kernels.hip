@@ -75,6 +75,31 @@ __device__ __forceinline__ void store_c_streaming(float* p, float4_t v) {
 }
 __device__ __forceinline__ void keep_streaming_hint() { asm volatile("" ::: "memory"); }
 
+// Where finished rows go.  OutPlain: the fp32 sums as they are.  OutFused: binary16 of
+// act(sum + bias), the form in which a GCN layer hands its features on (paper, Section 4.4);
+// bias (may be null) and activation are chosen at run time, uniformly for the launch.
+struct OutPlain {
+    static constexpr bool kFused = false;
+    float* C;
+};
+struct OutFused {
+    static constexpr bool kFused = true;
+    _Float16* C;
+    const float* bias;
+    int relu;
+};
+
+// act(v + bias[f .. f+3]) rounded to binary16 (to nearest even), as two packed words
+__device__ __forceinline__ uint2_t finish4(const OutFused& o, int f, float4_t v) {
+    if (o.bias) v += *reinterpret_cast<const float4_t*>(o.bias + f);
+    if (o.relu) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+    }
+    const half4_t h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+    return __builtin_bit_cast(uint2_t, h);
+}
+
 // A team's finished row of the panel -- lane t holds features 8t .. 8t+7 -- leaves as two streaming
 // stores of consecutive 16-byte pieces (lane t writes pieces t and TPR + t), i.e. whole lines, after
 // a turn through the team's LDS stage; lane-owned pieces would make every store a half-written
@@ -87,6 +112,23 @@ __device__ __forceinline__ void store_row_streaming(float* out_row, const float 
     const float4_t v1 = *reinterpret_cast<const float4_t*>(stage + 4 * TPR + 4 * tl);
     store_c_streaming(out_row + 4 * tl, v0);
     store_c_streaming(out_row + 4 * TPR + 4 * tl, v1);
+}
+
+// A team's finished row `row` of C, panel starting at feature `panel`.  In binary16 a lane's
+// eight features are one 16-byte piece and the team's pieces are consecutive, so the row
+// leaves as one store of whole lines without a turn through LDS.
+template <int TPR>
+__device__ __forceinline__ void emit_row(const OutPlain& o, size_t row, int N, int panel, const float (&acc)[8],
+                                         float* stage, int tl) {
+    store_row_streaming<TPR>(o.C + row * N + panel, acc, stage, tl);
+}
+template <int TPR>
+__device__ __forceinline__ void emit_row(const OutFused& o, size_t row, int N, int panel, const float (&acc)[8],
+                                         float*, int tl) {
+    const int f = panel + 8 * tl;
+    const uint2_t lo = finish4(o, f, (float4_t){acc[0], acc[1], acc[2], acc[3]});
+    const uint2_t hi = finish4(o, f + 4, (float4_t){acc[4], acc[5], acc[6], acc[7]});
+    __builtin_nontemporal_store((uint4_t){lo[0], lo[1], hi[0], hi[1]}, reinterpret_cast<uint4_t*>(o.C + row * N + f));
 }
 
 // ---------------------------------------------------------------------------
@@ -142,15 +184,16 @@ __device__ __forceinline__ void gather_group(const BRows& Bp, int my_col, float 
 
 // Short-row variant of a group: the same U back-to-back loads, but a row of C is stored
 // whenever L steps have been consumed (the step counter is uniform over the wave).
+template <class OUT>
 struct ShortRowState {
-    float* C;        // C + first feature of the panel
+    const OUT& out;
     float* stage;    // the team's LDS stage
-    int N, tl, L, k, rq;
+    int N, panel, tl, L, k, rq;
 };
 
-template <int U, int TPR>
+template <int U, int TPR, class OUT>
 __device__ __forceinline__ void short_rows_group(const BRows& Bp, int my_col, float my_val, int my_row,
-                                                 int team_base, int j0, float (&acc)[8], ShortRowState& st) {
+                                                 int team_base, int j0, float (&acc)[8], ShortRowState<OUT>& st) {
     uint4_t b[U];
     float v[U];
 #pragma unroll
@@ -172,7 +215,7 @@ __device__ __forceinline__ void short_rows_group(const BRows& Bp, int my_col, fl
             st.k = 0;
             const int row = shfl_i32(my_row, team_base + st.rq);
             ++st.rq;
-            if (row >= 0) store_row_streaming<TPR>(st.C + (size_t)row * st.N, acc, st.stage, st.tl);
+            if (row >= 0) emit_row<TPR>(st.out, (size_t)row, st.N, st.panel, acc, st.stage, st.tl);
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = 0.f;
         }
@@ -195,11 +238,11 @@ __device__ __forceinline__ void gather_steps(const BRows& Bp, int my_col, float 
     if (steps & 1) gather_group<1>(Bp, my_col, my_val, team_base + j, acc);
 }
 
-template <int TPR>
+template <int TPR, class OUT>
 __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void rsh_irregular_kernel(
     const uint4* __restrict__ waves, XcdSplit xs,
     const int32_t* __restrict__ irr_row, const int32_t* __restrict__ irr_col,
-    const uint16_t* __restrict__ irr_val, const __half* __restrict__ B, float* __restrict__ C,
+    const uint16_t* __restrict__ irr_val, const __half* __restrict__ B, const OUT out,
     float* __restrict__ scratch, int N) {
     constexpr int G = 64 / TPR;
     __shared__ __attribute__((aligned(16))) float lds_stage[kWavesPerBlock][64 * 8];
@@ -222,9 +265,13 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
 
     if (kind == kWaveZeroRows) {
         for (uint32_t q = team; q < count; q += G) {
-            float* out = C + (size_t)irr_row[dst + q] * N + panel;
-            store_c_streaming(out + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
-            store_c_streaming(out + 4 * TPR + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
+            if constexpr (OUT::kFused) {
+                emit_row<TPR>(out, (size_t)irr_row[dst + q], N, panel, acc, stage, tl);   // act(bias)
+            } else {
+                float* o = out.C + (size_t)irr_row[dst + q] * N + panel;
+                store_c_streaming(o + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
+                store_c_streaming(o + 4 * TPR + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
+            }
         }
         return;
     }
@@ -240,7 +287,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
         const int my_row = tl < n_rows_mine ? irr_row[dst + q0 + tl] : -1;
         // R rows of L entries back to back: the loads of up to eight steps are in flight together,
         // whatever rows they belong to; after every L consumed steps a row is complete and stored
-        ShortRowState st{C + panel, stage, N, tl, L, 0, 0};
+        ShortRowState<OUT> st{out, stage, N, panel, tl, L, 0, 0};
         const int steps = R * L;
         int j = 0;
         for (; j + 8 <= steps; j += 8) short_rows_group<8, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
@@ -277,7 +324,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = sum_over_teams<TPR>(acc[i], lane);
     if (team != 0) return;
-    store_row_streaming<TPR>(((info & kWaveToScratch) ? scratch : C) + (size_t)dst * N + panel, acc, stage, tl);
+    if constexpr (OUT::kFused) {
+        if (info & kWaveToScratch) store_row_streaming<TPR>(scratch + (size_t)dst * N + panel, acc, stage, tl);
+        else emit_row<TPR>(out, (size_t)dst, N, panel, acc, stage, tl);
+    } else {
+        store_row_streaming<TPR>(((info & kWaveToScratch) ? scratch : out.C) + (size_t)dst * N + panel, acc, stage, tl);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -326,18 +378,21 @@ struct TileGeom {
 // KT = condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16, 4 cells per lane) or 32
 // (v_mfma_f32_16x16x32_f16, 8 cells per lane: lane l holds k = 8*(l/16) .. 8*(l/16)+7, fed by two
 // transposing reads four staged rows apart).
-template <int NCH, int NW, int D, int KT>
+template <int NCH, int NW, int D, int KT, class OUT>
 __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_tile_kernel(
     const uint4* __restrict__ items, XcdSplit xs,
     const int32_t* __restrict__ win_row, const int32_t* __restrict__ tile_colid,
     const uint64_t* __restrict__ tile_mask, const uint32_t* __restrict__ tile_val_off,
-    const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, float* __restrict__ C,
+    const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, const OUT out,
     float* __restrict__ scratch, int N) {
     using Gm = TileGeom<NCH, NW, KT>;
     constexpr int P = Gm::P, TPR = Gm::TPR, NLD = Gm::NLD, LDB = Gm::LDB, THREADS = Gm::THREADS, CPL = Gm::CPL;
     using vals_t = typename std::conditional<KT == 16, uint2_t, uint4_t>::type;   // CPL halves per lane
     using frag_t = typename std::conditional<KT == 16, half4_t, half8_t>::type;
-    __shared__ __attribute__((aligned(16))) _Float16 lds_b[Gm::ITEMS_PER_BLOCK][Gm::NBUF][KT * LDB];
+    // the staged tiles; the binary16 epilogue reuses the space as 16 output rows per wave
+    constexpr int kTileHalves = Gm::NBUF * KT * LDB;
+    constexpr int kSlotHalves = (OUT::kFused && NW > 1 && NW * 16 * LDB > kTileHalves) ? NW * 16 * LDB : kTileHalves;
+    __shared__ __attribute__((aligned(16))) _Float16 lds_b[Gm::ITEMS_PER_BLOCK][kSlotHalves];
     __shared__ __attribute__((aligned(16))) uint16_t lds_v[kWavesPerBlock > NW ? kWavesPerBlock : NW][16 * KT + 16];
 
     const int lane = threadIdx.x & 63;
@@ -354,7 +409,7 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     const uint32_t win = __builtin_amdgcn_readfirstlane(it.x), t_begin = __builtin_amdgcn_readfirstlane(it.y);
     const uint32_t t_end = __builtin_amdgcn_readfirstlane(it.z), dst = __builtin_amdgcn_readfirstlane(it.w);
     const int panel = blockIdx.y * P;
-    _Float16* sb0 = lds_b[NW == 1 ? wib : 0][0];
+    _Float16* sb0 = lds_b[NW == 1 ? wib : 0];
     uint16_t* sv = lds_v[wib];
 
     // cooperative staging: thread `tix` of the THREADS sharing the tile takes 16-byte piece
@@ -518,20 +573,49 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     if (dst != kNoDst) {
         // partial sums of a split window: ordinary stores (measured: the combine pass is faster
         // when these went through L2)
-        float* out = scratch + ((size_t)dst + r) * N + panel + 4 * q;
+        float* o = scratch + ((size_t)dst + r) * N + panel + 4 * q;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(out + 16 * c) = acc[c];
+        for (int c = 0; c < NCH; ++c) *reinterpret_cast<float4_t*>(o + 16 * c) = acc[c];
         return;
     }
-    if constexpr (NCH % 2 == 0) {
+    if constexpr (OUT::kFused) {
+        // binary16 output: the wave's 16 rows take a turn through LDS (row m at stride LDB, in the
+        // space of the staged tiles, which every wave of the block has finished reading) and
+        // leave as 16-byte pieces that are consecutive along a row, i.e. as whole lines
+        if (NW > 1) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        } else {
+            __builtin_amdgcn_wave_barrier();
+        }
+        _Float16* so = sb0 + (NW == 1 ? 0 : sub * 16 * LDB);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+            *reinterpret_cast<uint2_t*>(so + m * LDB + 16 * c + 4 * q) = finish4(out, panel + 16 * c + 4 * q, acc[c]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+        constexpr int kPieces = 16 * TPR;   // 16-byte pieces of the wave's rows of this panel
+#pragma unroll
+        for (int i = 0; i < (kPieces + 63) / 64; ++i) {
+            const int piece = i * 64 + lane;
+            const int pr = (piece / TPR) & 15, pc = piece % TPR;
+            const int prow = shfl_i32(row, pr);
+            if (piece < kPieces && prow >= 0) {
+                const uint4_t v = *reinterpret_cast<const uint4_t*>(so + pr * LDB + 8 * pc);
+                __builtin_nontemporal_store(v, reinterpret_cast<uint4_t*>(out.C + (size_t)prow * N + panel + 8 * pc));
+            }
+        }
+    } else if constexpr (NCH % 2 == 0) {
         // Stores of whole 128-byte lines: lanes r and r^8 trade halves of a pair of chunks,
         // so that one instruction writes 32 consecutive features of rows 0..7 and the next
         // those of rows 8..15 (a streaming store of a half line is much slower).
         const bool low = (lane & 8) == 0;
         const int row_other = swap_lane8(row);
         const int row_a = low ? row : row_other, row_b = low ? row_other : row;
-        float* out_a = C + (size_t)row_a * N + panel + 4 * q + (low ? 0 : 16);
-        float* out_b = C + (size_t)row_b * N + panel + 4 * q + (low ? 0 : 16);
+        float* out_a = out.C + (size_t)row_a * N + panel + 4 * q + (low ? 0 : 16);
+        float* out_b = out.C + (size_t)row_b * N + panel + 4 * q + (low ? 0 : 16);
 #pragma unroll
         for (int c = 0; c < NCH; c += 2) {
             float4_t send, recv;
@@ -550,9 +634,9 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
         }
     } else {
         if (row < 0) return;
-        float* out = C + (size_t)row * N + panel + 4 * q;
+        float* o = out.C + (size_t)row * N + panel + 4 * q;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) store_c_streaming(out + 16 * c, acc[c]);
+        for (int c = 0; c < NCH; ++c) store_c_streaming(o + 16 * c, acc[c]);
     }
     keep_streaming_hint();
 }
@@ -561,9 +645,10 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 // Combine: C[row] = sum over parts of scratch[first + p*stride], in a fixed order
 // (four interleaved running sums, then a fixed tree), one wave per entry.
 // ---------------------------------------------------------------------------
+template <class OUT>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_combine_kernel(
     const uint4* __restrict__ entries, uint32_t n_entries, const float* __restrict__ scratch,
-    float* __restrict__ C, int N) {
+    const OUT out, int N) {
     const int lane = threadIdx.x & 63;
     const uint32_t e = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (e >= n_entries) return;
@@ -591,7 +676,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rsh_combine_kernel(
         o.y = (s0.y + s1.y) + (s2.y + s3.y);
         o.z = (s0.z + s1.z) + (s2.z + s3.z);
         o.w = (s0.w + s1.w) + (s2.w + s3.w);
-        store_c_streaming(C + (size_t)row * N + f, (float4_t){o.x, o.y, o.z, o.w});
+        if constexpr (OUT::kFused) {
+            __builtin_nontemporal_store(finish4(out, f, (float4_t){o.x, o.y, o.z, o.w}),
+                                        reinterpret_cast<uint2_t*>(out.C + (size_t)row * N + f));
+        } else {
+            store_c_streaming(out.C + (size_t)row * N + f, (float4_t){o.x, o.y, o.z, o.w});
+        }
     }
 }
 
@@ -622,47 +712,48 @@ static inline uint32_t grid_for(const XcdSplit& xs) {
     return 8u * ((longest + kWavesPerBlock - 1) / kWavesPerBlock);
 }
 
-template <int TPR>
-static void launch_irregular_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+template <int TPR, class OUT>
+static void launch_irregular_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
     dim3 grid(grid_for(d.irr_split), (unsigned)(d.geo.N / d.geo.irr_panel));
-    hipLaunchKernelGGL(rsh_irregular_kernel<TPR>, grid, dim3(64 * kWavesPerBlock), 0, st,
-                       (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, (float*)C,
+    hipLaunchKernelGGL((rsh_irregular_kernel<TPR, OUT>), grid, dim3(64 * kWavesPerBlock), 0, st,
+                       (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, out,
                        d.scratch, d.geo.N);
 }
 
-template <int NCH, int NW, int D, int KT>
-static void launch_tile_t(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+template <int NCH, int NW, int D, int KT, class OUT>
+static void launch_tile_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
     constexpr int items_per_block = NW == 1 ? kWavesPerBlock : 1;
     uint32_t longest = 0;
     for (int x = 0; x < 8; ++x) longest = std::max(longest, d.tile_split.start[x + 1] - d.tile_split.start[x]);
     dim3 grid(8u * ((longest + items_per_block - 1) / items_per_block), (unsigned)(d.geo.N / d.geo.tile_panel));
-    hipLaunchKernelGGL((rsh_tile_kernel<NCH, NW, D, KT>), grid, dim3(NW == 1 ? 64 * kWavesPerBlock : 64 * NW), 0, st,
+    hipLaunchKernelGGL((rsh_tile_kernel<NCH, NW, D, KT, OUT>), grid, dim3(NW == 1 ? 64 * kWavesPerBlock : 64 * NW), 0, st,
                        (const uint4*)d.tile_item, d.tile_split, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off,
-                       d.tile_val, (const __half*)B, (float*)C, d.scratch, d.geo.N);
+                       d.tile_val, (const __half*)B, out, d.scratch, d.geo.N);
 }
 
 // Fragments in flight per thread: one for 16-row windows, two when the waves of a window share
 // the staging (measured best of 1, 2, 3).
-template <int NCH, int NW>
-static int launch_tile_d(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+template <int NCH, int NW, class OUT>
+static int launch_tile_d(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
     constexpr int D = NW == 1 ? 1 : 2;
-    if (d.geo.tile_k == 16) launch_tile_t<NCH, NW, D, 16>(d, B, C, st);
-    else if (d.geo.tile_k == 32) launch_tile_t<NCH, NW, D, 32>(d, B, C, st);
+    if (d.geo.tile_k == 16) launch_tile_t<NCH, NW, D, 16>(d, B, out, st);
+    else if (d.geo.tile_k == 32) launch_tile_t<NCH, NW, D, 32>(d, B, out, st);
     else return RSH_ERR_BAD_OPTION;
     return RSH_OK;
 }
 
-template <int NCH>
-static int launch_tile_nw(const DevicePlan& d, const void* B, void* C, hipStream_t st) {
+template <int NCH, class OUT>
+static int launch_tile_nw(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
     switch (d.geo.nw) {
-        case 1: return launch_tile_d<NCH, 1>(d, B, C, st);
-        case 2: return launch_tile_d<NCH, 2>(d, B, C, st);
-        case 4: return launch_tile_d<NCH, 4>(d, B, C, st);
+        case 1: return launch_tile_d<NCH, 1>(d, B, out, st);
+        case 2: return launch_tile_d<NCH, 2>(d, B, out, st);
+        case 4: return launch_tile_d<NCH, 4>(d, B, out, st);
         default: return RSH_ERR_BAD_OPTION;
     }
 }
 
-int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void* const* events) {
+template <class OUT>
+static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* stream, void* const* events) {
     hipStream_t st = (hipStream_t)stream;
     auto mark = [&](int i) {
         if (events) (void)hipEventRecord((hipEvent_t)events[i], st);
@@ -671,11 +762,11 @@ int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void*
     int rc = RSH_OK;
     if (d.n_tile_items > 0) {
         switch (d.geo.tile_nch) {
-            case 1: rc = launch_tile_nw<1>(d, B, C, st); break;
-            case 2: rc = launch_tile_nw<2>(d, B, C, st); break;
-            case 4: rc = launch_tile_nw<4>(d, B, C, st); break;
-            case 8: rc = launch_tile_nw<8>(d, B, C, st); break;
-            case 16: rc = launch_tile_nw<16>(d, B, C, st); break;
+            case 1: rc = launch_tile_nw<1>(d, B, out, st); break;
+            case 2: rc = launch_tile_nw<2>(d, B, out, st); break;
+            case 4: rc = launch_tile_nw<4>(d, B, out, st); break;
+            case 8: rc = launch_tile_nw<8>(d, B, out, st); break;
+            case 16: rc = launch_tile_nw<16>(d, B, out, st); break;
             default: return RSH_ERR_UNSUPPORTED_N;
         }
         if (rc != RSH_OK) return rc;
@@ -683,21 +774,29 @@ int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void*
     mark(1);
     if (d.n_irr_waves > 0) {
         switch (d.geo.irr_tpr) {
-            case 2: launch_irregular_t<2>(d, B, C, st); break;
-            case 4: launch_irregular_t<4>(d, B, C, st); break;
-            case 8: launch_irregular_t<8>(d, B, C, st); break;
-            case 16: launch_irregular_t<16>(d, B, C, st); break;
+            case 2: launch_irregular_t<2>(d, B, out, st); break;
+            case 4: launch_irregular_t<4>(d, B, out, st); break;
+            case 8: launch_irregular_t<8>(d, B, out, st); break;
+            case 16: launch_irregular_t<16>(d, B, out, st); break;
             default: return RSH_ERR_UNSUPPORTED_N;
         }
     }
     mark(2);
     if (d.n_combine > 0) {
         const uint32_t n = (uint32_t)d.n_combine;
-        hipLaunchKernelGGL(rsh_combine_kernel, dim3((n + kWavesPerBlock - 1) / kWavesPerBlock), dim3(64 * kWavesPerBlock),
-                           0, st, (const uint4*)d.combine, n, d.scratch, (float*)C, d.geo.N);
+        hipLaunchKernelGGL(rsh_combine_kernel<OUT>, dim3((n + kWavesPerBlock - 1) / kWavesPerBlock), dim3(64 * kWavesPerBlock),
+                           0, st, (const uint4*)d.combine, n, d.scratch, out, d.geo.N);
     }
     mark(3);
     return hipGetLastError() == hipSuccess ? RSH_OK : RSH_ERR_HIP;
+}
+
+int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void* const* events) {
+    return launch_all(d, B, OutPlain{(float*)C}, stream, events);
+}
+
+int launch_spmm_f16(const DevicePlan& d, const void* B, void* C16, const float* bias, int relu, void* stream, void* const* events) {
+    return launch_all(d, B, OutFused{(_Float16*)C16, bias, relu}, stream, events);
 }
 
 }  // namespace rsh

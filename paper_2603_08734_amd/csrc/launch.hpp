@@ -31,6 +31,11 @@ struct DevicePlan {
 // after each of the three kernels.
 int launch_spmm(const DevicePlan& d, const void* B_dev, void* C_dev, void* stream, void* const* events);
 
+// Same kernels with the fused epilogue: C16 (binary16, n_rows x N) = act(A B + bias); bias is a
+// device array of N floats or null, relu != 0 selects max(x, 0).
+int launch_spmm_f16(const DevicePlan& d, const void* B_dev, void* C16_dev, const float* bias_dev, int relu,
+                    void* stream, void* const* events);
+
 // Plain device-to-device copy of `bytes` (multiple of 16) used to calibrate traffic counters.
 int launch_copy_probe(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
 

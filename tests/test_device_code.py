@@ -41,13 +41,24 @@ def test_rows_of_c_leave_with_the_streaming_hint(kernels_asm):
     tile = {n: b for n, b in kernels_asm.items() if "rsh_tile_kernel" in n}
     irregular = {n: b for n, b in kernels_asm.items() if "rsh_irregular_kernel" in n}
     combine = {n: b for n, b in kernels_asm.items() if "rsh_combine_kernel" in n}
-    assert len(tile) >= 30 and len(irregular) == 4 and len(combine) == 1
+    # every kernel exists twice: fp32 sums (OutPlain) and the fused binary16 epilogue (OutFused)
+    assert len(tile) >= 60 and len(irregular) == 8 and len(combine) == 2
     for name, body in tile.items():
         n, nt = _stores(body)
-        assert n > 0 and nt * 2 == n, f"{name}: {nt} of {n} stores are streaming (C path streaming, scratch path ordinary)"
-    for name, body in list(irregular.items()) + list(combine.items()):
+        if "OutFused" in name:
+            # scratch path: one ordinary store per 16-feature chunk; C path: the wave's 16 rows of
+            # binary16 leave as 16 * (2 * chunks) 16-byte pieces, 64 per streaming store
+            nch = int(re.search(r"rsh_tile_kernelILi(\d+)E", name).group(1))
+            assert n - nt == nch and nt == max(1, nch // 2), f"{name}: {nt} streaming of {n} stores"
+        else:
+            assert n > 0 and nt * 2 == n, f"{name}: {nt} of {n} stores are streaming (C path streaming, scratch path ordinary)"
+    for name, body in irregular.items():
         n, nt = _stores(body)
         assert n > 0 and nt == n, f"{name}: {nt} of {n} stores are streaming"
+    for name, body in combine.items():
+        st = [l for l in body.splitlines() if "global_store_dword" in l]
+        want = "global_store_dwordx2" if "OutFused" in name else "global_store_dwordx4"
+        assert st and all(want in l and " nt" in l for l in st), f"{name}: {st}"
 
 
 def test_kernels_keep_their_registers(kernels_asm):

@@ -41,7 +41,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(os.path.dirname(__file__), "..", "include", "rsh_spmm.h")).read()
     L = binding.lib()
     import re
-    declared = set(re.findall(r"\b(rsh_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(rsh_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(L, name)
