@@ -88,6 +88,9 @@ def main() -> int:
     ap.add_argument("--reorder", type=int, default=-1, help="override the plan's reorder option")
     ap.add_argument("--opt", action="append", default=[], help="plan option override name=value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--epilogue", action="store_true",
+                    help="also time rsh_spmm_f16 (bias + ReLU + binary16 output fused) against rsh_spmm followed by "
+                         "the same epilogue as separate elementwise kernels; adds a 'fused_epilogue' object")
     ap.add_argument("--ablation", choices=["thresholds", "reorder", "shape"], default=None,
                     help="instead of the benchmark line: sweep one planning knob on --config and print one JSON "
                          "line with a row per setting (the paper's Sections 4.3.2 and 4.3.3 on synthetic data)")
@@ -195,6 +198,30 @@ def main() -> int:
                  "mean_nnz_per_window": round(st["nnz_tile"] / max(1, st["n_windows"]), 1)},
         "gen_s": round(gen_s, 2),
     }
+
+    if args.epilogue:
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0) / args.steps
+
+        bias = torch.from_numpy(np.random.default_rng(2).normal(scale=0.1, size=N).astype(np.float32)).cuda()
+        C16 = torch.empty((A.n_rows, N), dtype=torch.float16, device="cuda")
+        fused_ms = timed(lambda: plan.spmm_f16(B, C16, bias, True))
+
+        def unfused():
+            plan.spmm(B, C)
+            torch.relu(C + bias).to(torch.float16)
+
+        unfused_ms = timed(unfused)
+        out["fused_epilogue"] = {"op": "binary16(relu(A*B + bias))", "ms_per_step": round(fused_ms, 4),
+                                 "separate_kernels_ms_per_step": round(unfused_ms, 4)}
+        del C16
 
     if not args.no_cpu_baseline:
         # the oracle as it stands, on this machine's host cores, whole matrix, one run

@@ -1,0 +1,72 @@
+"""GPU parity of the GCN layer (forward and backward, both association orders) against the fp64 oracle.
+
+Tolerances.  With T = |A| |H| |W| + |b| (products of absolute values): the layer rounds one
+intermediate (H W or A H) and its output to binary16 (2^-11 relative each) and accumulates in fp32
+(1e-4 of the absolute sums at most), so |Y - Y_ref| <= 3 * 2^-11 * T + 2^-24.  The backward pass
+chains three more roundings (dZ, A^T dZ or dZ W^T, and the result) through two products; its
+results are held to 2^-8 of the corresponding products of absolute values.  The gradient from above
+is zero where the oracle's pre-activation is within twice the forward bound of the kink, so that
+both sides take the same ReLU mask.
+"""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+from oracle import gcn as oracle_gcn
+from workloads import make_config
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(k, d_in, d_out, seed):
+    A, _, _ = make_config(k, small=True)
+    rng = np.random.default_rng(seed)
+    H = rng.normal(scale=1.0, size=(A.n_cols, d_in)).astype(np.float16)
+    W = rng.normal(scale=1.0 / np.sqrt(d_in), size=(d_in, d_out)).astype(np.float16)
+    b = rng.normal(scale=0.2, size=d_out).astype(np.float32)
+    return A, H, W, b
+
+
+@pytest.mark.parametrize("relu", [True, False])
+@pytest.mark.parametrize("order", ["A_HW", "AH_W"])
+@pytest.mark.parametrize("k,d_in,d_out", [(2, 64, 32), (4, 32, 64), (3, 128, 128)])
+def test_layer_forward_and_backward(k, d_in, d_out, order, relu):
+    import torch
+    from paper_2603_08734_amd.gcn import GCNLayer
+    assert torch.cuda.is_available()
+    A, H, W, b = _problem(k, d_in, d_out, seed=k)
+    if A.n_rows != A.n_cols:
+        pytest.skip("a GCN layer needs a square adjacency")
+    print(f"case gcn config={k} small d_in={d_in} d_out={d_out} order={order} relu={relu}", flush=True)
+    args = (A.row_ptr, A.col_idx, A.val, A.n_cols)
+    Y_ref, Z_ref = oracle_gcn.layer_forward(*args, H, W, b, relu, order)
+    absA = abs(sp.csr_matrix((A.val.astype(np.float64), A.col_idx, A.row_ptr), shape=(A.n_rows, A.n_cols)))
+    aH, aW = np.abs(H.astype(np.float64)), np.abs(W.astype(np.float64))
+    T = (absA @ aH) @ aW + np.abs(b.astype(np.float64))[None, :]
+    fwd_bound = 3 * 2.0 ** -11 * T + 2.0 ** -24
+    rng = np.random.default_rng(99)
+    G = rng.normal(size=Y_ref.shape).astype(np.float16)
+    if relu:
+        G[np.abs(Z_ref) <= 2 * fwd_bound] = 0
+    aG = np.abs(G.astype(np.float64))
+    dH_ref, dW_ref, db_ref = oracle_gcn.layer_backward(*args, H, W, b, relu, G)
+
+    layer = GCNLayer(*args, d_in, d_out, order=order)
+    Hd = torch.from_numpy(H).cuda().requires_grad_(True)
+    Wd = torch.from_numpy(W).cuda().requires_grad_(True)
+    bd = torch.from_numpy(b).cuda().requires_grad_(True)
+    Y = layer(Hd, Wd, bd, relu)
+    Y.backward(torch.from_numpy(G).cuda())
+    torch.cuda.synchronize()
+
+    err = np.abs(Y.detach().cpu().numpy().astype(np.float64) - Y_ref)
+    assert (err <= fwd_bound).all(), f"forward: max err {err.max()}"
+
+    loose = 2.0 ** -8
+    dW_err = np.abs(Wd.grad.cpu().numpy().astype(np.float64) - dW_ref)
+    assert (dW_err <= loose * ((absA @ aH).T @ aG) + 1e-6).all(), f"dW: max err {dW_err.max()}"
+    dH_err = np.abs(Hd.grad.cpu().numpy().astype(np.float64) - dH_ref)
+    assert (dH_err <= loose * (absA.T @ (aG @ aW.T)) + 1e-6).all(), f"dH: max err {dH_err.max()}"
+    db_err = np.abs(bd.grad.cpu().numpy().astype(np.float64) - db_ref)
+    assert (db_err <= loose * aG.sum(axis=0) + 1e-6).all(), f"db: max err {db_err.max()}"
+    layer.destroy()
