@@ -152,3 +152,69 @@ def test_argument_errors():
         host_only.spmm_f16(B, C16, None, False)
     plan.destroy()
     host_only.destroy()
+
+
+def test_fused_product_can_be_captured_in_a_graph_and_replayed():
+    """rsh_spmm_f16 launches kernels only, so it records into a HIP graph like rsh_spmm; every replay,
+    with operand and bias changed and eager work in between, must equal an eager call bit for bit."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, N, dist = make_config(2, small=True)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, xcd_partition_nnz=32, max_tiles_per_item=3)
+    st = plan.stats()
+    assert st["nnz_tile"] > 0 and st["nnz_irregular"] > 0 and st["n_combine"] > 0     # all three kernels run
+    Bs = torch.zeros((A.n_cols, N), dtype=torch.float16, device="cuda")
+    bias = torch.zeros(N, dtype=torch.float32, device="cuda")
+    Cs = torch.full((A.n_rows, N), float("nan"), dtype=torch.float16, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.spmm_f16(Bs, Cs, bias, True)     # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.spmm_f16(Bs, Cs, bias, True)
+    for seed in (5, 6, 7):
+        B = dense_B(A.n_cols, N, dist, seed=seed)
+        b_np = bias_for(N, seed)
+        Bs.copy_(torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16))
+        bias.copy_(torch.from_numpy(b_np))
+        Cs.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Cs.cpu().numpy()
+        C_eager = torch.full_like(Cs, float("nan"))
+        plan.spmm_f16(Bs, C_eager, bias, True)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.view(np.uint16), C_eager.cpu().numpy().view(np.uint16)), "a replay differs from the eager call"
+        Z, S = oracle_gcn.product_epilogue(A.row_ptr, A.col_idx, A.val, A.n_cols, B, b_np, True)
+        bound = TOL * S + 2.0 ** -11 * (np.abs(Z) + TOL * S) + 2.0 ** -24
+        assert (np.abs(got.astype(np.float64) - Z) <= bound).all(), f"graph replay, seed {seed}"
+    plan.destroy()
+
+
+@pytest.mark.parametrize("k", [2, 5])
+def test_fused_transposed_product(k):
+    """transpose = 1 with the epilogue: binary16(relu(A^T B + bias)), the transposition made by scipy."""
+    import scipy.sparse as sp
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, N, dist = make_config(k, small=True)
+    At = sp.csr_matrix((A.val.view(np.uint16), A.col_idx, A.row_ptr), shape=(A.n_rows, A.n_cols)).T.tocsr()
+    At.sort_indices()
+    B = dense_B(A.n_rows, N, dist, seed=40 + k)
+    b_np = bias_for(N, 40 + k)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, transpose=1)
+    Bd = torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16)
+    C16 = torch.full((A.n_cols, N), float("nan"), dtype=torch.float16, device="cuda")
+    plan.spmm_f16(Bd, C16, torch.from_numpy(b_np).cuda(), True)
+    torch.cuda.synchronize()
+    Z, S = oracle_gcn.product_epilogue(At.indptr.astype(np.int64), At.indices.astype(np.int32), At.data.view(np.float16),
+                                       A.n_rows, B, b_np, True)
+    got = C16.cpu().numpy()
+    assert not np.isnan(got).any()
+    bound = TOL * S + 2.0 ** -11 * (np.abs(Z) + TOL * S) + 2.0 ** -24
+    assert (np.abs(got.astype(np.float64) - Z) <= bound).all(), f"transposed config {k}"
+    plan.destroy()
