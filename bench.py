@@ -178,6 +178,14 @@ def main() -> int:
         roofline["traffic_GBps"] = round(moved, 1)
         roofline["traffic_frac"] = round(moved / HBM_PEAK_GBPS, 4)
 
+    # work the matrix cores are given: every W x K fragment is multiplied out in full, zeros included
+    mfma = None
+    if kernel_ms["tile"] > 0:
+        dense_flops = 2.0 * st["window_rows"] * st["tile_k"] * N * st["n_tiles"]
+        tf = dense_flops / (kernel_ms["tile"] * 1e-3) / 1e12
+        mfma = {"dense_equivalent_TFLOPs": round(tf, 1), "peak_TFLOPs": 2500.0, "frac": round(tf / 2500.0, 4),
+                "useful_share": round(2.0 * st["nnz_tile"] * N / dense_flops, 4)}
+
     out = {
         "metric": "SpMM GFLOP/s (2*nnz*N/t), N=%d, 1 MI355X" % N, "value": round(gflops, 1), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -186,6 +194,7 @@ def main() -> int:
         "config": {"workload": A.meta["name"], "rows": A.n_rows, "cols": A.n_cols, "nnz": A.nnz, "N": N,
                    "seed": 0, "csr_checksum": A.checksum(), "plan_options": opts},
         "roofline": roofline,
+        "tile_mfma": mfma,
         "hbm_useful_GBps": round(bytes_min / (ms_per_step * 1e-3) / 1e9, 1),
         "bytes_min": int(bytes_min),
         "kernel_ms": {k: round(v, 4) for k, v in kernel_ms.items()},
