@@ -88,6 +88,9 @@ def main() -> int:
     ap.add_argument("--reorder", type=int, default=-1, help="override the plan's reorder option")
     ap.add_argument("--opt", action="append", default=[], help="plan option override name=value")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gcn-epoch", type=int, default=0, metavar="HIDDEN",
+                    help="also time one training epoch (forward, backward, gradient step) of the 6-layer GCN of the "
+                         "paper's case study with this hidden width on the workload's graph; adds a 'gcn_epoch' object")
     ap.add_argument("--epilogue", action="store_true",
                     help="also time rsh_spmm_f16 (bias + ReLU + binary16 output fused) against rsh_spmm followed by "
                          "the same epilogue as separate elementwise kernels; adds a 'fused_epilogue' object")
@@ -231,6 +234,51 @@ def main() -> int:
         out["fused_epilogue"] = {"op": "binary16(relu(A*B + bias))", "ms_per_step": round(fused_ms, 4),
                                  "separate_kernels_ms_per_step": round(unfused_ms, 4)}
         del C16
+
+    if args.gcn_epoch:
+        from paper_2603_08734_amd.gcn import Adjacency, GCNLayer
+        assert A.n_rows == A.n_cols, "a GCN needs a square adjacency"
+        d, n_layers = args.gcn_epoch, 6
+        adj = Adjacency(A.row_ptr, A.col_idx, A.val, A.n_cols, **opts)
+        layers = [GCNLayer(adj, d, d) for _ in range(n_layers)]      # A (H W): bias/ReLU/rounding fused
+        g = torch.Generator(device="cuda").manual_seed(0)
+        X = torch.randn((A.n_cols, d), device="cuda", generator=g).to(torch.float16)
+        T = torch.randn((A.n_rows, d), device="cuda", generator=g)
+        Ws = [(torch.randn((d, d), device="cuda", generator=g) / d ** 0.5).requires_grad_(True) for _ in range(n_layers)]
+
+        def epoch():
+            h = X
+            for i, (layer, w) in enumerate(zip(layers, Ws)):
+                h = layer(h, w.to(torch.float16), None, i + 1 < n_layers)
+            loss = ((h.float() - T) ** 2).sum() / A.n_rows
+            loss.backward()
+            with torch.no_grad():
+                for w in Ws:
+                    w -= 1e-3 * w.grad
+                    w.grad = None
+
+        for _ in range(3):
+            epoch()                      # the first backward pass also builds the plan of the transpose
+        torch.cuda.synchronize()
+        n_ep = max(3, min(args.steps, 10))
+        t0 = time.perf_counter()
+        for _ in range(n_ep):
+            epoch()
+        torch.cuda.synchronize()
+        ep_ms = 1e3 * (time.perf_counter() - t0) / n_ep
+        Y16 = torch.empty((A.n_rows, d), dtype=torch.float16, device="cuda")
+        pf, pb = adj.plan(d), adj.plan(d, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_ep):
+            for _ in range(n_layers):
+                pf.spmm_f16(X, Y16, None, False)
+                pb.spmm_f16(X, Y16, None, False)
+        torch.cuda.synchronize()
+        sp_ms = 1e3 * (time.perf_counter() - t0) / n_ep
+        out["gcn_epoch"] = {"layers": n_layers, "hidden": d, "order": "A (H W)", "ms_per_epoch": round(ep_ms, 3),
+                            "sparse_products_ms": round(sp_ms, 3), "epochs_timed": n_ep}
+        adj.destroy()
 
     if not args.no_cpu_baseline:
         # the oracle as it stands, on this machine's host cores, whole matrix, one run

@@ -70,6 +70,34 @@ class _SparseProduct(torch.autograd.Function):
         return None, dX, dbias, None
 
 
+class _DenseProduct(torch.autograd.Function):
+    """H W with library GEMMs.  The weight gradient H^T dZ reduces over all rows of the graph into a
+    d_in x d_out result; as one GEMM that is a single output tile (one workgroup streams the whole
+    of H), so it is issued as a batched GEMM over row slabs whose partial results are then added."""
+
+    @staticmethod
+    def forward(ctx, H, W):
+        ctx.save_for_backward(H, W)
+        return H @ W
+
+    @staticmethod
+    def backward(ctx, dZ):
+        H, W = ctx.saved_tensors
+        dH = dZ @ W.t() if ctx.needs_input_grad[0] else None
+        dW = None
+        if ctx.needs_input_grad[1]:
+            n = H.shape[0]
+            slabs = 256      # the largest power of two that divides n and leaves slabs of 64 rows or more
+            while slabs > 1 and (n % slabs or n // slabs < 64):
+                slabs //= 2
+            if slabs > 1:
+                part = torch.bmm(H.view(slabs, n // slabs, -1).transpose(1, 2), dZ.reshape(slabs, n // slabs, -1))
+                dW = part.sum(dim=0, dtype=torch.float32).to(W.dtype)
+            else:
+                dW = H.t() @ dZ
+        return dH, dW
+
+
 class GCNLayer:
     """One layer on an ``Adjacency``; layers of equal width share its plans."""
 
@@ -86,9 +114,9 @@ class GCNLayer:
         """H: binary16 [n_cols, d_in]; W: binary16 [d_in, d_out]; bias: fp32 [d_out] or None."""
         assert H.dtype == torch.float16 and W.dtype == torch.float16 and tuple(W.shape) == (self.d_in, self.d_out)
         if self.order == "A_HW":
-            return _SparseProduct.apply(self.adj, H @ W, bias, relu)
+            return _SparseProduct.apply(self.adj, _DenseProduct.apply(H, W), bias, relu)
         M = _SparseProduct.apply(self.adj, H, None, False)
-        Z = M @ W
+        Z = _DenseProduct.apply(M, W)
         if bias is not None:
             Z = Z.float() + bias
         return (torch.relu(Z) if relu else Z).to(torch.float16)
