@@ -20,6 +20,9 @@ namespace {
 
 thread_local std::string g_hip_error;
 
+constexpr double kCopyCostPerColumn = 0.0011;   // ms per feature column read or written by the widening copies
+constexpr double kCopyFixedCost = 0.05;         // and a margin in favour of running at N itself
+
 bool hip_ok(hipError_t e) {
     if (e == hipSuccess) return true;
     g_hip_error = hipGetErrorString(e);
@@ -42,7 +45,8 @@ int upload_array(const std::vector<T>& h, T** d) {
 
 void free_device(rsh::DevicePlan& d) {
     void* ptrs[] = {d.win_row, d.win_tile_off, d.tile_colid, d.tile_mask, d.tile_val_off, d.tile_val,
-                    d.tile_item, d.irr_col, d.irr_val, d.irr_wave, d.irr_row, d.combine, d.scratch};
+                    d.tile_item, d.irr_col, d.irr_val, d.irr_wave, d.irr_row, d.combine, d.scratch,
+                    d.b_pad, d.c_pad, d.bias_pad};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     d = rsh::DevicePlan{};
@@ -73,9 +77,35 @@ int upload_plan(rsh_plan& p) {
     if ((rc = upload_array(h.combine, &d.combine))) return rc;
     const size_t sbytes = (size_t)std::max<int64_t>(1, h.n_scratch_slots) * (size_t)h.geo.N * sizeof(float);
     if (!hip_ok(hipMalloc((void**)&d.scratch, sbytes))) return RSH_ERR_OOM;
+    if (d.n_user != h.geo.N) {
+        const size_t np = (size_t)h.geo.N;
+        if (!hip_ok(hipMalloc(&d.b_pad, (size_t)std::max<int64_t>(1, h.n_cols) * np * 2))) return RSH_ERR_OOM;
+        if (!hip_ok(hipMalloc(&d.c_pad, (size_t)std::max<int64_t>(1, h.n_rows) * np * 4))) return RSH_ERR_OOM;
+        if (!hip_ok(hipMalloc((void**)&d.bias_pad, np * 4))) return RSH_ERR_OOM;
+    }
     if (!hip_ok(hipGetDevice(&p.device))) return RSH_ERR_HIP;
     p.uploaded = true;
     return RSH_OK;
+}
+
+// The width the kernels run at when the caller leaves the choice open.  Every feature panel is a
+// pass over the matrix, and a run at a width other than N adds the copies of B and C.  Costs are
+// in milliseconds as measured on the R-MAT case with 2^20 rows (a pass with a panel of 16 or 32
+// columns 0.33, 64: 0.45, 128: 0.74 including the combine pass; copies 0.0011 per column read or
+// written); only their ratios matter.
+int32_t auto_run_width(int32_t n) {
+    int32_t best = 0;
+    double best_cost = 0.0;
+    for (int32_t unit : {16, 32, 64, 128}) {
+        const int32_t w = (n + unit - 1) / unit * unit;
+        if (w > 4096) continue;
+        int32_t panel = 128;
+        while (w % panel) panel /= 2;
+        const double pass = panel == 128 ? 0.74 : panel == 64 ? 0.45 : 0.33;
+        const double cost = (double)(w / panel) * pass + (w != n ? kCopyFixedCost + kCopyCostPerColumn * (n + w) : 0.0);
+        if (best == 0 || cost < best_cost) best = w, best_cost = cost;
+    }
+    return best;
 }
 
 }  // namespace
@@ -101,6 +131,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->window_schedule = 1;
     o->hub_windows = 0;
     o->xcd_partition_nnz = 0;
+    o->run_width = 0;
     o->transpose = 0;
     o->upload = 1;
     o->threads = 0;
@@ -110,10 +141,14 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
 int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts, rsh_plan_t** out) {
     if (!csr || !out) return RSH_ERR_NULL;
     *out = nullptr;
-    if (N <= 0 || N % 16 != 0 || N > 4096) return RSH_ERR_UNSUPPORTED_N;
+    if (N <= 0 || N > 4096) return RSH_ERR_UNSUPPORTED_N;
     rsh_plan_opts_t o;
     rsh_plan_opts_default(&o);
     if (opts) o = *opts;
+    const int32_t n_user = N;
+    if (o.run_width != 0 && (o.run_width < N || o.run_width % 16 != 0 || o.run_width > 4096)) return RSH_ERR_BAD_OPTION;
+    N = o.run_width != 0 ? o.run_width : auto_run_width(N);   // operands of another width are copied
+    o.run_width = N;
     if ((o.window_rows != 0 && o.window_rows != 16 && o.window_rows != 32 && o.window_rows != 64) ||
         (o.tile_k != 0 && o.tile_k != 16 && o.tile_k != 32))
         return RSH_ERR_BAD_OPTION;
@@ -215,6 +250,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         h.stats.tau_inc = tau_inc;
 
         t0 = std::chrono::steady_clock::now();
+        p->dev.n_user = n_user;
         if (o.upload) {
             rc = upload_plan(*p);
             if (rc) throw rc;
@@ -238,50 +274,89 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     return RSH_OK;
 }
 
-int rsh_spmm(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_stream) {
+namespace {
+
+// Common checks of the three launch entry points; *padded tells whether the operands pass through
+// the plan's buffers of the padded width (then only element alignment is needed).
+int check_launch(const rsh_plan_t* plan, const void* B, const void* C, const void* bias, int c_elem, bool* padded) {
     if (!plan) return RSH_ERR_NULL;
     if (!plan->uploaded) return RSH_ERR_NOT_UPLOADED;
+    *padded = plan->dev.n_user != plan->dev.geo.N;
     if (plan->host.n_rows == 0) return RSH_OK;
-    if (!C_dev || (!B_dev && plan->host.nnz > 0)) return RSH_ERR_NULL;
-    if (((uintptr_t)B_dev & 15u) || ((uintptr_t)C_dev & 15u)) return RSH_ERR_BAD_OPTION;
-    const int rc = rsh::launch_spmm(plan->dev, B_dev, C_dev, hip_stream, nullptr);
+    if (!C || (!B && plan->host.nnz > 0)) return RSH_ERR_NULL;
+    const uintptr_t mb = *padded ? 1u : 15u, mc = *padded ? (uintptr_t)c_elem - 1u : 15u, mbias = *padded ? 3u : 15u;
+    if (((uintptr_t)B & mb) || ((uintptr_t)C & mc) || ((uintptr_t)bias & mbias)) return RSH_ERR_BAD_OPTION;
+    return RSH_OK;
+}
+
+// B (and bias) into the padded buffers before the kernels, C out of its padded buffer after them.
+int widen_operands(const rsh::DevicePlan& d, int64_t n_cols, const void* B, const float* bias, void* stream) {
+    int rc = rsh::launch_widen_rows(B, d.b_pad, n_cols, d.n_user, d.geo.N, 2, stream);
+    if (rc == RSH_OK && bias) rc = rsh::launch_widen_rows(bias, d.bias_pad, 1, d.n_user, d.geo.N, 4, stream);
+    return rc;
+}
+
+}  // namespace
+
+int rsh_spmm(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_stream) {
+    bool padded = false;
+    int rc = check_launch(plan, B_dev, C_dev, nullptr, 4, &padded);
+    if (rc != RSH_OK || plan->host.n_rows == 0) return rc;
+    const rsh::DevicePlan& d = plan->dev;
+    if (!padded) {
+        rc = rsh::launch_spmm(d, B_dev, C_dev, hip_stream, nullptr);
+    } else {
+        rc = widen_operands(d, plan->host.n_cols, B_dev, nullptr, hip_stream);
+        if (rc == RSH_OK) rc = rsh::launch_spmm(d, d.b_pad, d.c_pad, hip_stream, nullptr);
+        if (rc == RSH_OK) rc = rsh::launch_narrow_rows(d.c_pad, C_dev, plan->host.n_rows, d.n_user, d.geo.N, 4, hip_stream);
+    }
     if (rc == RSH_ERR_HIP) g_hip_error = "kernel launch failed";
     return rc;
 }
 
 int rsh_spmm_f16(const rsh_plan_t* plan, const void* B_dev, void* C16_dev, const float* bias_dev, int32_t relu,
                  void* hip_stream) {
-    if (!plan) return RSH_ERR_NULL;
-    if (!plan->uploaded) return RSH_ERR_NOT_UPLOADED;
-    if (relu != 0 && relu != 1) return RSH_ERR_BAD_OPTION;
-    if (plan->host.n_rows == 0) return RSH_OK;
-    if (!C16_dev || (!B_dev && plan->host.nnz > 0)) return RSH_ERR_NULL;
-    if (((uintptr_t)B_dev & 15u) || ((uintptr_t)C16_dev & 15u) || ((uintptr_t)bias_dev & 15u)) return RSH_ERR_BAD_OPTION;
-    const int rc = rsh::launch_spmm_f16(plan->dev, B_dev, C16_dev, bias_dev, relu, hip_stream, nullptr);
+    if (relu != 0 && relu != 1) return plan ? RSH_ERR_BAD_OPTION : RSH_ERR_NULL;
+    bool padded = false;
+    int rc = check_launch(plan, B_dev, C16_dev, bias_dev, 2, &padded);
+    if (rc != RSH_OK || plan->host.n_rows == 0) return rc;
+    const rsh::DevicePlan& d = plan->dev;
+    if (!padded) {
+        rc = rsh::launch_spmm_f16(d, B_dev, C16_dev, bias_dev, relu, hip_stream, nullptr);
+    } else {
+        rc = widen_operands(d, plan->host.n_cols, B_dev, bias_dev, hip_stream);
+        if (rc == RSH_OK) rc = rsh::launch_spmm_f16(d, d.b_pad, d.c_pad, bias_dev ? d.bias_pad : nullptr, relu, hip_stream, nullptr);
+        if (rc == RSH_OK) rc = rsh::launch_narrow_rows(d.c_pad, C16_dev, plan->host.n_rows, d.n_user, d.geo.N, 2, hip_stream);
+    }
     if (rc == RSH_ERR_HIP) g_hip_error = "kernel launch failed";
     return rc;
 }
 
 int rsh_spmm_profile(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_stream, rsh_kernel_times_t* out) {
-    if (!plan || !out) return RSH_ERR_NULL;
+    if (!out) return RSH_ERR_NULL;
     out->ms_tile = out->ms_irregular = out->ms_combine = 0.f;
-    if (!plan->uploaded) return RSH_ERR_NOT_UPLOADED;
-    if (plan->host.n_rows == 0) return RSH_OK;
-    if (!C_dev || (!B_dev && plan->host.nnz > 0)) return RSH_ERR_NULL;
-    if (((uintptr_t)B_dev & 15u) || ((uintptr_t)C_dev & 15u)) return RSH_ERR_BAD_OPTION;
+    bool padded = false;
+    int rc = check_launch(plan, B_dev, C_dev, nullptr, 4, &padded);
+    if (rc != RSH_OK || plan->host.n_rows == 0) return rc;
+    const rsh::DevicePlan& d = plan->dev;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    int rc = RSH_OK;
     for (int i = 0; i < 4 && rc == RSH_OK; ++i)
         if (!hip_ok(hipEventCreate(&ev[i]))) rc = RSH_ERR_HIP;
     if (rc == RSH_OK) {
         void* evp[4] = {ev[0], ev[1], ev[2], ev[3]};
-        rc = rsh::launch_spmm(plan->dev, B_dev, C_dev, hip_stream, evp);
+        if (!padded) {
+            rc = rsh::launch_spmm(d, B_dev, C_dev, hip_stream, evp);
+        } else {   // the copies to and from the padded width lie outside the three timed kernels
+            rc = widen_operands(d, plan->host.n_cols, B_dev, nullptr, hip_stream);
+            if (rc == RSH_OK) rc = rsh::launch_spmm(d, d.b_pad, d.c_pad, hip_stream, evp);
+            if (rc == RSH_OK) rc = rsh::launch_narrow_rows(d.c_pad, C_dev, plan->host.n_rows, d.n_user, d.geo.N, 4, hip_stream);
+        }
         if (!hip_ok(hipStreamSynchronize((hipStream_t)hip_stream))) rc = RSH_ERR_HIP;
         if (rc == RSH_OK) {
             float ms = 0.f;
-            if (plan->dev.n_tile_items > 0 && hip_ok(hipEventElapsedTime(&ms, ev[0], ev[1]))) out->ms_tile = ms;
-            if (plan->dev.n_irr_waves > 0 && hip_ok(hipEventElapsedTime(&ms, ev[1], ev[2]))) out->ms_irregular = ms;
-            if (plan->dev.n_combine > 0 && hip_ok(hipEventElapsedTime(&ms, ev[2], ev[3]))) out->ms_combine = ms;
+            if (d.n_tile_items > 0 && hip_ok(hipEventElapsedTime(&ms, ev[0], ev[1]))) out->ms_tile = ms;
+            if (d.n_irr_waves > 0 && hip_ok(hipEventElapsedTime(&ms, ev[1], ev[2]))) out->ms_irregular = ms;
+            if (d.n_combine > 0 && hip_ok(hipEventElapsedTime(&ms, ev[2], ev[3]))) out->ms_combine = ms;
         }
     }
     for (int i = 0; i < 4; ++i)

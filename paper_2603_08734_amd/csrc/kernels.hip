@@ -694,6 +694,82 @@ __global__ __launch_bounds__(256) void rsh_copy_probe_kernel(const uint4* __rest
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// ---------------------------------------------------------------------------
+// Feature widths the kernels do not run at: the kernels above work on whole 16-byte pieces of
+// rows whose length is a multiple of 32 bytes, so such operands are copied row by row into
+// (B, bias) and out of (C) plan-owned buffers of the run width.  A lane moves one vector per
+// step; the vector is the widest of 16, 8, 4, 2 bytes that divides a narrow row and the
+// caller's alignment (the wide rows are multiples of 32 bytes at 256-byte aligned bases).
+// ---------------------------------------------------------------------------
+template <class VT>
+__global__ __launch_bounds__(256) void rsh_widen_rows_kernel(const VT* __restrict__ src, VT* __restrict__ dst, size_t rows, uint32_t n, uint32_t n_wide) {
+    const size_t total = rows * (size_t)n_wide, stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const size_t r = i / n_wide;
+        const uint32_t j = (uint32_t)(i - r * n_wide);
+        VT v = {};
+        if (j < n) v = src[r * n + j];
+        dst[i] = v;
+    }
+}
+template <class VT>
+__global__ __launch_bounds__(256) void rsh_narrow_rows_kernel(const VT* __restrict__ src, VT* __restrict__ dst, size_t rows, uint32_t n, uint32_t n_wide) {
+    const size_t total = rows * (size_t)n, stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const size_t r = i / n;
+        const uint32_t j = (uint32_t)(i - r * n);
+        dst[i] = src[r * n_wide + j];
+    }
+}
+
+static unsigned copy_blocks(size_t vectors) { return (unsigned)std::min<size_t>((vectors + 255) / 256, 256 * 64); }
+
+// widest vector (bytes) that divides a narrow row of `row_bytes` and the alignment of `narrow`
+static int copy_vector_bytes(const void* narrow, size_t row_bytes, int elem) {
+    int v = 16;
+    while (v > elem && (row_bytes % (size_t)v || (uintptr_t)narrow % (uintptr_t)v)) v /= 2;
+    return v;
+}
+
+template <class VT>
+static void widen_t(const void* src, void* dst, int64_t rows, size_t row_bytes, size_t wide_bytes, hipStream_t st) {
+    const uint32_t n = (uint32_t)(row_bytes / sizeof(VT)), nw = (uint32_t)(wide_bytes / sizeof(VT));
+    hipLaunchKernelGGL(rsh_widen_rows_kernel<VT>, dim3(copy_blocks((size_t)rows * nw)), dim3(256), 0, st,
+                       (const VT*)src, (VT*)dst, (size_t)rows, n, nw);
+}
+template <class VT>
+static void narrow_t(const void* src, void* dst, int64_t rows, size_t row_bytes, size_t wide_bytes, hipStream_t st) {
+    const uint32_t n = (uint32_t)(row_bytes / sizeof(VT)), nw = (uint32_t)(wide_bytes / sizeof(VT));
+    hipLaunchKernelGGL(rsh_narrow_rows_kernel<VT>, dim3(copy_blocks((size_t)rows * n)), dim3(256), 0, st,
+                       (const VT*)src, (VT*)dst, (size_t)rows, n, nw);
+}
+
+int launch_widen_rows(const void* src, void* dst, int64_t rows, int n, int n_pad, int elem, void* stream) {
+    if (rows <= 0) return RSH_OK;
+    const size_t rb = (size_t)n * elem, wb = (size_t)n_pad * elem;
+    hipStream_t st = (hipStream_t)stream;
+    switch (copy_vector_bytes(src, rb, elem)) {
+        case 16: widen_t<uint4_t>(src, dst, rows, rb, wb, st); break;
+        case 8: widen_t<uint2_t>(src, dst, rows, rb, wb, st); break;
+        case 4: widen_t<uint32_t>(src, dst, rows, rb, wb, st); break;
+        default: widen_t<uint16_t>(src, dst, rows, rb, wb, st); break;
+    }
+    return hipGetLastError() == hipSuccess ? RSH_OK : RSH_ERR_HIP;
+}
+
+int launch_narrow_rows(const void* src, void* dst, int64_t rows, int n, int n_pad, int elem, void* stream) {
+    if (rows <= 0) return RSH_OK;
+    const size_t rb = (size_t)n * elem, wb = (size_t)n_pad * elem;
+    hipStream_t st = (hipStream_t)stream;
+    switch (copy_vector_bytes(dst, rb, elem)) {
+        case 16: narrow_t<uint4_t>(src, dst, rows, rb, wb, st); break;
+        case 8: narrow_t<uint2_t>(src, dst, rows, rb, wb, st); break;
+        case 4: narrow_t<uint32_t>(src, dst, rows, rb, wb, st); break;
+        default: narrow_t<uint16_t>(src, dst, rows, rb, wb, st); break;
+    }
+    return hipGetLastError() == hipSuccess ? RSH_OK : RSH_ERR_HIP;
+}
+
 int launch_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
     const size_t n16 = bytes / 16;
     if (n16 == 0) return RSH_OK;

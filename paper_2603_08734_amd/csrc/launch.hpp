@@ -24,6 +24,12 @@ struct DevicePlan {
     int32_t* irr_row = nullptr;
     uint32_t* combine = nullptr;
     float* scratch = nullptr;
+    // feature widths that are not a multiple of 16 (n_user != geo.N): operands pass through these
+    // plan-owned buffers of the padded width
+    int n_user = 0;
+    void* b_pad = nullptr;      // binary16 [n_cols][geo.N]
+    void* c_pad = nullptr;      // fp32 (or binary16) [n_rows][geo.N]
+    float* bias_pad = nullptr;  // fp32 [geo.N]
 };
 
 // Enqueue the tile, irregular and combine kernels on `stream` (a hipStream_t).  When
@@ -35,6 +41,11 @@ int launch_spmm(const DevicePlan& d, const void* B_dev, void* C_dev, void* strea
 // device array of N floats or null, relu != 0 selects max(x, 0).
 int launch_spmm_f16(const DevicePlan& d, const void* B_dev, void* C16_dev, const float* bias_dev, int relu,
                     void* stream, void* const* events);
+
+// Row-wise copies between a matrix of `n` columns and one of `n_pad` >= n columns (`elem` bytes per
+// element, 2 or 4): widen (pad columns become zero) and narrow (pad columns are dropped).
+int launch_widen_rows(const void* src, void* dst, int64_t rows, int n, int n_pad, int elem, void* stream);
+int launch_narrow_rows(const void* src, void* dst, int64_t rows, int n, int n_pad, int elem, void* stream);
 
 // Plain device-to-device copy of `bytes` (multiple of 16) used to calibrate traffic counters.
 int launch_copy_probe(const void* src_dev, void* dst_dev, size_t bytes, void* stream);

@@ -317,3 +317,79 @@ def test_transposed_product(k):
     C_ref, S, _ = oracle.spmm(At.indptr.astype(np.int64), At.indices.astype(np.int32), At.data.view(np.float16), B)
     assert_parity(C.cpu().numpy(), C_ref, S, f"transposed config {k}")
     plan.destroy()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("N,run_width", [(1, 0), (7, 0), (20, 0), (33, 0), (100, 0), (250, 0), (100, 112), (7, 48),
+                                         (48, 0), (48, 48), (96, 96), (112, 0), (112, 112)])
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile"])
+def test_feature_widths_that_the_kernels_do_not_run_at(N, run_width, mode):
+    """Any width runs at a multiple of 16 (chosen by the planner or given) through the plan's padded
+    buffers: plain and fused entry points against the oracle, on tensors whose rows are not 16-byte
+    aligned.  The pairs with run_width == N keep the narrow-panel kernels (two or four lanes per row,
+    several panels) under test, which the planner's own choice avoids."""
+    from oracle import gcn as oracle_gcn
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, _, _ = make_config(3, small=True)
+    B = dense_B(A.n_cols, N, "normal", seed=N)
+    bias_np = np.random.default_rng(N).normal(size=N).astype(np.float32)
+    print(f"case width N={N} run_width={run_width} mode={mode}", flush=True)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, run_width=run_width, **OPTION_SETS[mode])
+    Bd = torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16)
+    guard = 64                                        # canaries around C catch writes outside its N columns
+    buf = torch.full((A.n_rows * N + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+    C = buf[guard:guard + A.n_rows * N].view(A.n_rows, N)
+    plan.spmm(Bd, C)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:guard]).all() and torch.isnan(buf[-guard:]).all()
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    assert_parity(C.cpu().numpy(), C_ref, S, f"N={N} {mode}")
+    t = plan.spmm_profile(Bd, C)
+    assert set(t) == {"tile", "irregular", "combine"}
+    C16 = torch.full((A.n_rows, N), float("nan"), dtype=torch.float16, device="cuda")
+    plan.spmm_f16(Bd, C16, torch.from_numpy(bias_np).cuda(), True)
+    torch.cuda.synchronize()
+    Z, S2 = oracle_gcn.product_epilogue(A.row_ptr, A.col_idx, A.val, A.n_cols, B, bias_np, True)
+    got = C16.cpu().numpy()
+    assert not np.isnan(got).any()
+    bound = TOL * S2 + 2.0 ** -11 * (np.abs(Z) + TOL * S2) + 2.0 ** -24
+    assert (np.abs(got.astype(np.float64) - Z) <= bound).all()
+    plan.destroy()
+
+
+@pytest.mark.gpu
+def test_padded_width_under_graph_replay():
+    """At a width the kernels do not run at, rsh_spmm is five kernel launches (copy in, three kernels,
+    copy out) on plan-owned buffers: still capturable, and every replay equals the eager call."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, _, dist = make_config(2, small=True)
+    N = 100
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, xcd_partition_nnz=32, max_tiles_per_item=3)
+    Bs = torch.zeros((A.n_cols, N), dtype=torch.float16, device="cuda")
+    Cs = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.spmm(Bs, Cs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.spmm(Bs, Cs)
+    for seed in (5, 6, 7):
+        B = dense_B(A.n_cols, N, dist, seed=seed)
+        Bs.copy_(torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16))
+        Cs.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Cs.cpu().numpy()
+        C_eager = torch.full_like(Cs, float("nan"))
+        plan.spmm(Bs, C_eager)
+        torch.cuda.synchronize()
+        assert np.array_equal(got, C_eager.cpu().numpy()), "a replay differs from the eager call"
+        R, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+        assert_parity(got, R, S, f"graph replay at N = {N}, seed {seed}")
+    plan.destroy()

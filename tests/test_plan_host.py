@@ -248,8 +248,15 @@ def test_abi_error_codes():
     rp, ci, v = A.row_ptr.copy(), A.col_idx.copy(), A.val.view(np.uint16).copy()
     assert create(rp, ci, v, A.n_rows, A.n_cols) == B_.RSH_OK
     assert L.rsh_plan_create(None, 32, None, ctypes.byref(out)) == B_.RSH_ERR_NULL
-    for bad_N in (0, -16, 8, 40, 8192):
+    for bad_N in (0, -16, 4097, 8192):
         assert create(rp, ci, v, A.n_rows, A.n_cols, N=bad_N) == B_.RSH_ERR_UNSUPPORTED_N
+    for odd_N in (1, 8, 40, 100):      # planned at a multiple of 16
+        assert create(rp, ci, v, A.n_rows, A.n_cols, N=odd_N) == B_.RSH_OK
+    for bad_width in (16, 40, 8192):   # below N, not a multiple of 16, too wide
+        o2 = binding.rsh_plan_opts_default()
+        o2.upload = 0
+        o2.run_width = bad_width
+        assert create(rp, ci, v, A.n_rows, A.n_cols, N=32, o=o2) == B_.RSH_ERR_BAD_OPTION
     bad = ci.copy(); bad[5] = A.n_cols
     assert create(rp, bad, v, A.n_rows, A.n_cols) == B_.RSH_ERR_INVALID_CSR
     bad = ci.copy(); bad[1] = bad[0]
@@ -285,7 +292,7 @@ def test_abi_error_codes():
     assert L.rsh_plan_destroy(None) == B_.RSH_OK
     assert L.rsh_status_string(B_.RSH_ERR_INVALID_CSR).decode().startswith("invalid CSR")
     with pytest.raises(RshError):
-        Plan(rp, ci, v, A.n_cols, 24, upload=0)
+        Plan(rp, ci, v, A.n_cols, 5000, upload=0)
 
 
 def test_long_rows_are_split_into_bounded_slices_and_windows_into_bounded_items():
