@@ -25,13 +25,16 @@ from .binding import Plan
 class Adjacency:
     """A fixed sparse A (CSR, binary16 values) and its plans by (feature width, transposed)."""
 
-    def __init__(self, row_ptr, col_idx, val_f16, n_cols: int, **plan_opts):
+    def __init__(self, row_ptr, col_idx, val_f16, n_cols: int, symmetric: bool = False, **plan_opts):
+        """symmetric=True (the caller vouches that A equals its transpose, values included, as the
+        normalised adjacency of an undirected graph does): the backward pass reuses the plan of A."""
         self._csr = (row_ptr, col_idx, val_f16, int(n_cols))
         self._opts = dict(plan_opts)
+        self._symmetric = bool(symmetric)
         self._plans: dict[tuple[int, bool], Plan] = {}
 
     def plan(self, width: int, transposed: bool = False) -> Plan:
-        key = (int(width), bool(transposed))
+        key = (int(width), bool(transposed) and not self._symmetric)
         if key not in self._plans:
             row_ptr, col_idx, val, n_cols = self._csr
             self._plans[key] = Plan(row_ptr, col_idx, val, n_cols, key[0], transpose=1 if transposed else 0, **self._opts)

@@ -92,7 +92,7 @@ def test_two_layer_network_trains():
     T2 = (rng.normal(size=(d, d)) / np.sqrt(d)).astype(np.float16)
     Ht, _ = oracle_gcn.layer_forward(*args, X, T1, None, True)
     target = oracle_gcn.layer_forward(*args, Ht, T2, None, False)[0].astype(np.float32)
-    adj = Adjacency(*args)
+    adj = Adjacency(*args, symmetric=False)
     l1, l2 = GCNLayer(adj, d, d, "AH_W"), GCNLayer(adj, d, d, "AH_W")
     assert len(adj._plans) == 1                      # one width, one forward plan
     Xd, Td = torch.from_numpy(X).cuda(), torch.from_numpy(target).cuda()
@@ -127,3 +127,30 @@ def test_two_layer_network_trains():
         scale = np.abs(want).max()
         assert np.abs(got - want).max() <= 0.02 * scale, f"{name}: {np.abs(got - want).max()} vs scale {scale}"
     adj.destroy()
+
+
+def test_symmetric_adjacency_reuses_its_plan():
+    """Config 2's normalised adjacency is symmetric in pattern and values: with symmetric=True the
+    backward pass runs on the forward plan and gives the gradient the transposed plan gives."""
+    import torch
+    from paper_2603_08734_amd.gcn import Adjacency, GCNLayer
+    A, _, _ = make_config(2, small=True)
+    M = sp.csr_matrix((A.val.astype(np.float32), A.col_idx, A.row_ptr), shape=(A.n_rows, A.n_cols))
+    assert abs(M - M.T).max() == 0
+    d = 32
+    rng = np.random.default_rng(8)
+    H = torch.from_numpy(rng.normal(size=(A.n_cols, d)).astype(np.float16)).cuda()
+    W = torch.from_numpy((rng.normal(size=(d, d)) / 6).astype(np.float16)).cuda()
+    G = torch.from_numpy(rng.normal(size=(A.n_rows, d)).astype(np.float16)).cuda()
+    grads = []
+    for symmetric in (False, True):
+        adj = Adjacency(A.row_ptr, A.col_idx, A.val, A.n_cols, symmetric=symmetric)
+        Hd = H.clone().requires_grad_(True)
+        GCNLayer(adj, d, d, "A_HW")(Hd, W, None, True).backward(G)
+        torch.cuda.synchronize()
+        assert len(adj._plans) == (1 if symmetric else 2)
+        grads.append(Hd.grad.float().cpu().numpy())
+        adj.destroy()
+    # the two plans order their sums differently: equal up to fp32 accumulation and one binary16 rounding
+    scale = np.abs(grads[0]).max()
+    assert np.abs(grads[0] - grads[1]).max() <= 2.0 ** -9 * scale
