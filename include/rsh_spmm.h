@@ -88,10 +88,7 @@ typedef struct {
                              them; 0 = auto (128 for feature panels of 128 columns, 16384 / panel
                              columns for narrower ones), negative = off                            */
     int32_t run_width;    /* feature width the kernels run at: a multiple of 16 that is >= N and <= 4096, or
-                             0 = auto: N rounded up to 16, 32, 64 or 128 columns, whichever a cost model of
-                             passes over the matrix (one per feature panel, panels being the largest power
-                             of two up to 128 that divides the width) plus the copies to and from the wider
-                             buffers (see rsh_plan_create) rates cheapest; N itself when N is such a width */
+                             0 = N rounded up to a multiple of 16 (see rsh_plan_create)                */
     int32_t transpose;    /* 1 = plan C = A^T * B instead (the product a backward pass needs): the CSR is
                              transposed on the host first, and everything the plan reports (rows, columns,
                              decode, row order) then refers to A^T; B has n_rows rows, C has n_cols rows */
@@ -132,13 +129,14 @@ int rsh_plan_opts_default(rsh_plan_opts_t *opts);
  * the device arrays and the plan's private scratch are allocated on the current
  * HIP device.  opts == NULL means defaults.
  * Limits: nnz, n_rows * 1 and n_cols * (2N) must each be below 2^31.
- * Feature width: the kernels work at multiples of 16, and in panels that are the largest power
- * of two (up to 128 columns) dividing the width, one pass over the matrix per panel.  When N is
- * not a multiple of 16, or a wider run is cheaper (opts->run_width; 112 runs as 128), the kernels
- * run at a width NR > N: the plan then owns a binary16 buffer [n_cols][NR] and an fp32 buffer
- * [n_rows][NR] on the device, every product first copies B into the wide buffer (pad columns
- * zero) and last copies the N columns of the result into C, and B, C and bias then only need
- * the alignment of their element type.  Results are those of the padded product, column for
+ * Feature width: the kernels work at multiples of 16, in feature panels of up to 128 columns
+ * (irregular kernel; a last partial panel idles lanes) and 256, 128, ... 16 columns (tile kernel;
+ * widest first), one pass over the matrix per panel.  When N is not a multiple of 16 (or
+ * opts->run_width asks for it) the kernels run at a width NR > N: the plan then owns a binary16
+ * buffer [n_cols][NR] and an fp32 buffer [n_rows][NR] on the device, every product first copies
+ * B into the wide buffer (pad columns zero) and last copies the N columns of the result into C,
+ * and B, C and bias then only need the alignment of their element type.  Results are those of
+ * the padded product, column for
  * column; the cost is one more pass over B and C.
  */
 int rsh_plan_create(const rsh_csr_t *csr, int32_t N, const rsh_plan_opts_t *opts, rsh_plan_t **out);

@@ -20,8 +20,6 @@ namespace {
 
 thread_local std::string g_hip_error;
 
-constexpr double kCopyCostPerColumn = 0.0011;   // ms per feature column read or written by the widening copies
-constexpr double kCopyFixedCost = 0.05;         // and a margin in favour of running at N itself
 
 bool hip_ok(hipError_t e) {
     if (e == hipSuccess) return true;
@@ -88,25 +86,8 @@ int upload_plan(rsh_plan& p) {
     return RSH_OK;
 }
 
-// The width the kernels run at when the caller leaves the choice open.  Every feature panel is a
-// pass over the matrix, and a run at a width other than N adds the copies of B and C.  Costs are
-// in milliseconds as measured on the R-MAT case with 2^20 rows (a pass with a panel of 16 or 32
-// columns 0.33, 64: 0.45, 128: 0.74 including the combine pass; copies 0.0011 per column read or
-// written); only their ratios matter.
-int32_t auto_run_width(int32_t n) {
-    int32_t best = 0;
-    double best_cost = 0.0;
-    for (int32_t unit : {16, 32, 64, 128}) {
-        const int32_t w = (n + unit - 1) / unit * unit;
-        if (w > 4096) continue;
-        int32_t panel = 128;
-        while (w % panel) panel /= 2;
-        const double pass = panel == 128 ? 0.74 : panel == 64 ? 0.45 : 0.33;
-        const double cost = (double)(w / panel) * pass + (w != n ? kCopyFixedCost + kCopyCostPerColumn * (n + w) : 0.0);
-        if (best == 0 || cost < best_cost) best = w, best_cost = cost;
-    }
-    return best;
-}
+// The width the kernels run at when the caller leaves the choice open: the next multiple of 16.
+int32_t auto_run_width(int32_t n) { return (n + 15) / 16 * 16; }
 
 }  // namespace
 

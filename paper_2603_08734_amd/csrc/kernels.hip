@@ -104,28 +104,41 @@ __device__ __forceinline__ uint2_t finish4(const OutFused& o, int f, float4_t v)
 // stores of consecutive 16-byte pieces (lane t writes pieces t and TPR + t), i.e. whole lines, after
 // a turn through the team's LDS stage; lane-owned pieces would make every store a half-written
 // 32-byte sector, which the streaming path handles at a third of the rate.
+// Which of a lane's two 16-byte pieces of an fp32 panel row exist: all of them except in the last
+// panel of a width that is not a multiple of the panel, where pieces past the last feature are
+// not stored.
+struct PanelPieces {
+    bool first, second;   // pieces tl and TPR + tl
+};
+template <int TPR, bool PARTIAL>
+__device__ __forceinline__ PanelPieces panel_pieces(int N, int panel, int tl) {
+    if constexpr (!PARTIAL) return {true, true};
+    const int live = min(8 * TPR, N - panel);   // features of this panel, a multiple of 16
+    return {4 * tl < live, 4 * TPR + 4 * tl < live};
+}
 template <int TPR>
-__device__ __forceinline__ void store_row_streaming(float* out_row, const float (&acc)[8], float* stage, int tl) {
+__device__ __forceinline__ void store_row_streaming(float* out_row, const float (&acc)[8], float* stage, int tl, PanelPieces keep) {
     *reinterpret_cast<float4_t*>(stage + 8 * tl) = (float4_t){acc[0], acc[1], acc[2], acc[3]};
     *reinterpret_cast<float4_t*>(stage + 8 * tl + 4) = (float4_t){acc[4], acc[5], acc[6], acc[7]};
     const float4_t v0 = *reinterpret_cast<const float4_t*>(stage + 4 * tl);
     const float4_t v1 = *reinterpret_cast<const float4_t*>(stage + 4 * TPR + 4 * tl);
-    store_c_streaming(out_row + 4 * tl, v0);
-    store_c_streaming(out_row + 4 * TPR + 4 * tl, v1);
+    if (keep.first) store_c_streaming(out_row + 4 * tl, v0);
+    if (keep.second) store_c_streaming(out_row + 4 * TPR + 4 * tl, v1);
 }
 
 // A team's finished row `row` of C, panel starting at feature `panel`.  In binary16 a lane's
 // eight features are one 16-byte piece and the team's pieces are consecutive, so the row
 // leaves as one store of whole lines without a turn through LDS.
-template <int TPR>
+template <int TPR, bool PARTIAL>
 __device__ __forceinline__ void emit_row(const OutPlain& o, size_t row, int N, int panel, const float (&acc)[8],
                                          float* stage, int tl) {
-    store_row_streaming<TPR>(o.C + row * N + panel, acc, stage, tl);
+    store_row_streaming<TPR>(o.C + row * N + panel, acc, stage, tl, panel_pieces<TPR, PARTIAL>(N, panel, tl));
 }
-template <int TPR>
+template <int TPR, bool PARTIAL>
 __device__ __forceinline__ void emit_row(const OutFused& o, size_t row, int N, int panel, const float (&acc)[8],
                                          float*, int tl) {
     const int f = panel + 8 * tl;
+    if (PARTIAL && f >= N) return;   // lane past the last feature of a partial panel
     const uint2_t lo = finish4(o, f, (float4_t){acc[0], acc[1], acc[2], acc[3]});
     const uint2_t hi = finish4(o, f + 4, (float4_t){acc[4], acc[5], acc[6], acc[7]});
     __builtin_nontemporal_store((uint4_t){lo[0], lo[1], hi[0], hi[1]}, reinterpret_cast<uint4_t*>(o.C + row * N + f));
@@ -191,7 +204,7 @@ struct ShortRowState {
     int N, panel, tl, L, k, rq;
 };
 
-template <int U, int TPR, class OUT>
+template <int U, int TPR, bool PARTIAL, class OUT>
 __device__ __forceinline__ void short_rows_group(const BRows& Bp, int my_col, float my_val, int my_row,
                                                  int team_base, int j0, float (&acc)[8], ShortRowState<OUT>& st) {
     uint4_t b[U];
@@ -215,7 +228,7 @@ __device__ __forceinline__ void short_rows_group(const BRows& Bp, int my_col, fl
             st.k = 0;
             const int row = shfl_i32(my_row, team_base + st.rq);
             ++st.rq;
-            if (row >= 0) emit_row<TPR>(st.out, (size_t)row, st.N, st.panel, acc, st.stage, st.tl);
+            if (row >= 0) emit_row<TPR, PARTIAL>(st.out, (size_t)row, st.N, st.panel, acc, st.stage, st.tl);
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = 0.f;
         }
@@ -238,26 +251,30 @@ __device__ __forceinline__ void gather_steps(const BRows& Bp, int my_col, float 
     if (steps & 1) gather_group<1>(Bp, my_col, my_val, team_base + j, acc);
 }
 
-template <int TPR, class OUT>
+// PARTIAL: the panel (there is one, the last) holds fewer than 8 * TPR features; lanes past the last
+// feature gather the panel's first piece and store nothing.  Full panels carry no such checks.
+template <int TPR, class OUT, bool PARTIAL>
 __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void rsh_irregular_kernel(
     const uint4* __restrict__ waves, XcdSplit xs,
     const int32_t* __restrict__ irr_row, const int32_t* __restrict__ irr_col,
     const uint16_t* __restrict__ irr_val, const __half* __restrict__ B, const OUT out,
-    float* __restrict__ scratch, int N) {
+    float* __restrict__ scratch, int N, int feature0) {
     constexpr int G = 64 / TPR;
     __shared__ __attribute__((aligned(16))) float lds_stage[kWavesPerBlock][64 * 8];
     const int lane = threadIdx.x & 63;
     uint32_t wave;
     if (!xcd_work_item(xs, &wave)) return;
     const int team = lane / TPR, tl = lane % TPR, team_base = team * TPR;
-    const int panel = blockIdx.y * (TPR * 8);
+    const int panel = feature0 + blockIdx.y * (TPR * 8);
     float* stage = lds_stage[threadIdx.x >> 6] + team * (TPR * 8);
 
     const uint4 d = waves[wave];
     const uint32_t start = __builtin_amdgcn_readfirstlane(d.x), count = __builtin_amdgcn_readfirstlane(d.y);
     const uint32_t dst = __builtin_amdgcn_readfirstlane(d.z), info = __builtin_amdgcn_readfirstlane(d.w);
     const uint32_t kind = info & kWaveKindMask;
-    const BRows Bp{reinterpret_cast<const char*>(B + panel), 2u * (uint32_t)N, 16u * (uint32_t)tl};
+    // a lane past the last feature (partial last panel) reads the panel's first piece and stores nothing
+    const BRows Bp{reinterpret_cast<const char*>(B + panel), 2u * (uint32_t)N,
+                   (!PARTIAL || panel + 8 * tl < N) ? 16u * (uint32_t)tl : 0u};
 
     float acc[8];
 #pragma unroll
@@ -266,11 +283,12 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
     if (kind == kWaveZeroRows) {
         for (uint32_t q = team; q < count; q += G) {
             if constexpr (OUT::kFused) {
-                emit_row<TPR>(out, (size_t)irr_row[dst + q], N, panel, acc, stage, tl);   // act(bias)
+                emit_row<TPR, PARTIAL>(out, (size_t)irr_row[dst + q], N, panel, acc, stage, tl);   // act(bias)
             } else {
                 float* o = out.C + (size_t)irr_row[dst + q] * N + panel;
-                store_c_streaming(o + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
-                store_c_streaming(o + 4 * TPR + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
+                const PanelPieces keep = panel_pieces<TPR, PARTIAL>(N, panel, tl);
+                if (keep.first) store_c_streaming(o + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
+                if (keep.second) store_c_streaming(o + 4 * TPR + 4 * tl, (float4_t){0.f, 0.f, 0.f, 0.f});
             }
         }
         return;
@@ -290,16 +308,16 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
         ShortRowState<OUT> st{out, stage, N, panel, tl, L, 0, 0};
         const int steps = R * L;
         int j = 0;
-        for (; j + 8 <= steps; j += 8) short_rows_group<8, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+        for (; j + 8 <= steps; j += 8) short_rows_group<8, TPR, PARTIAL>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
         if (steps & 4) {
-            short_rows_group<4, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+            short_rows_group<4, TPR, PARTIAL>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
             j += 4;
         }
         if (steps & 2) {
-            short_rows_group<2, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+            short_rows_group<2, TPR, PARTIAL>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
             j += 2;
         }
-        if (steps & 1) short_rows_group<1, TPR>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
+        if (steps & 1) short_rows_group<1, TPR, PARTIAL>(Bp, my_col, my_val, my_row, team_base, j, acc, st);
         return;
     }
 
@@ -325,10 +343,11 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) __attribute__((amdgpu_waves_pe
     for (int i = 0; i < 8; ++i) acc[i] = sum_over_teams<TPR>(acc[i], lane);
     if (team != 0) return;
     if constexpr (OUT::kFused) {
-        if (info & kWaveToScratch) store_row_streaming<TPR>(scratch + (size_t)dst * N + panel, acc, stage, tl);
-        else emit_row<TPR>(out, (size_t)dst, N, panel, acc, stage, tl);
+        if (info & kWaveToScratch) store_row_streaming<TPR>(scratch + (size_t)dst * N + panel, acc, stage, tl, panel_pieces<TPR, PARTIAL>(N, panel, tl));
+        else emit_row<TPR, PARTIAL>(out, (size_t)dst, N, panel, acc, stage, tl);
     } else {
-        store_row_streaming<TPR>(((info & kWaveToScratch) ? scratch : out.C) + (size_t)dst * N + panel, acc, stage, tl);
+        store_row_streaming<TPR>(((info & kWaveToScratch) ? scratch : out.C) + (size_t)dst * N + panel, acc, stage, tl,
+                                 panel_pieces<TPR, PARTIAL>(N, panel, tl));
     }
 }
 
@@ -384,7 +403,7 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     const int32_t* __restrict__ win_row, const int32_t* __restrict__ tile_colid,
     const uint64_t* __restrict__ tile_mask, const uint32_t* __restrict__ tile_val_off,
     const uint16_t* __restrict__ tile_val, const __half* __restrict__ B, const OUT out,
-    float* __restrict__ scratch, int N) {
+    float* __restrict__ scratch, int N, int feature0) {
     using Gm = TileGeom<NCH, NW, KT>;
     constexpr int P = Gm::P, TPR = Gm::TPR, NLD = Gm::NLD, LDB = Gm::LDB, THREADS = Gm::THREADS, CPL = Gm::CPL;
     using vals_t = typename std::conditional<KT == 16, uint2_t, uint4_t>::type;   // CPL halves per lane
@@ -408,7 +427,7 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
     const uint4 it = items[item];
     const uint32_t win = __builtin_amdgcn_readfirstlane(it.x), t_begin = __builtin_amdgcn_readfirstlane(it.y);
     const uint32_t t_end = __builtin_amdgcn_readfirstlane(it.z), dst = __builtin_amdgcn_readfirstlane(it.w);
-    const int panel = blockIdx.y * P;
+    const int panel = feature0 + blockIdx.y * P;
     _Float16* sb0 = lds_b[NW == 1 ? wib : 0];
     uint16_t* sv = lds_v[wib];
 
@@ -788,42 +807,49 @@ static inline uint32_t grid_for(const XcdSplit& xs) {
     return 8u * ((longest + kWavesPerBlock - 1) / kWavesPerBlock);
 }
 
+// Full panels in one launch; a last partial panel (N not a multiple of the panel) in a launch of its own.
 template <int TPR, class OUT>
 static void launch_irregular_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
-    dim3 grid(grid_for(d.irr_split), (unsigned)(d.geo.N / d.geo.irr_panel));
-    hipLaunchKernelGGL((rsh_irregular_kernel<TPR, OUT>), grid, dim3(64 * kWavesPerBlock), 0, st,
-                       (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, out,
-                       d.scratch, d.geo.N);
+    const int full = d.geo.N / d.geo.irr_panel;
+    if (full > 0)
+        hipLaunchKernelGGL((rsh_irregular_kernel<TPR, OUT, false>), dim3(grid_for(d.irr_split), (unsigned)full), dim3(64 * kWavesPerBlock),
+                           0, st, (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, out,
+                           d.scratch, d.geo.N, 0);
+    if (d.geo.N % d.geo.irr_panel)
+        hipLaunchKernelGGL((rsh_irregular_kernel<TPR, OUT, true>), dim3(grid_for(d.irr_split), 1u), dim3(64 * kWavesPerBlock),
+                           0, st, (const uint4*)d.irr_wave, d.irr_split, d.irr_row, d.irr_col, d.irr_val, (const __half*)B, out,
+                           d.scratch, d.geo.N, full * d.geo.irr_panel);
 }
 
+// `panels` panels of 16 * NCH features starting at feature `feature0`
 template <int NCH, int NW, int D, int KT, class OUT>
-static void launch_tile_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
+static void launch_tile_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
     constexpr int items_per_block = NW == 1 ? kWavesPerBlock : 1;
     uint32_t longest = 0;
     for (int x = 0; x < 8; ++x) longest = std::max(longest, d.tile_split.start[x + 1] - d.tile_split.start[x]);
-    dim3 grid(8u * ((longest + items_per_block - 1) / items_per_block), (unsigned)(d.geo.N / d.geo.tile_panel));
+    dim3 grid(8u * ((longest + items_per_block - 1) / items_per_block), (unsigned)panels);
     hipLaunchKernelGGL((rsh_tile_kernel<NCH, NW, D, KT, OUT>), grid, dim3(NW == 1 ? 64 * kWavesPerBlock : 64 * NW), 0, st,
                        (const uint4*)d.tile_item, d.tile_split, d.win_row, d.tile_colid, d.tile_mask, d.tile_val_off,
-                       d.tile_val, (const __half*)B, out, d.scratch, d.geo.N);
+                       d.tile_val, (const __half*)B, out, d.scratch, d.geo.N, feature0);
 }
 
 // Fragments in flight per thread: one for 16-row windows, two when the waves of a window share
 // the staging (measured best of 1, 2, 3).
 template <int NCH, int NW, class OUT>
-static int launch_tile_d(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
+static int launch_tile_d(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
     constexpr int D = NW == 1 ? 1 : 2;
-    if (d.geo.tile_k == 16) launch_tile_t<NCH, NW, D, 16>(d, B, out, st);
-    else if (d.geo.tile_k == 32) launch_tile_t<NCH, NW, D, 32>(d, B, out, st);
+    if (d.geo.tile_k == 16) launch_tile_t<NCH, NW, D, 16>(d, B, out, st, feature0, panels);
+    else if (d.geo.tile_k == 32) launch_tile_t<NCH, NW, D, 32>(d, B, out, st, feature0, panels);
     else return RSH_ERR_BAD_OPTION;
     return RSH_OK;
 }
 
 template <int NCH, class OUT>
-static int launch_tile_nw(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
+static int launch_tile_nw(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
     switch (d.geo.nw) {
-        case 1: return launch_tile_d<NCH, 1>(d, B, out, st);
-        case 2: return launch_tile_d<NCH, 2>(d, B, out, st);
-        case 4: return launch_tile_d<NCH, 4>(d, B, out, st);
+        case 1: return launch_tile_d<NCH, 1>(d, B, out, st, feature0, panels);
+        case 2: return launch_tile_d<NCH, 2>(d, B, out, st, feature0, panels);
+        case 4: return launch_tile_d<NCH, 4>(d, B, out, st, feature0, panels);
         default: return RSH_ERR_BAD_OPTION;
     }
 }
@@ -837,13 +863,21 @@ static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* 
     mark(0);
     int rc = RSH_OK;
     if (d.n_tile_items > 0) {
-        switch (d.geo.tile_nch) {
-            case 1: rc = launch_tile_nw<1>(d, B, out, st); break;
-            case 2: rc = launch_tile_nw<2>(d, B, out, st); break;
-            case 4: rc = launch_tile_nw<4>(d, B, out, st); break;
-            case 8: rc = launch_tile_nw<8>(d, B, out, st); break;
-            case 16: rc = launch_tile_nw<16>(d, B, out, st); break;
-            default: return RSH_ERR_UNSUPPORTED_N;
+        // The feature width in 16-column chunks is covered by panels of 16, 8, 4, 2 and 1 chunks,
+        // widest first (N = 160: one panel of 128 columns and one of 32), one launch per panel width.
+        int chunks = d.geo.N / 16, feature0 = 0;
+        for (int nch = 16; nch >= 1 && rc == RSH_OK; nch /= 2) {
+            const int panels = chunks / nch;
+            if (panels == 0) continue;
+            switch (nch) {
+                case 1: rc = launch_tile_nw<1>(d, B, out, st, feature0, panels); break;
+                case 2: rc = launch_tile_nw<2>(d, B, out, st, feature0, panels); break;
+                case 4: rc = launch_tile_nw<4>(d, B, out, st, feature0, panels); break;
+                case 8: rc = launch_tile_nw<8>(d, B, out, st, feature0, panels); break;
+                default: rc = launch_tile_nw<16>(d, B, out, st, feature0, panels); break;
+            }
+            feature0 += panels * nch * 16;
+            chunks -= panels * nch;
         }
         if (rc != RSH_OK) return rc;
     }

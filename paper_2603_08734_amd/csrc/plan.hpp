@@ -20,11 +20,11 @@ constexpr uint32_t kWaveToScratch = 4u;  // slice result goes to a scratch slot
 // Feature-panel geometry derived from N (both kernels walk N in panels).
 struct Geometry {
     int N = 0;
-    int irr_panel = 0;  // features per irregular-kernel panel: gcd(N, 512)
+    int irr_panel = 0;  // features per irregular-kernel panel: 128, or the power of two >= N below that
     int irr_tpr = 0;    // lanes per B-row segment = irr_panel / 8
     int irr_teams = 0;  // 64 / irr_tpr
-    int tile_panel = 0; // features per tile-kernel panel: gcd(N, 256)
-    int tile_nch = 0;   // 16-feature MFMA chunks per panel
+    int tile_panel = 0; // features of the widest tile-kernel panel: the largest power of two <= min(N, 256)
+    int tile_nch = 0;   // 16-feature MFMA chunks of that panel
     int win_rows = 16;  // rows per window (16, 32 or 64)
     int nw = 1;         // sub-windows (waves) per window = win_rows / 16
     int tile_k = 16;    // condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16) or 32 (..._16x16x32_f16)

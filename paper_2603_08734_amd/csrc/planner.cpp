@@ -19,7 +19,6 @@ int hardware_threads() {
     return n ? (int)n : 1;
 }
 
-static int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
 
 Geometry make_geometry(int N, int window_rows, int tile_k) {
     Geometry g;
@@ -32,10 +31,14 @@ Geometry make_geometry(int N, int window_rows, int tile_k) {
     // per panel: a gathered row of B then occupies 256 bytes of L2 whatever N is, and measured on
     // the R-MAT case 128 beats both wider panels (N = 512: 2.9 ms against 3.4 at 256 and 4.0 at 512)
     // and narrower ones (N = 128: 0.94 ms at 64 against 0.69).  The tile kernel measures best at 256.
-    g.irr_panel = gcd_int(N, 128);
+    // A width that is not a multiple of the panel ends in a partial panel: the irregular kernel
+    // idles the lanes past the last feature, the tile kernel covers the rest with narrower panels.
+    g.irr_panel = 16;
+    while (g.irr_panel < 128 && g.irr_panel < N) g.irr_panel *= 2;
     g.irr_tpr = g.irr_panel / 8;
     g.irr_teams = 64 / g.irr_tpr;
-    g.tile_panel = gcd_int(N, 256);
+    g.tile_panel = 16;
+    while (g.tile_panel < 256 && g.tile_panel * 2 <= N) g.tile_panel *= 2;   // widest panel of the tile kernel
     g.tile_nch = g.tile_panel / 16;
     return g;
 }

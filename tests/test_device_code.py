@@ -41,8 +41,9 @@ def test_rows_of_c_leave_with_the_streaming_hint(kernels_asm):
     tile = {n: b for n, b in kernels_asm.items() if "rsh_tile_kernel" in n}
     irregular = {n: b for n, b in kernels_asm.items() if "rsh_irregular_kernel" in n}
     combine = {n: b for n, b in kernels_asm.items() if "rsh_combine_kernel" in n}
-    # every kernel exists twice: fp32 sums (OutPlain) and the fused binary16 epilogue (OutFused)
-    assert len(tile) >= 60 and len(irregular) == 8 and len(combine) == 2
+    # every kernel exists twice: fp32 sums (OutPlain) and the fused binary16 epilogue (OutFused);
+    # the irregular kernel once more for a partial last feature panel
+    assert len(tile) >= 60 and len(irregular) == 16 and len(combine) == 2
     for name, body in tile.items():
         n, nt = _stores(body)
         if "OutFused" in name:
@@ -66,7 +67,7 @@ def test_kernels_keep_their_registers(kernels_asm):
         m = re.search(r"\.amdhsa_private_segment_fixed_size\s+(\d+)", body)
         assert m, name
         spill = int(m.group(1))
-        limit = 16 if "rsh_irregular_kernel" in name else 0     # two registers of the 8-wave irregular kernel
+        limit = 24 if "rsh_irregular_kernel" in name else 0     # a few registers of the 8-wave irregular kernel, outside its gather loops
         assert spill <= limit, f"{name} uses {spill} bytes of scratch per lane"
 
 
