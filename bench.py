@@ -21,10 +21,10 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per rsh_spmm call measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE of the
 # dominant kernel, scaled by a copy kernel of known size); filled in from profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    (2, "irregular"): int((3681.3 + 742.3) * 1e6),   # profiles/spmm_rmat_gcn_2e20.md
+    (2, "irregular"): int((3681.7 + 742.3) * 1e6),   # profiles/spmm_rmat_gcn_2e20.md
     (3, "tile"): int((322.7 + 226.5) * 1e6),         # profiles/spmm_stencil27_96.md
-    (4, "tile"): int((1420.7 + 536.9) * 1e6),        # profiles/spmm_hidden_communities_524288.md
-    (5, "tile"): int((255.9 + 117.4) * 1e6),         # profiles/spmm_pruned_llm_28672x8192.md
+    (4, "tile"): int((1420.6 + 536.9) * 1e6),        # profiles/spmm_hidden_communities_524288.md
+    (5, "tile"): int((255.7 + 117.4) * 1e6),         # profiles/spmm_pruned_llm_28672x8192.md
 }
 
 
