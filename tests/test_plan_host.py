@@ -401,3 +401,19 @@ def test_transposed_plan_decodes_to_the_transpose(k):
     assert np.array_equal(col_idx, rows[order].astype(np.int32))
     assert np.array_equal(val, A.val.view(np.uint16)[order])
     assert np.array_equal(np.sort(p.row_order()), np.arange(A.n_cols))
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """The boundary is a C ABI: a C11 program that includes the header, links the library and plans
+    a small matrix on the host must compile without warnings and pass its own checks."""
+    here = os.path.dirname(os.path.abspath(__file__))
+    src = os.path.join(here, "c_abi", "host_plan.c")
+    inc = os.path.join(here, "..", "include")
+    libdir = os.path.dirname(binding._build.LIB)
+    binding.lib()
+    exe = str(tmp_path / "host_plan")
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, src, "-o", exe,
+                           "-L", libdir, "-lrsh", "-Wl,-rpath," + libdir])
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    assert "c abi ok" in res.stdout
