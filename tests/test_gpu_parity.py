@@ -321,7 +321,8 @@ def test_transposed_product(k):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("N,run_width", [(1, 0), (7, 0), (20, 0), (33, 0), (100, 0), (250, 0), (100, 112), (7, 48),
-                                         (48, 0), (48, 48), (96, 96), (112, 0), (112, 112)])
+                                         (48, 0), (48, 48), (96, 96), (112, 0), (112, 112),
+                                         (160, 0), (208, 0), (400, 0), (1000, 0)])       # full panels, then a partial one
 @pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile"])
 def test_feature_widths_that_the_kernels_do_not_run_at(N, run_width, mode):
     """Any width runs at a multiple of 16 (chosen by the planner or given) through the plan's padded
