@@ -156,6 +156,8 @@ FULL_SIZE_CASES = [
     (3, 0, dict(window_rows=64, tile_k=32)),                                          # 64-row windows on 32-column fragments
     (4, 0, dict(reorder=2, window_rows=32, tile_k=16)),                               # tree walk only, two waves per window
     (5, 0, dict(window_rows=16, tile_k=32, max_tiles_per_item=7)),                    # many partial blocks per window
+    (2, 160, dict(reorder=0)),                                                        # a full and a partial panel in the irregular kernel
+    (3, 112, {}),                                                                     # tile panels of 64, 32 and 16 columns
 ]
 
 
