@@ -248,7 +248,7 @@ def test_random_matrices_with_random_options():
             mask[rng.integers(0, n_rows)] = False
         r, c = np.nonzero(mask)
         A = from_coo(r, c, rng.standard_normal(r.size), n_rows, n_cols)
-        N = int(rng.choice([16, 32, 64, 80, 128, 256]))
+        N = int(rng.choice([16, 32, 64, 80, 100, 128, 160, 256]))
         opts = dict(window_rows=int(rng.choice([16, 32, 64])), tile_k=int(rng.choice([16, 32])), partition=int(rng.integers(0, 2)),
                     reorder=int(rng.integers(0, 2)), force_path=int(rng.choice([0, 0, 1, 2])),
                     max_tiles_per_item=int(rng.choice([0, 1, 4])), max_nnz_per_slice=int(rng.choice([0, 20, 70])),
