@@ -5,6 +5,10 @@
 //   rsh_irregular_kernel residual rows (Section 3.3.2, "CUDA path"), teams of lanes own
 //                        feature columns, long rows arrive as bounded slices (Section 3.3.3)
 //   rsh_combine_kernel   fixed-order sum of the partial results of split windows / rows
+//   rsh_widen_rows_kernel / rsh_narrow_rows_kernel   copies to and from the run width for feature
+//                        widths that are not a multiple of 16
+// Each of the first three exists for two outputs: the fp32 sums (OutPlain) and binary16 of
+// act(sum + bias) (OutFused, the GCN layer of Section 4.4).
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
