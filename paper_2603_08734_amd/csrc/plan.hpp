@@ -96,6 +96,11 @@ void parallel_chunks(int64_t n, int threads, F fn);
 template <class F>
 void parallel_dynamic(int64_t n, int threads, int64_t grain, F fn);
 
+// std::sort over `threads` threads: power-of-two many pieces sorted side by side, then merged pairwise.
+// With a strict total order the result is that of std::sort.
+template <class It, class Cmp>
+void parallel_sort(It first, It last, int threads, Cmp cmp);
+
 // Rows longer than this leave for the residual path under the cost-guided partition
 // (rsh_plan_opts_t::long_row_nnz, 0 = max(4 * mean row length, 64)).
 inline int64_t long_row_threshold(const rsh_csr_t& a, const rsh_plan_opts_t& o) {
@@ -128,6 +133,29 @@ void parallel_dynamic(int64_t n, int threads, int64_t grain, F fn) {
             }
         });
     for (auto& th : pool) th.join();
+}
+template <class It, class Cmp>
+void parallel_sort(It first, It last, int threads, Cmp cmp) {
+    const int64_t n = last - first;
+    int parts = 1;
+    while (parts * 2 <= threads && n / (parts * 2) >= 65536) parts *= 2;
+    if (parts == 1) {
+        std::sort(first, last, cmp);
+        return;
+    }
+    std::vector<int64_t> cut((size_t)parts + 1);
+    for (int i = 0; i <= parts; ++i) cut[(size_t)i] = n * i / parts;
+    parallel_chunks(parts, parts, [&](int64_t b, int64_t e, int) {
+        for (int64_t p = b; p < e; ++p) std::sort(first + cut[(size_t)p], first + cut[(size_t)p + 1], cmp);
+    });
+    for (int width = 1; width < parts; width *= 2) {
+        const int pairs = parts / (2 * width);
+        parallel_chunks(pairs, pairs, [&](int64_t b, int64_t e, int) {
+            for (int64_t q = b; q < e; ++q)
+                std::inplace_merge(first + cut[(size_t)(2 * width * q)], first + cut[(size_t)(2 * width * q + width)],
+                                   first + cut[(size_t)(2 * width * (q + 1))], cmp);
+        });
+    }
 }
 template <class F>
 void parallel_chunks(int64_t n, int threads, F fn) {

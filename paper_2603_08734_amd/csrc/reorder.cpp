@@ -212,7 +212,7 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
             if (u < 0) break;
             edges.push_back({nbr_sim[(size_t)r * K + i], std::min((int32_t)r, u), std::max((int32_t)r, u)});
         }
-    std::sort(edges.begin(), edges.end(), [](const Edge& x, const Edge& y) {
+    parallel_sort(edges.begin(), edges.end(), threads, [](const Edge& x, const Edge& y) {
         if (x.sim != y.sim) return x.sim > y.sim;
         if (x.a != y.a) return x.a < y.a;
         return x.b < y.b;
