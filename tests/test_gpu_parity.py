@@ -396,3 +396,32 @@ def test_padded_width_under_graph_replay():
         R, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
         assert_parity(got, R, S, f"graph replay at N = {N}, seed {seed}")
     plan.destroy()
+
+
+@pytest.mark.gpu
+def test_plans_give_their_device_memory_back():
+    """Creating and destroying plans (of widths with and without wide copies) leaves the device's free
+    memory where it was: every array of a plan, its scratch and its wide buffers are released."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, _, _ = make_config(2, small=True)
+    B = {}
+    for N in (64, 100):
+        B[N] = torch.from_numpy(dense_B(A.n_cols, N, "normal", seed=N).view(np.int16)).cuda().view(torch.float16)
+    C = {N: torch.empty((A.n_rows, N), dtype=torch.float32, device="cuda") for N in B}
+
+    def cycle(n):
+        for i in range(n):
+            N = (64, 100)[i % 2]
+            plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, reorder=0, xcd_partition_nnz=32)
+            plan.spmm(B[N], C[N])
+            torch.cuda.synchronize()
+            plan.destroy()
+
+    cycle(4)                                  # warm up allocator pools of the runtime
+    torch.cuda.synchronize()
+    free_before, _ = torch.cuda.mem_get_info()
+    cycle(60)
+    torch.cuda.synchronize()
+    free_after, _ = torch.cuda.mem_get_info()
+    assert free_before - free_after < 32 * 2 ** 20, f"{(free_before - free_after) / 2 ** 20:.1f} MiB not returned"
