@@ -124,11 +124,17 @@ typedef struct {
 int rsh_plan_opts_default(rsh_plan_opts_t *opts);
 
 /*
+ * Planning stage (paper, Section 3.1 overview): locality-aware row reordering (Section 3.4,
+ * Algorithm 3), row-level partitioning into row windows and residual rows (Section 3.3.1,
+ * Algorithm 1), construction of the RS-Tile representation (Section 3.2) and the load-balanced
+ * work lists (Section 3.3.3).
+ *
  * Build a plan for C[n_rows][N] = A * B[n_cols][N].  The plan copies everything
  * it needs; the CSR arrays may be freed after the call.  With opts->upload != 0
  * the device arrays and the plan's private scratch are allocated on the current
  * HIP device.  opts == NULL means defaults.
- * Limits: nnz, n_rows * 1 and n_cols * (2N) must each be below 2^31.
+ * Limits: nnz and n_rows must be below 2^31, n_cols * (2 NR) below 2^32 (NR = the run width,
+ * below); otherwise RSH_ERR_TOO_LARGE.
  * Feature width: the kernels work at multiples of 16, in feature panels of up to 128 columns
  * (irregular kernel; a last partial panel idles lanes) and 256, 128, ... 16 columns (tile kernel;
  * widest first), one pass over the matrix per panel.  When N is not a multiple of 16 (or
@@ -142,8 +148,15 @@ int rsh_plan_opts_default(rsh_plan_opts_t *opts);
 int rsh_plan_create(const rsh_csr_t *csr, int32_t N, const rsh_plan_opts_t *opts, rsh_plan_t **out);
 
 /*
+ * The product itself: C = A x B (paper, Section 2.2) with binary16 operands, fp32 accumulation and
+ * fp32 C (Section 4.1, Problem Configuration), executed by the dense-fragment kernel (Section
+ * 3.3.2, Algorithm 2) and the residual-row kernel (Section 3.3.2, "CUDA path") on disjoint rows
+ * of C (Section 3.1), followed by the fixed-order sum of the partial results of split work items
+ * (Section 3.3.3).
+ *
  * Enqueue C = A * B on hip_stream (a hipStream_t; NULL = default stream) and
- * return without waiting.
+ * return without waiting.  The current HIP device must be the one the plan was created on
+ * (RSH_ERR_BAD_OPTION otherwise).
  *   B_dev : device, binary16 [n_cols][N] row-major, leading dimension N, 16-byte aligned.
  *           Must be finite (padded fragment cells multiply a gathered value by 0).
  *   C_dev : device, fp32 [n_rows][N] row-major, 16-byte aligned; every element is

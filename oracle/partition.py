@@ -23,25 +23,40 @@ def estimate_threshold(n_rows: int, nnz: int) -> tuple[int, int]:
     return max(2, min(6, int(mean // 4))), 2
 
 
-def partition_rows(row_ptr, col_idx, W: int, tau_nnz: int, tau_inc: int):
-    """Returns (window_starts, residual_rows), both ascending lists of row ids."""
+def own_column_counts(row_ptr, col_idx, W: int) -> list[int]:
+    """For every row r: how many of its columns occur in none of the W-1 rows that follow it
+    (rows past the end of the matrix are simply absent).  This is the quantity Algorithm 1 calls
+    the column gain of a head row: the distinct columns of the span [r, r+W) minus the distinct
+    columns of the same span without r, i.e. |S_r \\ (S_{r+1} u ... u S_{r+W-1})|."""
     n = len(row_ptr) - 1
-    cols_of = [set(int(c) for c in col_idx[row_ptr[i]:row_ptr[i + 1]]) for i in range(n)]
+    cols_of = [frozenset(int(c) for c in col_idx[row_ptr[i]:row_ptr[i + 1]]) for i in range(n)]
+    own = []
+    for r in range(n):
+        followers = frozenset().union(*cols_of[r + 1:r + W]) if r + 1 < n and W > 1 else frozenset()
+        own.append(len(cols_of[r] - followers))
+    return own
+
+
+def partition_rows(row_ptr, col_idx, W: int, tau_nnz: int, tau_inc: int):
+    """Returns (window_starts, residual_rows), both ascending lists of row ids.
+
+    Written as a scan over two per-row quantities computed beforehand -- the row length and the
+    row's own-column count (``own_column_counts``) -- which decide, for whichever row the scan
+    finds at the head of a span, whether that row leaves for the residual set (short and gaining
+    fewer than tau_inc columns) or the span of W rows becomes a window."""
+    n = len(row_ptr) - 1
+    length = [int(row_ptr[i + 1] - row_ptr[i]) for i in range(n)]
+    own = own_column_counts(row_ptr, col_idx, W)
+    leaves = [length[r] > 0 and length[r] <= tau_nnz and own[r] < tau_inc for r in range(n)]
     windows, residual = [], []
-    r = 0
-    while r < n:
-        own = cols_of[r]
-        if not own:
-            r += 1
-            continue
-        rest = set()
-        for q in range(r + 1, min(n, r + W)):
-            rest |= cols_of[q]
-        gain = len(rest | own) - len(rest)
-        if gain < tau_inc and len(own) <= tau_nnz:
-            residual.append(r)
-            r += 1
+    head = 0
+    while head < n:
+        if length[head] == 0:
+            head += 1                      # empty rows belong to neither set
+        elif leaves[head]:
+            residual.append(head)
+            head += 1
         else:
-            windows.append(r)
-            r += W
+            windows.append(head)
+            head += W
     return windows, residual

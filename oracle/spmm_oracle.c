@@ -4,8 +4,8 @@
  * Only the tests, the smoke check and the benchmark's "cpu_baseline" leg may
  * call this file.  It shares no code, header, table or helper with the GPU
  * library.  It is deliberately plain: one loop nest that is the textbook
- * definition of the sparse-dense product (paper, Section 2.2: "SpMM computes
- * C = A x B, where A is sparse and B is dense"), with the operand precision of
+ * definition of the sparse-dense product C = A x B, A sparse and B dense (paper,
+ * Section 2.2), with the operand precision of
  * the paper's Problem Configuration (Section 4.1): A and B hold IEEE binary16
  * values.  The paper accumulates in fp32; this oracle widens every operand
  * exactly to fp64 and accumulates in fp64 in stored (CSR) order, so it is

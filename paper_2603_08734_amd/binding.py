@@ -77,10 +77,11 @@ _lib = None
 
 
 def lib() -> ctypes.CDLL:
-    """Load ``librsh.so`` (building it first only if no built library exists)."""
+    """Load ``librsh.so``; it is built first when it is missing or older than one of its sources
+    (and a compiler is there: a box without one runs the library it was given)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        if not os.path.exists(_build.LIB) or (_build.needs_build() and os.path.exists(_build.HIPCC)):
             _build.build(force=True)
         L = ctypes.CDLL(_build.LIB)
         vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)

@@ -1,6 +1,7 @@
 """Build the HIP library in-tree (``librsh.so`` next to this file) for gfx950."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 
@@ -22,17 +23,32 @@ def sources() -> list[str]:
     return [os.path.join(CSRC, s) for s in SOURCES]
 
 
-def needs_build() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+STAMP = LIB + ".sources"   # digest of the sources and flags the library was built from
+
+
+def source_digest() -> str:
+    deps = sources() + sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp"))
     deps.append(os.path.join(HERE, "..", "include", "rsh_spmm.h"))
-    return any(os.path.getmtime(d) > t for d in deps)
+    h = hashlib.sha256(" ".join(FLAGS).encode())
+    for d in deps:
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def needs_build() -> bool:
+    """True when there is no library or it was built from other sources (compared by content, so
+    that a copy of the tree with new file times is not taken for an edit)."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
+        return True
+    with open(STAMP) as f:
+        return f.read().strip() != source_digest()
 
 
 def build(force: bool = True) -> str:
     if force or needs_build():
         cmd = [HIPCC, *FLAGS, "-o", LIB, *sources(), "-lpthread"]
         subprocess.check_call(cmd)
+        with open(STAMP, "w") as f:
+            f.write(source_digest() + "\n")
     return LIB

@@ -222,7 +222,6 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         if (rc) throw rc;
         const double ms_pack = ms_since(t0);
 
-        h.stats.ms_validate = h.stats.ms_validate;
         h.stats.ms_reorder = ms_reorder;
         h.stats.ms_partition = ms_partition;
         h.stats.ms_pack = ms_pack;
@@ -263,8 +262,13 @@ int check_launch(const rsh_plan_t* plan, const void* B, const void* C, const voi
     if (!plan) return RSH_ERR_NULL;
     if (!plan->uploaded) return RSH_ERR_NOT_UPLOADED;
     *padded = plan->dev.n_user != plan->dev.geo.N;
+    // the plan's arrays live on the device that was current when it was created
+    int device = -1;
+    if (!hip_ok(hipGetDevice(&device))) return RSH_ERR_HIP;
+    if (device != plan->device) return RSH_ERR_BAD_OPTION;
     if (plan->host.n_rows == 0) return RSH_OK;
-    if (!C || (!B && plan->host.nnz > 0)) return RSH_ERR_NULL;
+    // B may be absent only when nothing reads it: no stored entry and no copy into the wide buffer
+    if (!C || (!B && (plan->host.nnz > 0 || (*padded && plan->host.n_cols > 0)))) return RSH_ERR_NULL;
     const uintptr_t mb = *padded ? 1u : 15u, mc = *padded ? (uintptr_t)c_elem - 1u : 15u, mbias = *padded ? 3u : 15u;
     if (((uintptr_t)B & mb) || ((uintptr_t)C & mc) || ((uintptr_t)bias & mbias)) return RSH_ERR_BAD_OPTION;
     return RSH_OK;
@@ -432,7 +436,7 @@ const char* rsh_status_string(int status) {
         case RSH_OK: return "ok";
         case RSH_ERR_NULL: return "null pointer argument";
         case RSH_ERR_INVALID_CSR: return "invalid CSR (row_ptr not monotone, or columns unsorted / duplicated / out of range)";
-        case RSH_ERR_UNSUPPORTED_N: return "unsupported N (must be a positive multiple of 16, at most 4096)";
+        case RSH_ERR_UNSUPPORTED_N: return "unsupported N (must be positive and at most 4096)";
         case RSH_ERR_BAD_OPTION: return "option or argument out of range";
         case RSH_ERR_OOM: return "out of memory";
         case RSH_ERR_HIP: return "HIP runtime error";

@@ -112,8 +112,31 @@ inline int64_t long_row_threshold(const rsh_csr_t& a, const rsh_plan_opts_t& o) 
 
 #include <algorithm>
 #include <atomic>
+#include <exception>
+#include <mutex>
 #include <thread>
 namespace rsh {
+// Runs body(t) for t = 0 .. threads-1 on as many threads and joins them.  An exception thrown by a
+// body (std::bad_alloc from a worker's own buffers) is kept and rethrown on the calling thread
+// after the join, so that it reaches the caller's handlers instead of ending the process.
+template <class Body>
+void run_workers(int threads, Body body) {
+    std::exception_ptr first;
+    std::mutex guard;
+    std::vector<std::thread> pool;
+    pool.reserve((size_t)threads);
+    for (int t = 0; t < threads; ++t)
+        pool.emplace_back([&, t]() {
+            try {
+                body(t);
+            } catch (...) {
+                std::lock_guard<std::mutex> lock(guard);
+                if (!first) first = std::current_exception();
+            }
+        });
+    for (auto& th : pool) th.join();
+    if (first) std::rethrow_exception(first);
+}
 template <class F>
 void parallel_dynamic(int64_t n, int threads, int64_t grain, F fn) {
     if (threads <= 1 || n <= grain) {
@@ -122,17 +145,13 @@ void parallel_dynamic(int64_t n, int threads, int64_t grain, F fn) {
     }
     threads = (int)std::min<int64_t>(threads, (n + grain - 1) / grain);
     std::atomic<int64_t> next{0};
-    std::vector<std::thread> pool;
-    pool.reserve(threads);
-    for (int t = 0; t < threads; ++t)
-        pool.emplace_back([&, t]() {
-            for (;;) {
-                const int64_t b = next.fetch_add(grain);
-                if (b >= n) break;
-                fn(b, std::min(n, b + grain), t);
-            }
-        });
-    for (auto& th : pool) th.join();
+    run_workers(threads, [&](int t) {
+        for (;;) {
+            const int64_t b = next.fetch_add(grain);
+            if (b >= n) break;
+            fn(b, std::min(n, b + grain), t);
+        }
+    });
 }
 template <class It, class Cmp>
 void parallel_sort(It first, It last, int threads, Cmp cmp) {
@@ -164,12 +183,6 @@ void parallel_chunks(int64_t n, int threads, F fn) {
         return;
     }
     threads = (int)std::min<int64_t>(threads, n);
-    std::vector<std::thread> pool;
-    pool.reserve(threads);
-    for (int t = 0; t < threads; ++t) {
-        int64_t b = n * t / threads, e = n * (t + 1) / threads;
-        pool.emplace_back([=, &fn]() { fn(b, e, t); });
-    }
-    for (auto& th : pool) th.join();
+    run_workers(threads, [&](int t) { fn(n * t / threads, n * (t + 1) / threads, t); });
 }
 }  // namespace rsh

@@ -376,13 +376,19 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     // meant to lower it; the found order is used only when it lowers the objective by at least
     // 3 % -- a smaller change means the given order was already as coherent (e.g. the natural
     // order of a stencil), and permuting it would only disturb the locality it has.
+    // Summed over pieces of a fixed size, so that the value (and with it the 3 % decision and the
+    // plan) does not depend on the number of threads.
     auto path_cost = [&](const std::vector<int32_t>* ord) {
-        std::vector<double> part((size_t)std::max(1, threads), 0.0);
-        parallel_chunks(n - 1, threads, [&](int64_t b, int64_t e, int t) {
-            double s = 0.0;
-            for (int64_t i = b; i < e; ++i)
-                s += 1.0 - (ord ? sim((*ord)[(size_t)i], (*ord)[(size_t)i + 1]) : sim((int32_t)i, (int32_t)i + 1));
-            part[(size_t)t] = s;
+        constexpr int64_t kPiece = 4096;
+        const int64_t n_pieces = (n - 1 + kPiece - 1) / kPiece;
+        std::vector<double> part((size_t)n_pieces, 0.0);
+        parallel_dynamic(n_pieces, threads, 16, [&](int64_t b, int64_t e, int) {
+            for (int64_t q = b; q < e; ++q) {
+                double s = 0.0;
+                for (int64_t i = q * kPiece; i < std::min(n - 1, (q + 1) * kPiece); ++i)
+                    s += 1.0 - (ord ? sim((*ord)[(size_t)i], (*ord)[(size_t)i + 1]) : sim((int32_t)i, (int32_t)i + 1));
+                part[(size_t)q] = s;
+            }
         });
         double s = 0.0;
         for (double x : part) s += x;

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import partition as opart
-from oracle import rstile
+import plan_reader as rstile
 from paper_2603_08734_amd import Plan, RshError, binding
 from workloads import from_coo, make_config
 
