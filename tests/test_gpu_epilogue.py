@@ -218,3 +218,25 @@ def test_fused_transposed_product(k):
     bound = TOL * S + 2.0 ** -11 * (np.abs(Z) + TOL * S) + 2.0 ** -24
     assert (np.abs(got.astype(np.float64) - Z) <= bound).all(), f"transposed config {k}"
     plan.destroy()
+
+
+@pytest.mark.parametrize("mode", ["all_tile_k16", "all_tile_w64", "all_irregular", "hybrid"])
+@pytest.mark.parametrize("what", ["a_subnormal", "b_subnormal"])
+def test_binary16_subnormal_operands_and_outputs(what, mode):
+    """Subnormal operands through the fused epilogue: with one operand subnormal and the other of
+    unit scale the sums themselves land in and around the binary16 subnormal range, so the one
+    rounding of the epilogue (to nearest even, gradual underflow, no flush) is exercised as well."""
+    from test_gpu_parity import SUBNORMAL_MODES, _mixed_length_matrix, _subnormal_halves
+    from workloads import from_coo
+    rng = np.random.default_rng(77 if what == "a_subnormal" else 78)
+    r, c, lengths = _mixed_length_matrix(rng)
+    N = 64
+    vals = _subnormal_halves(rng, r.size) if what == "a_subnormal" else rng.standard_normal(r.size).astype(np.float16)
+    A = from_coo(r, c, vals, lengths.size, 700)
+    B = _subnormal_halves(rng, 700 * N).reshape(700, N) if what == "b_subnormal" else dense_B(700, N, "normal", seed=9)
+    print(f"case epilogue subnormal what={what} mode={mode}", flush=True)
+    C16, C16b, C32 = run_both(A, B, N, None, False, **SUBNORMAL_MODES[mode])
+    Z, S = oracle_gcn.product_epilogue(A.row_ptr, A.col_idx, A.val, A.n_cols, B, None, False)
+    check(C16, C16b, C32, Z, S, None, False, f"subnormal {what} {mode}")
+    tiny = (np.abs(Z) > 0) & (np.abs(Z) < 2.0 ** -14)
+    assert tiny.any() and (C16[tiny] != 0).any(), "outputs in the subnormal range were flushed"

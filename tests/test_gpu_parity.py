@@ -149,8 +149,38 @@ def test_row_permutation_metamorphic():
     assert_parity(C, C_ref, S, "original rows")
 
 
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_full_size_configs_every_element(k):
+    """The five named workloads at full size under the default plan (what the benchmark times):
+    every element of C against the oracle, block of rows by block of rows, and two runs bit-identical."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, N, dist = make_config(k)
+    B = dense_B(A.n_cols, N, dist, seed=1)
+    print(f"case full-every-element config={k} rows={A.n_rows} nnz={A.nnz} N={N}", flush=True)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N)
+    Bd = torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16)
+    C = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+    plan.spmm(Bd, C)
+    torch.cuda.synchronize()
+    C1 = C.clone()
+    plan.spmm(Bd, C)
+    torch.cuda.synchronize()
+    assert torch.equal(C1.view(torch.int32), C.view(torch.int32)), "two runs differ bitwise"
+    del C1
+    C_host = C.cpu().numpy()
+    worst = 0.0
+    block = max(1, (1 << 24) // N)                       # 16 M outputs per block
+    for b in range(0, A.n_rows, block):
+        rows = np.arange(b, min(A.n_rows, b + block), dtype=np.int64)
+        C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B, rows=rows)
+        worst = max(worst, assert_parity(C_host[b:b + rows.size], C_ref, S, f"full config {k}, rows from {b}"))
+    st = plan.stats()
+    print(f"  max err/S = {worst:.2e} nnz_tile={st['nnz_tile']} nnz_irregular={st['nnz_irregular']}", flush=True)
+    plan.destroy()
+
+
 FULL_SIZE_CASES = [
-    (1, 0, {}), (2, 0, {}), (3, 0, {}), (4, 0, {}), (5, 0, {}),                       # as the benchmark times them
     (2, 0, dict(reorder=0, hub_windows=1, min_reuse=1.5)),                             # hub rows in windows: all three kernels, split windows
     (2, 512, dict(reorder=0)),                                                        # four feature panels in the irregular kernel
     (3, 0, dict(window_rows=64, tile_k=32)),                                          # 64-row windows on 32-column fragments
@@ -163,9 +193,9 @@ FULL_SIZE_CASES = [
 
 @pytest.mark.parametrize("k,features,opts", FULL_SIZE_CASES, ids=lambda v: str(v).replace(" ", ""))
 def test_full_size_configs_on_sampled_rows(k, features, opts):
-    """The five named workloads at full size, in the plan configuration the benchmark times and
-    in a few others that exercise the remaining kernel variants at scale; the oracle recomputes a
-    sample of output rows (random rows, the longest rows, the first and last rows) one by one."""
+    """The named workloads at full size under plan options that exercise the remaining kernel
+    variants at scale (the default plans are compared element by element above); the oracle
+    recomputes a sample of output rows (random rows, the longest rows, the first and last rows)."""
     torch = _torch()
     from paper_2603_08734_amd import Plan
     A, N, dist = make_config(k)
@@ -425,3 +455,160 @@ def test_plans_give_their_device_memory_back():
     torch.cuda.synchronize()
     free_after, _ = torch.cuda.mem_get_info()
     assert free_before - free_after < 32 * 2 ** 20, f"{(free_before - free_after) / 2 ** 20:.1f} MiB not returned"
+
+
+# ---------------------------------------------------------------------------
+# operands the arithmetic could treat specially
+# ---------------------------------------------------------------------------
+def _mixed_length_matrix(rng, n_rows=320, n_cols=700):
+    """Rows of every kind the irregular kernel distinguishes (empty, 1 .. 16 entries, a few dozen,
+    several hundred) in random order; returns COO coordinates."""
+    lengths = np.minimum(rng.choice([0, 1, 2, 3, 5, 8, 13, 16, 17, 40, 100, 200, 500], size=n_rows), n_cols)
+    r = np.repeat(np.arange(n_rows), lengths)
+    c = np.concatenate([np.sort(rng.choice(n_cols, size=int(L), replace=False)) for L in lengths]) if r.size else r
+    return r, c, lengths
+
+
+def _subnormal_halves(rng, n):
+    """n random binary16 subnormals (bit patterns 0x0001 .. 0x03ff, either sign) as float16."""
+    bits = rng.integers(1, 0x400, size=n).astype(np.uint16) | (rng.integers(0, 2, size=n).astype(np.uint16) << 15)
+    return bits.view(np.float16)
+
+
+SUBNORMAL_MODES = {
+    "all_tile_k16": dict(force_path=2, tile_k=16),
+    "all_tile_k32": dict(force_path=2, tile_k=32),
+    "all_tile_w64": dict(force_path=2, window_rows=64, tile_k=32, max_tiles_per_item=3),
+    "all_irregular": dict(force_path=1, xcd_partition_nnz=150, max_nnz_per_slice=96),   # short rows, slices, column-group pieces
+    "hybrid": dict(),
+}
+
+
+@pytest.mark.parametrize("mode", list(SUBNORMAL_MODES))
+@pytest.mark.parametrize("what", ["a_subnormal", "b_subnormal", "both_subnormal", "mixed_rows"])
+@pytest.mark.parametrize("N", [32, 128])
+def test_binary16_subnormal_operands(what, mode, N):
+    """Binary16 subnormals are ordinary operands (Section 4.1 fixes binary16 inputs and says nothing
+    of flushing): matrices whose stored values are all subnormal, a B that is all subnormal, both at
+    once, and rows that mix subnormal and normal values, through the matrix-core path (both fragment
+    widths), the lane-team path (short rows, slices, column-group pieces) and the default routing."""
+    import zlib
+    rng = np.random.default_rng(zlib.crc32(f"{what}-{N}".encode()))
+    r, c, lengths = _mixed_length_matrix(rng)
+    n_rows, n_cols = lengths.size, 700
+    if what in ("a_subnormal", "both_subnormal"):
+        vals = _subnormal_halves(rng, r.size)
+    elif what == "mixed_rows":
+        vals = rng.standard_normal(r.size).astype(np.float16)
+        sub = rng.random(r.size) < 0.5
+        vals[sub] = _subnormal_halves(rng, int(sub.sum()))
+        whole = np.isin(r, rng.choice(n_rows, size=n_rows // 4, replace=False))      # a quarter of the rows: subnormal only
+        vals[whole] = _subnormal_halves(rng, int(whole.sum()))
+    else:
+        vals = rng.standard_normal(r.size).astype(np.float16)
+    A = from_coo(r, c, vals, n_rows, n_cols)
+    if what in ("b_subnormal", "both_subnormal"):
+        B = _subnormal_halves(rng, n_cols * N).reshape(n_cols, N)
+    else:
+        B = dense_B(n_cols, N, "normal", seed=N)
+    print(f"case subnormal what={what} mode={mode} N={N} nnz={A.nnz}", flush=True)
+    (C,), st = gpu_spmm(A, B, N, **SUBNORMAL_MODES[mode])
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    assert S.max() > 0
+    assert_parity(C, C_ref, S, f"subnormal {what} {mode}")
+    # nothing was flushed: where a single stored entry makes the output, the product is exact
+    single = np.flatnonzero(lengths == 1)
+    if single.size:
+        assert np.array_equal(C[single].astype(np.float64), C_ref[single])
+
+
+@pytest.mark.parametrize("mode", ["all_tile", "k32_all_tile", "w64_all_tile", "all_irregular", "hybrid"])
+def test_stored_zeros(mode):
+    """Stored explicit zeros (+0 and -0 bit patterns) stay entries of the plan and contribute nothing:
+    a row whose stored values are all zero, and an element whose terms all vanish, must come out as
+    exactly 0 (S = 0), also through the bitmap fragments, where a stored zero has a set bit."""
+    rng = np.random.default_rng(11)
+    r, c, lengths = _mixed_length_matrix(rng, n_rows=200, n_cols=300)
+    vals = rng.standard_normal(r.size).astype(np.float16)
+    zero = rng.random(r.size) < 0.3
+    vals[zero] = np.where(rng.random(int(zero.sum())) < 0.5, np.float16(0.0), np.float16(-0.0))
+    zero_rows = np.flatnonzero(lengths > 0)[::7]
+    vals[np.isin(r, zero_rows)] = np.float16(0.0)
+    A = from_coo(r, c, vals, lengths.size, 300)
+    N = 64
+    B = dense_B(300, N, "normal", seed=5)
+    B[::3] = 0                                              # zero rows of B too: more elements with S = 0
+    print(f"case stored-zeros mode={mode} nnz={A.nnz} zeros={int((A.val == 0).sum())}", flush=True)
+    (C,), st = gpu_spmm(A, B, N, **OPTION_SETS[mode])
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    assert (S == 0).any() and (S > 0).any()
+    assert_parity(C, C_ref, S, f"stored zeros {mode}")
+    assert np.all(C[zero_rows] == 0)
+    from paper_2603_08734_amd import Plan
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, upload=0, **OPTION_SETS[mode])
+    rp, ci, v, _ = plan.decode()
+    assert np.array_equal(v, A.val.view(np.uint16)) and np.array_equal(ci, A.col_idx)     # zeros (and their signs) are kept
+    plan.destroy()
+
+
+@pytest.mark.parametrize("mode", ["all_tile", "all_irregular", "hybrid"])
+def test_b_byte_offsets_above_2_31(mode):
+    """The kernels address a row of B as a 32-bit byte offset from a 64-bit base.  With 2^21 - 1
+    columns and N = 1024 (2048-byte rows) the offsets of the upper half of B lie in [2^31, 2^32):
+    rows that name the first column, columns on both sides of offset 2^31 and the very last column
+    must read the right rows of a 4.3 GB B.  The oracle gets the referenced rows of B only."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    n_cols, N = (1 << 21) - 1, 1024
+    rng = np.random.default_rng(31)
+    half = 1 << 20                                          # first column whose byte offset reaches 2^31
+    special = np.array([0, 1, half - 1, half, half + 1, n_cols - 2, n_cols - 1])
+    rows, cols = [], []
+    for i in range(48):                                     # short rows: a few special columns + random ones
+        cs = np.unique(np.concatenate([rng.choice(special, size=3), rng.integers(0, n_cols, size=int(rng.integers(1, 14)))]))
+        rows.append(np.full(cs.size, i)); cols.append(cs)
+    for i, L in ((48, 60), (49, 200), (50, 700)):           # a row cut into team pieces, into slices, by column group
+        cs = np.unique(np.concatenate([special, rng.integers(half, n_cols, size=L)]))
+        rows.append(np.full(cs.size, i)); cols.append(cs)
+    for i in range(51, 67):                                 # sixteen rows over one set of upper-half columns: a window with reuse
+        shared = half + 4096 * np.arange(40)
+        cs = np.unique(np.concatenate([shared[rng.random(40) < 0.7], [n_cols - 1]]))
+        rows.append(np.full(cs.size, i)); cols.append(cs)
+    r, c = np.concatenate(rows), np.concatenate(cols)
+    A = from_coo(r, c, rng.standard_normal(r.size), 67, n_cols)
+    print(f"case big-offsets mode={mode} nnz={A.nnz}", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(31)
+    Bd = torch.randn((n_cols, N), device="cuda", dtype=torch.float16, generator=g)
+    opts = dict(OPTION_SETS[mode])
+    if mode == "all_irregular":
+        opts.update(xcd_partition_nnz=256, max_nnz_per_slice=128)
+    plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, **opts)
+    C = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+    plan.spmm(Bd, C)
+    torch.cuda.synchronize()
+    used = np.unique(A.col_idx)
+    B_used = Bd[torch.from_numpy(used.astype(np.int64)).cuda()].cpu().numpy()
+    compact = np.searchsorted(used, A.col_idx).astype(np.int32)                       # order-preserving renumbering
+    C_ref, S, _ = oracle.spmm(A.row_ptr, compact, A.val, B_used)
+    assert_parity(C.cpu().numpy(), C_ref, S, f"big offsets {mode}")
+    plan.destroy()
+    del Bd
+
+
+def test_null_b_is_refused_when_the_wide_copy_would_read_it():
+    """A matrix without stored entries needs no B -- unless the plan runs at another width than N,
+    where B is first copied into the plan's wide buffer: then a NULL B is an error, not a fault."""
+    import ctypes
+    torch = _torch()
+    from paper_2603_08734_amd import Plan, binding
+    A = from_coo([], [], [], 40, 40)
+    L = binding.lib()
+    vp = ctypes.c_void_p
+    for N, want in ((32, binding.RSH_OK), (20, binding.RSH_ERR_NULL)):
+        plan = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N)
+        C = torch.full((40, N), float("nan"), dtype=torch.float32, device="cuda")
+        assert L.rsh_spmm(plan._h, None, vp(C.data_ptr()), None) == want
+        torch.cuda.synchronize()
+        if want == binding.RSH_OK:
+            assert torch.all(C == 0)
+        plan.destroy()
