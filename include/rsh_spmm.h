@@ -37,7 +37,8 @@ enum {
     RSH_ERR_OOM = 5,           /* host or device allocation failed                              */
     RSH_ERR_HIP = 6,           /* a HIP runtime call failed (see rsh_last_hip_error)            */
     RSH_ERR_NOT_UPLOADED = 7,  /* rsh_spmm on a plan created with upload == 0                   */
-    RSH_ERR_TOO_LARGE = 8      /* a 32-bit plan index would overflow (see rsh_plan_create)      */
+    RSH_ERR_TOO_LARGE = 8      /* a 32-bit plan index would overflow (rsh_plan_create), or the plan
+                                  needs more than the library-owned scratch (rsh_spmm_noalloc)  */
 };
 
 typedef struct rsh_plan rsh_plan_t; /* opaque */
@@ -167,6 +168,24 @@ int rsh_plan_create(const rsh_csr_t *csr, int32_t N, const rsh_plan_opts_t *opts
  * from run to run: no atomics are used.
  */
 int rsh_spmm(const rsh_plan_t *plan, const void *B_dev, void *C_dev, void *hip_stream);
+
+/*
+ * rsh_spmm for callers that cannot allocate device memory or have it allocated on their behalf:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels, same results bit for bit, same arguments and errors as rsh_spmm; the one difference is
+ * where the partial sums of split work items live: not in the plan's own scratch buffer but in an
+ * array that is part of the library's device code, RSH_STATIC_SCRATCH_BYTES (64 MiB) per GPU,
+ * held from the moment the library is loaded on a device until the process ends.  The call makes
+ * no hipMalloc / hipFree and uses no allocating routine; its first call on a device looks up the
+ * array's address (hipGetSymbolAddress).  A plan whose partial sums need more (n_scratch_slots *
+ * run width * 4 bytes, see rsh_plan_stats) is refused with RSH_ERR_TOO_LARGE and
+ * rsh_last_hip_error() says how much it needs.  The array is shared by every plan on that GPU and
+ * keeps the last call's contents (each call overwrites what it later reads, nothing has to start
+ * at zero): two rsh_spmm_noalloc calls that overlap in time on one GPU race, whatever their plans
+ * and streams.
+ */
+#define RSH_STATIC_SCRATCH_BYTES (64u << 20)
+int rsh_spmm_noalloc(const rsh_plan_t *plan, const void *B_dev, void *C_dev, void *hip_stream);
 
 /*
  * The product with the epilogue of a GCN layer fused into the kernels that finish a row

@@ -30,7 +30,7 @@ _ARRAY_DTYPES = {
 }
 
 EXPORTED_SYMBOLS = [
-    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_f16", "rsh_spmm_profile", "rsh_copy_probe", "rsh_plan_destroy", "rsh_plan_stats",
+    "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_noalloc", "rsh_spmm_f16", "rsh_spmm_profile", "rsh_copy_probe", "rsh_plan_destroy", "rsh_plan_stats",
     "rsh_plan_decode", "rsh_plan_row_order", "rsh_plan_array", "rsh_plan_teams_per_wave",
     "rsh_struct_sizes", "rsh_status_string", "rsh_last_hip_error",
 ]
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.rsh_plan_create.argtypes = [ctypes.POINTER(rsh_csr_t), i32, ctypes.POINTER(rsh_plan_opts_t),
                                       ctypes.POINTER(vp)]
         L.rsh_spmm.argtypes = [vp, vp, vp, vp]
+        L.rsh_spmm_noalloc.argtypes = [vp, vp, vp, vp]
         L.rsh_spmm_f16.argtypes = [vp, vp, vp, vp, i32, vp]
         L.rsh_spmm_profile.argtypes = [vp, vp, vp, vp, ctypes.POINTER(rsh_kernel_times_t)]
         L.rsh_copy_probe.argtypes = [vp, vp, ctypes.c_int64, vp]
@@ -118,7 +119,7 @@ class RshError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
         msg = lib().rsh_status_string(status).decode()
-        if status == RSH_ERR_HIP:
+        if status in (RSH_ERR_HIP, RSH_ERR_TOO_LARGE) and lib().rsh_last_hip_error():
             msg += ": " + lib().rsh_last_hip_error().decode()
         super().__init__(f"rsh status {status}: {msg}")
 
@@ -178,6 +179,14 @@ class Plan:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
         _check(lib().rsh_spmm(self._h, ctypes.c_void_p(b_ptr), ctypes.c_void_p(c_ptr), ctypes.c_void_p(stream)))
+
+    def spmm_noalloc(self, B, C, stream=None) -> None:
+        """Enqueue C = A @ B with the partial sums in the library-owned array (rsh_spmm_noalloc)."""
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        _check(lib().rsh_spmm_noalloc(self._h, ctypes.c_void_p(B.data_ptr()), ctypes.c_void_p(C.data_ptr()),
+                                      ctypes.c_void_p(stream)))
 
     def spmm_f16(self, B, C16, bias=None, relu: bool = False, stream=None) -> None:
         """Enqueue C16 = binary16(act(A @ B + bias)) (rsh_spmm_f16); bias: fp32 device tensor [N] or None."""

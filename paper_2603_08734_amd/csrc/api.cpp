@@ -299,6 +299,33 @@ int rsh_spmm(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_s
     return rc;
 }
 
+int rsh_spmm_noalloc(const rsh_plan_t* plan, const void* B_dev, void* C_dev, void* hip_stream) {
+    bool padded = false;
+    int rc = check_launch(plan, B_dev, C_dev, nullptr, 4, &padded);
+    if (rc != RSH_OK || plan->host.n_rows == 0) return rc;
+    const size_t need = (size_t)plan->host.n_scratch_slots * (size_t)plan->host.geo.N * sizeof(float);
+    if (need > rsh::kStaticScratchBytes) {
+        g_hip_error = "the plan's partial sums need " + std::to_string(need) + " bytes, the library-owned array holds " +
+                      std::to_string(rsh::kStaticScratchBytes);
+        return RSH_ERR_TOO_LARGE;
+    }
+    rsh::DevicePlan d = plan->dev;   // same arrays, partial sums in the library's array instead of the plan's
+    rc = rsh::static_scratch(&d.scratch);
+    if (rc != RSH_OK) {
+        g_hip_error = "hipGetSymbolAddress failed for the library-owned scratch array";
+        return rc;
+    }
+    if (!padded) {
+        rc = rsh::launch_spmm(d, B_dev, C_dev, hip_stream, nullptr);
+    } else {
+        rc = widen_operands(d, plan->host.n_cols, B_dev, nullptr, hip_stream);
+        if (rc == RSH_OK) rc = rsh::launch_spmm(d, d.b_pad, d.c_pad, hip_stream, nullptr);
+        if (rc == RSH_OK) rc = rsh::launch_narrow_rows(d.c_pad, C_dev, plan->host.n_rows, d.n_user, d.geo.N, 4, hip_stream);
+    }
+    if (rc == RSH_ERR_HIP) g_hip_error = "kernel launch failed";
+    return rc;
+}
+
 int rsh_spmm_f16(const rsh_plan_t* plan, const void* B_dev, void* C16_dev, const float* bias_dev, int32_t relu,
                  void* hip_stream) {
     if (relu != 0 && relu != 1) return plan ? RSH_ERR_BAD_OPTION : RSH_ERR_NULL;
@@ -441,7 +468,7 @@ const char* rsh_status_string(int status) {
         case RSH_ERR_OOM: return "out of memory";
         case RSH_ERR_HIP: return "HIP runtime error";
         case RSH_ERR_NOT_UPLOADED: return "plan was created host-only (upload == 0)";
-        case RSH_ERR_TOO_LARGE: return "matrix too large for 32-bit plan indices";
+        case RSH_ERR_TOO_LARGE: return "too large: a 32-bit plan index would overflow, or the plan's partial sums exceed the library-owned array (rsh_spmm_noalloc)";
         default: return "unknown status";
     }
 }

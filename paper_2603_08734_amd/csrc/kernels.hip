@@ -13,6 +13,7 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "launch.hpp"
@@ -907,6 +908,32 @@ static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* 
 
 int launch_spmm(const DevicePlan& d, const void* B, void* C, void* stream, void* const* events) {
     return launch_all(d, B, OutPlain{(float*)C}, stream, events);
+}
+
+// ---------------------------------------------------------------------------
+// Library-owned partial-sum space for callers that must not allocate: one array per GPU, part of
+// the loaded code object, held until the process ends.  In host code the array's name is only a
+// handle; its device address is looked up once per device and that address is what kernels get.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char g_scratch[kStaticScratchBytes];
+
+int static_scratch(float** ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void* address[kMaxDevices] = {};
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return RSH_ERR_HIP;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!address[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return RSH_ERR_HIP;
+        }
+        address[device] = p;
+    }
+    *ptr = static_cast<float*>(address[device]);
+    return RSH_OK;
 }
 
 int launch_spmm_f16(const DevicePlan& d, const void* B, void* C16, const float* bias, int relu, void* stream, void* const* events) {

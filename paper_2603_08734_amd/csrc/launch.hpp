@@ -37,6 +37,11 @@ struct DevicePlan {
 // after each of the three kernels.
 int launch_spmm(const DevicePlan& d, const void* B_dev, void* C_dev, void* stream, void* const* events);
 
+// Bytes of the library-owned partial-sum array that every GPU holds for rsh_spmm_noalloc, and its
+// address on the current device (looked up on the first call per device; allocates nothing).
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+int static_scratch(float** ptr);
+
 // Same kernels with the fused epilogue: C16 (binary16, n_rows x N) = act(A B + bias); bias is a
 // device array of N floats or null, relu != 0 selects max(x, 0).
 int launch_spmm_f16(const DevicePlan& d, const void* B_dev, void* C16_dev, const float* bias_dev, int relu,
