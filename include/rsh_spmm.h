@@ -53,13 +53,17 @@ typedef struct {
 
 /* Planning options.  Obtain defaults with rsh_plan_opts_default, then override. */
 typedef struct {
-    int32_t window_rows;  /* W of Algorithm 1: 16, 32 or 64.  A window is W/16 sub-windows of 16 rows (one
-                             MFMA N-extent each) that share one condensed column space; the W/16 waves
-                             of a workgroup share each staged B tile.  0 (default) = choose: starting
-                             from 16, W doubles while merging neighbouring windows (a sample of them)
-                             keeps the merged windows' distinct columns within 0.6 of the sum        */
+    int32_t window_rows;  /* W of Algorithm 1: 16, 32, 64 or 128.  Up to 64 a window is W/16 sub-windows of 16
+                             rows (one MFMA N-extent each) that share one condensed column space; the W/16
+                             waves of a workgroup share each staged B tile.  128 selects the panel form for
+                             tall windows (four row groups of 32 rows on v_mfma_f32_32x32x16_f16, entries
+                             stored with their cell address instead of a bitmap; see rsh_plan_array).
+                             0 (default) = choose: starting from 16, W doubles while merging neighbouring
+                             windows (a sample of them) keeps the merged windows' distinct columns within
+                             0.6 of the sum                                                           */
     int32_t tile_k;       /* K, condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16) or 32
-                             (v_mfma_f32_16x16x32_f16); 0 (default) = 16 for 16-row windows, else 32 */
+                             (v_mfma_f32_16x16x32_f16); 0 (default) = 16 for 16-row windows, else 32;
+                             128-row windows always take 32 (two K steps of v_mfma_f32_32x32x16_f16)  */
     int32_t tau_nnz;      /* Algorithm 1 row-length threshold; -1 = estimate from the matrix     */
     int32_t tau_inc;      /* Algorithm 1 column-gain threshold; -1 = estimate                    */
     int32_t partition;    /* 0 = Algorithm 1 exactly as printed (contiguous windows, head-row test);
@@ -258,6 +262,20 @@ int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
  *   RSH_ARR_TILE_ITEM    uint32 [n_items*4]     {window, first tile, end tile, dst}: dst ==
  *                                               0xffffffff -> rows of C; else first scratch slot
  *                                               of a W-slot partial block
+ * Panel form of the dense-fragment part (window_rows == 128; TILE_MASK, TILE_VAL_OFF and TILE_VAL are
+ * then empty).  A window is four row groups of 32 rows; a fragment is 32 condensed columns = two K
+ * steps of 16; the entries of (row group g, fragment t, K step h) form one unit, the 32 x 16 operand
+ * of one v_mfma_f32_32x32x16_f16.  With t0 = WIN_TILE_OFF[w] and nt the window's fragment count, the
+ * unit has index 8*t0 + (g*nt + (t - t0))*2 + h, so that the units of one row group are consecutive:
+ *   RSH_ARR_PANEL_COL0   int32  [n_windows]     first column of a window whose condensed columns are
+ *                                               one run of consecutive columns filling whole
+ *                                               fragments (column ids are then computed), else -1
+ *   RSH_ARR_PANEL_OFF    uint32 [8*n_tiles+1]   start of each unit's entries in PANEL_ENT
+ *   RSH_ARR_PANEL_ENT    uint32 []              one word per stored entry: bits 0..15 the binary16
+ *                                               value, bits 16..31 the byte address of its cell in
+ *                                               the operand as the instruction holds it:
+ *                                               ((r + 32*(k/8))*8 + k%8)*2 for row r of the group and
+ *                                               column k (0..15) of the K step; ascending in a unit
  * Irregular part (RS-Tile "residual part", Section 3.2):
  *   RSH_ARR_IRR_COL      int32  []              column ids, CSR order inside a row
  *   RSH_ARR_IRR_VAL      uint16 []              binary16 values, same order
@@ -282,7 +300,8 @@ int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
 enum {
     RSH_ARR_WIN_ROW = 0, RSH_ARR_WIN_TILE_OFF, RSH_ARR_TILE_COLID, RSH_ARR_TILE_MASK,
     RSH_ARR_TILE_VAL_OFF, RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL,
-    RSH_ARR_IRR_WAVE, RSH_ARR_IRR_ROW, RSH_ARR_COMBINE, RSH_ARR_TILE_XCD, RSH_ARR_IRR_XCD, RSH_ARR_COUNT
+    RSH_ARR_IRR_WAVE, RSH_ARR_IRR_ROW, RSH_ARR_COMBINE, RSH_ARR_TILE_XCD, RSH_ARR_IRR_XCD,
+    RSH_ARR_PANEL_COL0, RSH_ARR_PANEL_OFF, RSH_ARR_PANEL_ENT, RSH_ARR_COUNT
 };
 int rsh_plan_array(const rsh_plan_t *plan, int32_t which, const void **ptr, int64_t *count);
 

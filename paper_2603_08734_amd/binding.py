@@ -19,7 +19,8 @@ RSH_OK = 0
 
 (RSH_ARR_WIN_ROW, RSH_ARR_WIN_TILE_OFF, RSH_ARR_TILE_COLID, RSH_ARR_TILE_MASK, RSH_ARR_TILE_VAL_OFF,
  RSH_ARR_TILE_VAL, RSH_ARR_TILE_ITEM, RSH_ARR_IRR_COL, RSH_ARR_IRR_VAL, RSH_ARR_IRR_WAVE, RSH_ARR_IRR_ROW,
- RSH_ARR_COMBINE, RSH_ARR_TILE_XCD, RSH_ARR_IRR_XCD, RSH_ARR_COUNT) = range(15)
+ RSH_ARR_COMBINE, RSH_ARR_TILE_XCD, RSH_ARR_IRR_XCD, RSH_ARR_PANEL_COL0, RSH_ARR_PANEL_OFF, RSH_ARR_PANEL_ENT,
+ RSH_ARR_COUNT) = range(18)
 
 _ARRAY_DTYPES = {
     RSH_ARR_WIN_ROW: np.int32, RSH_ARR_WIN_TILE_OFF: np.uint32, RSH_ARR_TILE_COLID: np.int32,
@@ -27,6 +28,7 @@ _ARRAY_DTYPES = {
     RSH_ARR_TILE_ITEM: np.uint32, RSH_ARR_IRR_COL: np.int32, RSH_ARR_IRR_VAL: np.uint16,
     RSH_ARR_IRR_WAVE: np.uint32, RSH_ARR_IRR_ROW: np.int32, RSH_ARR_COMBINE: np.uint32,
     RSH_ARR_TILE_XCD: np.uint32, RSH_ARR_IRR_XCD: np.uint32,
+    RSH_ARR_PANEL_COL0: np.int32, RSH_ARR_PANEL_OFF: np.uint32, RSH_ARR_PANEL_ENT: np.uint32,
 }
 
 EXPORTED_SYMBOLS = [

@@ -666,6 +666,276 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 }
 
 // ---------------------------------------------------------------------------
+// Tall windows: the panel kernel.  Where many rows name the same columns (a pruned weight matrix:
+// every window covers nearly all columns) the dense-fragment path is bound by its own instructions,
+// not by memory, so this form spends as few as possible per multiply-add:
+//   * a window is 128 rows, one workgroup of four waves, each wave owning a row group of 32 rows and
+//     the whole feature panel (up to 128 features) on v_mfma_f32_32x32x16_f16 -- per transposing LDS
+//     read of B and per expanded cell of A twice the multiply-adds of the 16 x 16 shapes;
+//   * a fragment's 32 B rows are staged in LDS once per workgroup, double-buffered, one barrier per
+//     fragment; rows in flight sit in registers two fragments ahead;
+//   * the stored entries of a 32 x 16 unit carry the byte address of their cell in the MFMA operand,
+//     so the wave scatters them into a zeroed 1 KB LDS tile of its own (work proportional to the
+//     entries) and reads the operand back with one 16-byte read per lane, where the bitmap form
+//     expands cell by cell; a wave's entries are one contiguous stream, fetched three fragments ahead;
+//   * sums are kept in two levels (every 1024 condensed columns the running sums are added to a
+//     second set and cleared), which bounds the fp32 accumulation chain whatever the item length, so
+//     windows are cut into few, long items and few partial sums cross HBM.
+// The product is formed transposed as in the fragment kernel: features along M (operand A, from the
+// staged B rows through the transposing read), window rows along N (operand B, the expanded piece
+// of the sparse matrix).
+//
+// v_mfma_f32_32x32x16_f16 operand layout (lane l, j = 0..7, v = 0..15):
+//   A[m = l%32][k = 8*(l/32)+j]   B[k = 8*(l/32)+j][n = l%32]   D[m = 8*(v/4) + 4*(l/32) + v%4][n = l%32]
+// ---------------------------------------------------------------------------
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+template <int NCH32>
+struct PanelGeom {
+    static constexpr int P = 32 * NCH32;                      // features per panel
+    static constexpr int TPR = P / 8;                         // 16-byte pieces per staged B row
+    static constexpr int LDB = P >= 64 ? P + 32 : 32;         // LDS row stride in halves: rows 16 banks apart (mod 64)
+    static constexpr int PIECES = kPanelK * TPR;              // pieces of one staged tile
+    static constexpr int NLD = (PIECES + 255) / 256;          // pieces per thread
+    static constexpr int TILE_HALVES = kPanelK * LDB;
+    static constexpr int LOOP_BYTES = 2 * TILE_HALVES * 2 + kPanelGroups * 2 * 512 * 2;   // two B tiles + the waves' operand tiles
+    static constexpr int STAGE_STRIDE = 36;                   // floats per staged output row (32 + pad)
+    static constexpr int STAGE_BYTES = kPanelGroups * 32 * STAGE_STRIDE * 4;
+    static constexpr int SMEM_BYTES = LOOP_BYTES > STAGE_BYTES ? LOOP_BYTES : STAGE_BYTES;
+};
+
+__device__ __forceinline__ void panel_store(const OutPlain& o, size_t row, int N, int f, float4_t v) {
+    store_c_streaming(o.C + row * N + f, v);
+}
+__device__ __forceinline__ void panel_store(const OutFused& o, size_t row, int N, int f, float4_t v) {
+    __builtin_nontemporal_store(finish4(o, f, v), reinterpret_cast<uint2_t*>(o.C + row * N + f));
+}
+
+// R = rounds of 64 entries a unit may need (a plan-wide bound: 2, 4 or 8)
+template <int NCH32, int R, class OUT>
+__global__ __launch_bounds__(256) void rsh_panel_kernel(
+    const uint4* __restrict__ items, XcdSplit xs, const int32_t* __restrict__ win_row,
+    const uint32_t* __restrict__ win_tile_off, const int32_t* __restrict__ win_col0,
+    const int32_t* __restrict__ tile_colid, const uint32_t* __restrict__ unit_off,
+    const uint32_t* __restrict__ ent, const __half* __restrict__ B, const OUT out,
+    float* __restrict__ scratch, int N, int feature0) {
+    using Gm = PanelGeom<NCH32>;
+    constexpr int P = Gm::P, TPR = Gm::TPR, LDB = Gm::LDB, NLD = Gm::NLD, KT = kPanelK;
+    constexpr int LB = 2;    // fragments ahead at which B rows are requested
+    constexpr int LA = 3;    // fragments ahead at which a wave's entries are requested
+    __shared__ __attribute__((aligned(16))) unsigned char smem[Gm::SMEM_BYTES];
+    _Float16* const lds_b = reinterpret_cast<_Float16*>(smem);                                  // [2][KT * LDB]
+    _Float16* const lds_a = reinterpret_cast<_Float16*>(smem + 2 * Gm::TILE_HALVES * 2);        // [4 waves][2 K steps][512]
+
+    const int lane = threadIdx.x & 63;
+    const int g = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // row group of this wave
+    uint32_t item;
+    {
+        const uint32_t x = blockIdx.x & 7u;
+        const uint32_t i = xs.start[x] + (blockIdx.x >> 3);
+        item = __builtin_amdgcn_readfirstlane(i);
+        if (i >= xs.start[x + 1]) return;   // uniform per block
+    }
+    const uint4 it = items[item];
+    const uint32_t win = __builtin_amdgcn_readfirstlane(it.x), t_begin = __builtin_amdgcn_readfirstlane(it.y);
+    const uint32_t t_end = __builtin_amdgcn_readfirstlane(it.z), dst = __builtin_amdgcn_readfirstlane(it.w);
+    const uint32_t t0 = win_tile_off[win], nt = win_tile_off[win + 1] - t0;
+    const int32_t col0 = win_col0[win];
+    const uint32_t steps = t_end - t_begin;
+    const int panel = feature0 + blockIdx.y * P;
+    const int row = win_row[(size_t)win * kPanelRows + g * 32 + (lane & 31)];   // lane n (and n + 32) <-> row n of the group
+
+    float16_t acc[NCH32], acc2[NCH32];
+#pragma unroll
+    for (int c = 0; c < NCH32; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = acc2[c][v] = 0.f;
+
+    if (steps > 0) {
+        const uint32_t last = steps - 1;
+        // ---- staging of B rows: thread tix takes 16-byte piece j*256 + tix of the KT x TPR pieces ----
+        const int tix = threadIdx.x;
+        int ld_row[NLD];
+        uint32_t ld_lds[NLD], ld_byte[NLD];
+        bool ld_on[NLD];
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int piece = j * 256 + tix;
+            ld_row[j] = (piece / TPR) & (KT - 1);
+            const int cp = piece % TPR;
+            ld_on[j] = piece < Gm::PIECES;
+            ld_lds[j] = (uint32_t)(ld_row[j] * LDB + cp * 8);
+            // a piece past the last feature (partial last panel) reads the panel's first piece; its
+            // products land in features that are never stored
+            ld_byte[j] = panel + 8 * cp < N ? 16u * (uint32_t)cp : 0u;
+        }
+        const char* Bbytes = reinterpret_cast<const char*>(B + panel);
+        const uint32_t row_bytes = 2u * (uint32_t)N;
+        const bool run = col0 >= 0;                                   // columns are col0, col0 + 1, ...: no ids to fetch
+        auto column_of = [&](uint32_t step, int j, int fetched) -> uint32_t {
+            return run ? (uint32_t)col0 + (t_begin - t0 + step) * KT + (uint32_t)ld_row[j] : (uint32_t)fetched;
+        };
+        auto fetch_colid = [&](uint32_t step, int j) -> int {
+            return run ? 0 : tile_colid[(size_t)(t_begin + min(step, last)) * KT + ld_row[j]];
+        };
+        // ---- this wave's entry stream ----
+        const uint32_t unit0 = 8u * t0 + ((uint32_t)g * nt + (t_begin - t0)) * 2u;
+        _Float16* const my_a = lds_a + g * 1024;
+        const int g4 = lane >> 4, rr4 = (lane & 15) >> 2, ss4 = lane & 3;
+        const int tr_off = (8 * (g4 >> 1) + rr4) * LDB + 16 * (g4 & 1) + 4 * ss4;
+
+        uint4_t breg[4][NLD];
+        uint32_t areg[4][2][R];
+        uint32_t cnt_ring[4][2];
+        int cid_n[NLD];
+        uint32_t off_n[3];
+
+        auto load_offsets = [&](uint32_t step, uint32_t (&o)[3]) {
+            const uint32_t* p = unit_off + unit0 + 2u * min(step, last);
+            o[0] = p[0];
+            o[1] = p[1];
+            o[2] = p[2];
+        };
+        auto issue_entries = [&](uint32_t step, const uint32_t (&o)[3], uint32_t (&a)[2][R], uint32_t (&cnt)[2]) {
+            const bool live = step < steps;
+            cnt[0] = live ? o[1] - o[0] : 0u;
+            cnt[1] = live ? o[2] - o[1] : 0u;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int q = 0; q < R; ++q) a[h][q] = ent[o[h] + (uint32_t)(64 * q + lane)];   // unconditional: the stream is padded
+        };
+        auto issue_b = [&](uint32_t step, const int (&cid)[NLD], uint4_t (&b)[NLD]) {
+            const uint32_t sc = min(step, last);
+#pragma unroll
+            for (int j = 0; j < NLD; ++j)
+                b[j] = *reinterpret_cast<const uint4_t*>(Bbytes + (column_of(sc, j, cid[j]) * row_bytes + ld_byte[j]));
+        };
+        auto stage_b = [&](const uint4_t (&b)[NLD], int buf) {
+            _Float16* sb = lds_b + buf * Gm::TILE_HALVES;
+#pragma unroll
+            for (int j = 0; j < NLD; ++j)
+                if (ld_on[j]) *reinterpret_cast<uint4_t*>(sb + ld_lds[j]) = b[j];
+        };
+        auto scatter = [&](const uint32_t (&a)[2][R], const uint32_t (&cnt)[2]) {
+            *reinterpret_cast<uint4_t*>(my_a + lane * 8) = (uint4_t){0u, 0u, 0u, 0u};
+            *reinterpret_cast<uint4_t*>(my_a + 512 + lane * 8) = (uint4_t){0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int q = 0; q < R; ++q)
+                    if ((uint32_t)(64 * q + lane) < cnt[h])
+                        *reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(my_a + 512 * h) + (a[h][q] >> 16)) = (uint16_t)a[h][q];
+        };
+        auto block_barrier = [&]() {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        };
+
+        // ---- prologue: entries of fragments 0 .. LA-1, B rows of fragments 0 .. LB-1 in flight; fragment 0 staged ----
+        {
+            int cid0[NLD];
+#pragma unroll
+            for (int d = 0; d < LB; ++d) {
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) cid0[j] = fetch_colid((uint32_t)d, j);
+                issue_b((uint32_t)d, cid0, breg[d]);
+            }
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) cid_n[j] = fetch_colid((uint32_t)LB, j);
+#pragma unroll
+            for (int d = 0; d < LA; ++d) {
+                uint32_t o[3];
+                load_offsets((uint32_t)d, o);
+                issue_entries((uint32_t)d, o, areg[d], cnt_ring[d]);
+            }
+            load_offsets((uint32_t)LA, off_n);
+            stage_b(breg[0], 0);
+            scatter(areg[0], cnt_ring[0]);
+            block_barrier();
+        }
+
+        for (uint32_t base = 0; base < steps; base += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t s = base + (uint32_t)u;
+                // operands of fragment s (scattered during the previous round)
+                const half8_t a0 = *reinterpret_cast<const half8_t*>(my_a + lane * 8);
+                const half8_t a1 = *reinterpret_cast<const half8_t*>(my_a + 512 + lane * 8);
+                // requests: B rows of fragment s + LB (their column ids arrived a round ago), then the
+                // ids of fragment s + LB + 1, then this wave's entries of fragment s + LA
+                issue_b(s + LB, cid_n, breg[(u + LB) & 3]);
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) cid_n[j] = fetch_colid(s + LB + 1, j);
+                issue_entries(s + LA, off_n, areg[(u + LA) & 3], cnt_ring[(u + LA) & 3]);
+                // multiply fragment s out of LDS
+                const _Float16* sb = lds_b + (u & 1) * Gm::TILE_HALVES + tr_off;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int c = 0; c < NCH32; ++c) {
+                        const half4_t lo = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4_t __attribute__((address_space(3)))*)(sb + (16 * h) * LDB + 32 * c)));
+                        const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (short4_t __attribute__((address_space(3)))*)(sb + (16 * h + 4) * LDB + 32 * c)));
+                        const half8_t b_frag = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b_frag, h ? a1 : a0, acc[c], 0, 0, 0);
+                    }
+                // fragment s + 1: B rows into the other buffer, entries into the operand tiles
+                stage_b(breg[(u + 1) & 3], (u + 1) & 1);
+                scatter(areg[(u + 1) & 3], cnt_ring[(u + 1) & 3]);
+                // scalar loads go last (an LDS wait also waits for them), then the round's barrier
+                __builtin_amdgcn_sched_barrier(0);
+                load_offsets(s + LA + 1, off_n);
+                block_barrier();
+            }
+            if ((base & 31u) == 28u) {   // 32 fragments = 1024 condensed columns: second level
+#pragma unroll
+                for (int c = 0; c < NCH32; ++c) {
+                    acc2[c] += acc[c];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+                }
+            }
+        }
+    }
+
+    // ---- output: each wave's 32 rows x 32 features take a turn through LDS and leave as whole lines ----
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    float* const stage = reinterpret_cast<float*>(smem) + g * (32 * Gm::STAGE_STRIDE);
+    const int n = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int c = 0; c < NCH32; ++c) {
+        const float16_t sum = acc2[c] + acc[c];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<float4_t*>(stage + n * Gm::STAGE_STRIDE + 8 * q + 4 * hh) =
+                (float4_t){sum[4 * q], sum[4 * q + 1], sum[4 * q + 2], sum[4 * q + 3]};
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = i * 64 + lane, pr = id >> 3, fp = id & 7;
+            const float4_t v = *reinterpret_cast<const float4_t*>(stage + pr * Gm::STAGE_STRIDE + 4 * fp);
+            const int f = panel + 32 * c + 4 * fp;
+            const int prow = shfl_i32(row, pr);
+            if (f >= N) continue;
+            if (dst != kNoDst) {
+                *reinterpret_cast<float4_t*>(scratch + ((size_t)dst + g * 32 + pr) * N + f) = v;   // partial sums: ordinary stores
+            } else if (prow >= 0) {
+                panel_store(out, (size_t)prow, N, f, v);
+                keep_streaming_hint();
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Combine: C[row] = sum over parts of scratch[first + p*stride], in a fixed order
 // (four interleaved running sums, then a fixed tree), one wave per entry.
 // ---------------------------------------------------------------------------
@@ -859,6 +1129,37 @@ static int launch_tile_nw(const DevicePlan& d, const void* B, const OUT& out, hi
     }
 }
 
+// Panels of 128 features in one launch; what remains (N not a multiple of 128) in a launch of its own
+// with a panel of 32, 64 or 128 features, the features past N masked.
+template <int NCH32, int R, class OUT>
+static void launch_panel_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
+    uint32_t longest = 0;
+    for (int x = 0; x < 8; ++x) longest = std::max(longest, d.tile_split.start[x + 1] - d.tile_split.start[x]);
+    hipLaunchKernelGGL((rsh_panel_kernel<NCH32, R, OUT>), dim3(8u * longest, (unsigned)panels), dim3(256), 0, st,
+                       (const uint4*)d.tile_item, d.tile_split, d.win_row, d.win_tile_off, d.panel_col0, d.tile_colid,
+                       d.panel_off, d.panel_ent, (const __half*)B, out, d.scratch, d.geo.N, feature0);
+}
+template <int NCH32, class OUT>
+static int launch_panel_r(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
+    switch (d.geo.panel_rounds) {
+        case 2: launch_panel_t<NCH32, 2>(d, B, out, st, feature0, panels); return RSH_OK;
+        case 4: launch_panel_t<NCH32, 4>(d, B, out, st, feature0, panels); return RSH_OK;
+        case 8: launch_panel_t<NCH32, 8>(d, B, out, st, feature0, panels); return RSH_OK;
+        default: return RSH_ERR_BAD_OPTION;
+    }
+}
+template <class OUT>
+static int launch_panels(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st) {
+    const int full = d.geo.N / 128, rest = d.geo.N % 128;
+    int rc = RSH_OK;
+    if (full > 0) rc = launch_panel_r<4>(d, B, out, st, 0, full);
+    if (rc == RSH_OK && rest > 0)
+        rc = rest <= 32 ? launch_panel_r<1>(d, B, out, st, 128 * full, 1)
+           : rest <= 64 ? launch_panel_r<2>(d, B, out, st, 128 * full, 1)
+                        : launch_panel_r<4>(d, B, out, st, 128 * full, 1);
+    return rc;
+}
+
 template <class OUT>
 static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* stream, void* const* events) {
     hipStream_t st = (hipStream_t)stream;
@@ -867,7 +1168,10 @@ static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* 
     };
     mark(0);
     int rc = RSH_OK;
-    if (d.n_tile_items > 0) {
+    if (d.n_tile_items > 0 && d.geo.panel) {
+        rc = launch_panels(d, B, out, st);
+        if (rc != RSH_OK) return rc;
+    } else if (d.n_tile_items > 0) {
         // The feature width in 16-column chunks is covered by panels of 16, 8, 4, 2 and 1 chunks,
         // widest first (N = 160: one panel of 128 columns and one of 32), one launch per panel width.
         int chunks = d.geo.N / 16, feature0 = 0;

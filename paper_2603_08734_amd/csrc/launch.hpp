@@ -18,6 +18,9 @@ struct DevicePlan {
     uint32_t* tile_val_off = nullptr;
     uint16_t* tile_val = nullptr;
     uint32_t* tile_item = nullptr;
+    int32_t* panel_col0 = nullptr;
+    uint32_t* panel_off = nullptr;
+    uint32_t* panel_ent = nullptr;
     int32_t* irr_col = nullptr;
     uint16_t* irr_val = nullptr;
     uint32_t* irr_wave = nullptr;

@@ -40,6 +40,7 @@ Geometry make_geometry(int N, int window_rows, int tile_k) {
     g.tile_panel = 16;
     while (g.tile_panel < 256 && g.tile_panel * 2 <= N) g.tile_panel *= 2;   // widest panel of the tile kernel
     g.tile_nch = g.tile_panel / 16;
+    g.panel = window_rows == kPanelRows ? 1 : 0;
     return g;
 }
 
@@ -113,31 +114,34 @@ static int64_t union_size(const rsh_csr_t& a, const int32_t* rows, int n, std::v
 
 // Sampled test of whether taller windows pay.  Taller windows share one staged B tile among
 // more MFMA waves, which helps only when the merged windows name mostly the same columns.  Up
-// to 512 groups of four consecutive 16-row windows are measured: distinct columns of the single
-// windows (u1), of the two pairs (u2) and of the group (u4).
+// to 512 groups of eight consecutive 16-row windows are measured: distinct columns of the single
+// windows (u[0]), of the pairs (u[1]), of the groups of four (u[2]) and of the whole group (u[3]).
+// The height doubles while the merged windows keep within 0.6 of the columns of their parts.
 int choose_window_rows(const rsh_csr_t& a, const Partition& part16) {
     const int64_t n_win = (int64_t)part16.win_row.size() / kW;
     if (n_win < 64) return kW;
-    const int64_t n_groups = n_win / 4, n_samples = std::min<int64_t>(512, n_groups);
-    // seen[c] = last (sample, unit) stamp under which column c was counted, per merge level
-    std::vector<int64_t> seen1((size_t)a.n_cols, -1), seen2((size_t)a.n_cols, -1), seen4((size_t)a.n_cols, -1);
-    int64_t u1 = 0, u2 = 0, u4 = 0;
+    const int64_t n_groups = n_win / 8, n_samples = std::min<int64_t>(512, n_groups);
+    // seen[level][c] = last (sample, unit) stamp under which column c was counted at that merge level
+    std::vector<int64_t> seen[4];
+    for (auto& v : seen) v.assign((size_t)a.n_cols, -1);
+    int64_t u[4] = {0, 0, 0, 0};
     for (int64_t s = 0; s < n_samples; ++s) {
-        const int32_t* rows = &part16.win_row[(size_t)((s * n_groups / n_samples) * 4 * kW)];
-        for (int i = 0; i < 4 * kW; ++i) {
+        const int32_t* rows = &part16.win_row[(size_t)((s * n_groups / n_samples) * 8 * kW)];
+        for (int i = 0; i < 8 * kW; ++i) {
             const int32_t r = rows[i];
             if (r < 0) continue;
-            const int64_t s1 = 4 * s + i / kW, s2 = 2 * s + i / (2 * kW);
             for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
                 const size_t c = (size_t)a.col_idx[p];
-                if (seen1[c] != s1) seen1[c] = s1, ++u1;
-                if (seen2[c] != s2) seen2[c] = s2, ++u2;
-                if (seen4[c] != s) seen4[c] = s, ++u4;
+                for (int level = 0; level < 4; ++level) {
+                    const int64_t stamp = ((8 * s + i / kW) >> level);
+                    if (seen[level][c] != stamp) seen[level][c] = stamp, ++u[level];
+                }
             }
         }
     }
-    if (u2 * 10 > u1 * 6) return kW;
-    return u4 * 10 > u2 * 6 ? 2 * kW : 4 * kW;
+    int rows = kW;
+    for (int level = 1; level < 4 && u[level] * 10 <= u[level - 1] * 6; ++level) rows *= 2;
+    return rows;
 }
 
 void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
@@ -313,7 +317,7 @@ XcdSplit split_by_cost(const std::vector<uint32_t>& cost) {
 static inline uint32_t round_up_to(uint32_t x, uint32_t m) { return (x + m - 1u) / m * m; }   // m = 4 or 8
 
 struct WinEntry {
-    uint64_t key;  // col << 6 | window row
+    uint64_t key;  // col << 7 | window row
     uint16_t val;
 };
 
@@ -323,7 +327,7 @@ static void gather_window(const rsh_csr_t& a, const int32_t* rows, int W, std::v
     for (int r = 0; r < W; ++r) {
         if (rows[r] < 0) continue;
         for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p)
-            ent.push_back({((uint64_t)(uint32_t)a.col_idx[p] << 6) | (uint64_t)r, a.val_f16[p]});
+            ent.push_back({((uint64_t)(uint32_t)a.col_idx[p] << 7) | (uint64_t)r, a.val_f16[p]});
     }
     std::sort(ent.begin(), ent.end(), [](const WinEntry& x, const WinEntry& y) { return x.key < y.key; });
 }
@@ -397,119 +401,246 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
     return order;
 }
 
-int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads) {
-    const Geometry& geo = plan.geo;
-    const int W = geo.win_rows, NW = geo.nw;
-    const uint32_t K = (uint32_t)geo.tile_k, CPL = (uint32_t)geo.cpl;   // fragment columns; cells per lane = bitmap words
+// ---------------------------------------------------------------------------
+// Tall windows in the panel form.  A window is 128 rows = four row groups of 32 (one wave each); its
+// sorted distinct columns are cut into fragments of 32 (two MFMA K steps of 16).  The stored entries
+// of row group g, fragment t, K step h form one unit -- the 32 x 16 operand of one
+// v_mfma_f32_32x32x16_f16 -- and each entry carries the byte address of its cell in that operand as
+// the instruction wants it in registers (lane = row + 32 * (k / 8), element k % 8, 16 bytes per lane):
+// the kernel scatters a unit's entries into a zeroed 1 KB tile and reads the operand back with one
+// 16-byte read per lane, so the work per unit grows with its entries, not with its 512 cells (the
+// bitmap form expands cell by cell).  Units are stored row group by row group, so that the stream
+// a wave reads is contiguous: unit (g, t, h) of window w is 8 * first_fragment(w) +
+// (g * fragments(w) + (t - first_fragment(w))) * 2 + h.
+// ---------------------------------------------------------------------------
+static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads,
+                              int64_t* sum_cols, int64_t* nnz_tile) {
+    constexpr int W = kPanelRows, G = kPanelGroups;
+    constexpr uint32_t K = kPanelK;
     const int64_t n_win = (int64_t)part.win_row.size() / W;
-    plan.win_row = part.win_row;
-
-    // ---- pass 1: fragments and padded value count per window ---------------------------
-    // A window of W = 16*NW rows shares one condensed column space; fragment t of the window
-    // has NW sub-fragments (rows 16s .. 16s+15), each with its own bitmap and value run.
-    std::vector<uint32_t> win_tiles((size_t)n_win), win_vals((size_t)n_win);
+    // pass 1: fragments and entries per window
+    std::vector<uint32_t> win_tiles((size_t)n_win);
+    std::vector<uint64_t> win_ent((size_t)n_win);
     std::vector<int64_t> win_cols((size_t)n_win);
     parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
         std::vector<WinEntry> ent;
-        std::vector<uint32_t> cnt;   // entries per (fragment, sub-fragment)
         for (int64_t w = b; w < e; ++w) {
             gather_window(a, &part.win_row[w * W], W, ent);
             int64_t u = 0;
-            cnt.clear();
             uint64_t prev_col = ~0ull;
-            for (const WinEntry& x : ent) {
-                const uint64_t c = x.key >> 6;
-                if (c != prev_col) {
-                    prev_col = c;
-                    if (u % K == 0) cnt.insert(cnt.end(), (size_t)NW, 0u);
-                    ++u;
-                }
-                ++cnt[cnt.size() - (size_t)NW + (size_t)((x.key & 63) >> 4)];
-            }
-            uint32_t v = 0;
-            for (uint32_t c : cnt) v += round_up_to(c, CPL);
-            win_tiles[w] = (uint32_t)(cnt.size() / (size_t)NW);
-            win_vals[w] = v;
+            for (const WinEntry& x : ent)
+                if ((x.key >> 7) != prev_col) prev_col = x.key >> 7, ++u;
             win_cols[w] = u;
+            win_tiles[w] = (uint32_t)((u + K - 1) / K);
+            win_ent[w] = ent.size();
         }
     });
     plan.win_tile_off.assign((size_t)n_win + 1, 0);
-    std::vector<uint64_t> win_val_off((size_t)n_win + 1, 0);
-    int64_t sum_cols = 0;
+    std::vector<uint64_t> win_ent_off((size_t)n_win + 1, 0);
     for (int64_t w = 0; w < n_win; ++w) {
         const uint64_t t = (uint64_t)plan.win_tile_off[w] + win_tiles[w];
-        if (t * (uint64_t)NW >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+        if (t * 2 * G >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
         plan.win_tile_off[w + 1] = (uint32_t)t;
-        win_val_off[w + 1] = win_val_off[w] + win_vals[w];
-        sum_cols += win_cols[w];
+        win_ent_off[w + 1] = win_ent_off[w] + win_ent[w];
+        *sum_cols += win_cols[w];
     }
-    const int64_t n_tiles = plan.win_tile_off[n_win];
-    if (win_val_off[n_win] >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
-    plan.tile_colid.assign((size_t)n_tiles * K, 0);
-    plan.tile_mask.assign((size_t)n_tiles * NW * CPL, 0);
-    plan.tile_val_off.assign((size_t)n_tiles * NW + 1, 0);
-    plan.tile_val.assign((size_t)win_val_off[n_win] + 520, 0);  // tail pad: every lane reads CPL elements, unconditionally
-
-    // ---- pass 2: fill -------------------------------------------------------------------
-    std::vector<int64_t> win_nnz((size_t)n_win, 0);
+    if (win_ent_off[n_win] >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+    const size_t n_tiles = plan.win_tile_off[n_win], n_units = n_tiles * 2 * G;
+    plan.tile_colid.assign(n_tiles * K, 0);
+    plan.panel_col0.assign((size_t)n_win, -1);
+    plan.panel_off.assign(n_units + 1, 0);
+    plan.panel_ent.assign((size_t)win_ent_off[n_win] + 64 * 8, 0);   // tail pad: lanes read whole rounds of 64
+    plan.tile_mask.clear();
+    plan.tile_val_off.clear();
+    plan.tile_val.clear();
+    // pass 2: fill
+    std::vector<uint32_t> win_max_unit((size_t)n_win, 0);
     parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
         std::vector<WinEntry> ent;
-        std::vector<uint32_t> ucol;   // condensed column index of each entry
+        std::vector<uint32_t> unit_of, cnt;
         for (int64_t w = b; w < e; ++w) {
             gather_window(a, &part.win_row[w * W], W, ent);
-            win_nnz[w] = (int64_t)ent.size();
-            const uint32_t t0 = plan.win_tile_off[w];
-            const uint32_t nt = plan.win_tile_off[w + 1] - t0;
-            // condensed column ids (sorted ascending) and bitmaps
-            ucol.resize(ent.size());
+            const uint32_t t0 = plan.win_tile_off[w], nt = plan.win_tile_off[w + 1] - t0;
+            if (nt == 0) continue;
+            unit_of.resize(ent.size());
+            cnt.assign((size_t)nt * 2 * G + 1, 0);
             int64_t u = -1;
             uint64_t prev_col = ~0ull;
             for (size_t i = 0; i < ent.size(); ++i) {
-                const uint64_t c = ent[i].key >> 6;
+                const uint64_t c = ent[i].key >> 7;
                 if (c != prev_col) {
                     prev_col = c;
                     ++u;
                     plan.tile_colid[(size_t)t0 * K + (size_t)u] = (int32_t)c;
                 }
-                ucol[i] = (uint32_t)u;
-                const uint32_t t = (uint32_t)u / K, k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 63);
-                plan.tile_mask[((size_t)(t0 + t) * NW + (r >> 4)) * CPL + (k % CPL)] |= 1ull << ((k / CPL) * 16 + (r & 15));
+                const uint32_t t = (uint32_t)u / K, k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 127);
+                unit_of[i] = ((r / 32) * nt + t) * 2 + k / 16;
+                ++cnt[unit_of[i] + 1];
             }
-            // padding columns of the last fragment repeat its last valid column
-            if (nt > 0) {
-                const int64_t n_u = u + 1;
-                for (int64_t k = n_u; k < (int64_t)nt * K; ++k)
-                    plan.tile_colid[(size_t)t0 * K + (size_t)k] = plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)];
+            const int64_t n_u = u + 1;
+            for (int64_t k = n_u; k < (int64_t)nt * K; ++k)   // padding columns repeat the last valid one
+                plan.tile_colid[(size_t)t0 * K + (size_t)k] = plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)];
+            // one run of consecutive columns that fills whole fragments: the kernel computes column ids
+            if (n_u == (int64_t)nt * K && plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)] - plan.tile_colid[(size_t)t0 * K] == n_u - 1)
+                plan.panel_col0[(size_t)w] = plan.tile_colid[(size_t)t0 * K];
+            uint32_t most = 0;
+            for (size_t q = 1; q < cnt.size(); ++q) {
+                most = std::max(most, cnt[q]);
+                cnt[q] += cnt[q - 1];
             }
-            // value offsets of every sub-fragment
-            uint64_t off = win_val_off[w];
-            for (uint32_t q = 0; q < nt * (uint32_t)NW; ++q) {
-                plan.tile_val_off[(size_t)t0 * NW + q] = (uint32_t)off;
-                uint32_t c = 0;
-                for (uint32_t j = 0; j < CPL; ++j) c += (uint32_t)popc64(plan.tile_mask[((size_t)t0 * NW + q) * CPL + j]);
-                off += round_up_to(c, CPL);
-            }
-            // values: position = (entries of lower lanes) + (entries of this lane in lower words)
+            win_max_unit[(size_t)w] = most;
+            const size_t ub = (size_t)t0 * 2 * G;
+            for (size_t q = 0; q + 1 < cnt.size(); ++q) plan.panel_off[ub + q] = (uint32_t)(win_ent_off[w] + cnt[q]);
+            // entries arrive sorted by (column, row); inside a unit they are stored by cell address
+            uint32_t* out = &plan.panel_ent[(size_t)win_ent_off[w]];
+            u = -1;
+            prev_col = ~0ull;
             for (size_t i = 0; i < ent.size(); ++i) {
-                const uint32_t t = ucol[i] / K, k = ucol[i] % K, r = (uint32_t)(ent[i].key & 63);
-                const uint32_t lane = (k / CPL) * 16 + (r & 15), word = k % CPL;
-                const size_t sub = (size_t)(t0 + t) * NW + (r >> 4);
-                const uint64_t* m = &plan.tile_mask[sub * CPL];
-                const uint64_t below = lane ? (~0ull >> (64 - lane)) : 0ull;
-                uint32_t pos = 0;
-                for (uint32_t q = 0; q < CPL; ++q) pos += (uint32_t)popc64(m[q] & below);
-                for (uint32_t q = 0; q < word; ++q) pos += (uint32_t)((m[q] >> lane) & 1ull);
-                plan.tile_val[plan.tile_val_off[sub] + pos] = ent[i].val;
+                if ((ent[i].key >> 7) != prev_col) prev_col = ent[i].key >> 7, ++u;
+                const uint32_t k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 127);
+                const uint32_t lane = (r % 32) + 32 * ((k % 16) / 8), addr = (lane * 8 + k % 8) * 2;
+                out[cnt[unit_of[i]]++] = (addr << 16) | ent[i].val;
+            }
+            // cnt[q] is now the end of unit q
+            for (size_t q = 0; q + 1 < cnt.size(); ++q) {
+                uint32_t* ub_ = out + (q ? cnt[q - 1] : 0u);
+                std::sort(ub_, out + cnt[q]);
             }
         }
     });
-    plan.tile_val_off[(size_t)n_tiles * NW] = (uint32_t)win_val_off[n_win];
-    int64_t nnz_tile = 0;
-    for (int64_t w = 0; w < n_win; ++w) nnz_tile += win_nnz[w];
+    plan.panel_off[n_units] = (uint32_t)win_ent_off[n_win];
+    uint32_t most = 0;
+    for (uint32_t m : win_max_unit) most = std::max(most, m);
+    const int rounds = (int)((most + 63) / 64);
+    plan.geo.panel_rounds = rounds <= 2 ? 2 : rounds <= 4 ? 4 : 8;
+    *nnz_tile = (int64_t)win_ent_off[n_win];
+    return RSH_OK;
+}
+
+int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads) {
+    Geometry& geo = plan.geo;
+    const int W = geo.win_rows, NW = geo.nw;
+    const uint32_t K = (uint32_t)geo.tile_k, CPL = (uint32_t)geo.cpl;   // fragment columns; cells per lane = bitmap words
+    const int64_t n_win = (int64_t)part.win_row.size() / W;
+    plan.win_row = part.win_row;
+
+    int64_t sum_cols = 0, n_tiles = 0, nnz_tile = 0;
+    if (geo.panel) {
+        const int rc = pack_panel_windows(a, part, plan, threads, &sum_cols, &nnz_tile);
+        if (rc != RSH_OK) return rc;
+        n_tiles = plan.win_tile_off[n_win];
+    } else {
+        // ---- pass 1: fragments and padded value count per window ---------------------------
+        // A window of W = 16*NW rows shares one condensed column space; fragment t of the window
+        // has NW sub-fragments (rows 16s .. 16s+15), each with its own bitmap and value run.
+        std::vector<uint32_t> win_tiles((size_t)n_win), win_vals((size_t)n_win);
+        std::vector<int64_t> win_cols((size_t)n_win);
+        parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
+            std::vector<WinEntry> ent;
+            std::vector<uint32_t> cnt;   // entries per (fragment, sub-fragment)
+            for (int64_t w = b; w < e; ++w) {
+                gather_window(a, &part.win_row[w * W], W, ent);
+                int64_t u = 0;
+                cnt.clear();
+                uint64_t prev_col = ~0ull;
+                for (const WinEntry& x : ent) {
+                    const uint64_t c = x.key >> 7;
+                    if (c != prev_col) {
+                        prev_col = c;
+                        if (u % K == 0) cnt.insert(cnt.end(), (size_t)NW, 0u);
+                        ++u;
+                    }
+                    ++cnt[cnt.size() - (size_t)NW + (size_t)((x.key & 127) >> 4)];
+                }
+                uint32_t v = 0;
+                for (uint32_t c : cnt) v += round_up_to(c, CPL);
+                win_tiles[w] = (uint32_t)(cnt.size() / (size_t)NW);
+                win_vals[w] = v;
+                win_cols[w] = u;
+            }
+        });
+        plan.win_tile_off.assign((size_t)n_win + 1, 0);
+        std::vector<uint64_t> win_val_off((size_t)n_win + 1, 0);
+        for (int64_t w = 0; w < n_win; ++w) {
+            const uint64_t t = (uint64_t)plan.win_tile_off[w] + win_tiles[w];
+            if (t * (uint64_t)NW >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+            plan.win_tile_off[w + 1] = (uint32_t)t;
+            win_val_off[w + 1] = win_val_off[w] + win_vals[w];
+            sum_cols += win_cols[w];
+        }
+        n_tiles = plan.win_tile_off[n_win];
+        if (win_val_off[n_win] >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
+        plan.tile_colid.assign((size_t)n_tiles * K, 0);
+        plan.tile_mask.assign((size_t)n_tiles * NW * CPL, 0);
+        plan.tile_val_off.assign((size_t)n_tiles * NW + 1, 0);
+        plan.tile_val.assign((size_t)win_val_off[n_win] + 520, 0);  // tail pad: every lane reads CPL elements, unconditionally
+
+        // ---- pass 2: fill -------------------------------------------------------------------
+        std::vector<int64_t> win_nnz((size_t)n_win, 0);
+        parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
+            std::vector<WinEntry> ent;
+            std::vector<uint32_t> ucol;   // condensed column index of each entry
+            for (int64_t w = b; w < e; ++w) {
+                gather_window(a, &part.win_row[w * W], W, ent);
+                win_nnz[w] = (int64_t)ent.size();
+                const uint32_t t0 = plan.win_tile_off[w];
+                const uint32_t nt = plan.win_tile_off[w + 1] - t0;
+                // condensed column ids (sorted ascending) and bitmaps
+                ucol.resize(ent.size());
+                int64_t u = -1;
+                uint64_t prev_col = ~0ull;
+                for (size_t i = 0; i < ent.size(); ++i) {
+                    const uint64_t c = ent[i].key >> 7;
+                    if (c != prev_col) {
+                        prev_col = c;
+                        ++u;
+                        plan.tile_colid[(size_t)t0 * K + (size_t)u] = (int32_t)c;
+                    }
+                    ucol[i] = (uint32_t)u;
+                    const uint32_t t = (uint32_t)u / K, k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 127);
+                    plan.tile_mask[((size_t)(t0 + t) * NW + (r >> 4)) * CPL + (k % CPL)] |= 1ull << ((k / CPL) * 16 + (r & 15));
+                }
+                // padding columns of the last fragment repeat its last valid column
+                if (nt > 0) {
+                    const int64_t n_u = u + 1;
+                    for (int64_t k = n_u; k < (int64_t)nt * K; ++k)
+                        plan.tile_colid[(size_t)t0 * K + (size_t)k] = plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)];
+                }
+                // value offsets of every sub-fragment
+                uint64_t off = win_val_off[w];
+                for (uint32_t q = 0; q < nt * (uint32_t)NW; ++q) {
+                    plan.tile_val_off[(size_t)t0 * NW + q] = (uint32_t)off;
+                    uint32_t c = 0;
+                    for (uint32_t j = 0; j < CPL; ++j) c += (uint32_t)popc64(plan.tile_mask[((size_t)t0 * NW + q) * CPL + j]);
+                    off += round_up_to(c, CPL);
+                }
+                // values: position = (entries of lower lanes) + (entries of this lane in lower words)
+                for (size_t i = 0; i < ent.size(); ++i) {
+                    const uint32_t t = ucol[i] / K, k = ucol[i] % K, r = (uint32_t)(ent[i].key & 127);
+                    const uint32_t lane = (k / CPL) * 16 + (r & 15), word = k % CPL;
+                    const size_t sub = (size_t)(t0 + t) * NW + (r >> 4);
+                    const uint64_t* m = &plan.tile_mask[sub * CPL];
+                    const uint64_t below = lane ? (~0ull >> (64 - lane)) : 0ull;
+                    uint32_t pos = 0;
+                    for (uint32_t q = 0; q < CPL; ++q) pos += (uint32_t)popc64(m[q] & below);
+                    for (uint32_t q = 0; q < word; ++q) pos += (uint32_t)((m[q] >> lane) & 1ull);
+                    plan.tile_val[plan.tile_val_off[sub] + pos] = ent[i].val;
+                }
+            }
+        });
+        plan.tile_val_off[(size_t)n_tiles * NW] = (uint32_t)win_val_off[n_win];
+        for (int64_t w = 0; w < n_win; ++w) nnz_tile += win_nnz[w];
+
+    }
 
     // ---- tile work items (bounded fragments per item, Section 3.3.3) --------------------
     int64_t t_max = plan.opts.max_tiles_per_item;
-    if (t_max <= 0) {
+    if (t_max <= 0 && geo.panel) {
+        // Tall windows: a workgroup sums an item's fragments in two levels (every 1024 condensed
+        // columns the running sums are added to a second set), so an item may be long; windows are
+        // only cut to hand every compute unit about two workgroups, never below 1024 columns.
+        t_max = std::max<int64_t>(1024 / kPanelK, (n_tiles + 511) / 512);
+    } else if (t_max <= 0) {
         int64_t per = (n_tiles + 4095) / 4096, p2 = 1;
         while (p2 < per) p2 <<= 1;
         // 512 .. 1024 condensed columns per item: the upper end keeps the fp32 accumulation chain of
@@ -523,13 +654,17 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     for (int64_t wi = 0; wi < n_win; ++wi) {
         const int64_t w = worder[(size_t)wi];
         const uint32_t t0 = plan.win_tile_off[w], nt = plan.win_tile_off[w + 1] - t0;
-        if (nt <= (uint32_t)t_max) {
+        // the panel form cuts a window into the nearest whole number of parts (items of about t_max
+        // fragments), the bitmap form into the fewest parts of at most t_max fragments
+        const uint32_t parts = geo.panel && plan.opts.max_tiles_per_item <= 0
+                                   ? (uint32_t)std::max<int64_t>(1, (2 * (int64_t)nt + t_max) / (2 * t_max))
+                                   : (uint32_t)((nt + t_max - 1) / t_max);
+        if (parts <= 1) {
             // a window without fragments (only absent/empty rows) still zero-fills its rows
             plan.tile_item.insert(plan.tile_item.end(), {(uint32_t)w, t0, t0 + nt, kNoDst});
             continue;
         }
         ++n_split_windows;
-        const uint32_t parts = (uint32_t)((nt + t_max - 1) / t_max);
         for (uint32_t p = 0; p < parts; ++p) {
             const uint32_t b = t0 + (uint32_t)((uint64_t)nt * p / parts);
             const uint32_t e = t0 + (uint32_t)((uint64_t)nt * (p + 1) / parts);
@@ -809,11 +944,13 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     st.sum_window_cols = sum_cols;
     st.plan_bytes = (int64_t)(plan.win_row.size() * 4 + plan.win_tile_off.size() * 4 + plan.tile_colid.size() * 4 +
                               plan.tile_mask.size() * 8 + plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 +
-                              plan.tile_item.size() * 4 + plan.irr_col.size() * 4 + plan.irr_val.size() * 2 +
+                              plan.tile_item.size() * 4 + plan.panel_col0.size() * 4 + plan.panel_off.size() * 4 +
+                              plan.panel_ent.size() * 4 + plan.irr_col.size() * 4 + plan.irr_val.size() * 2 +
                               plan.irr_wave.size() * 4 + plan.irr_row.size() * 4 + plan.combine.size() * 4);
     st.csr_bytes = 6 * a.nnz + 8 * (a.n_rows + 1);
     st.tile_part_bytes = (int64_t)(plan.win_row.size() * 4 + plan.tile_colid.size() * 4 + plan.tile_mask.size() * 8 +
-                                   plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 + plan.tile_item.size() * 4);
+                                   plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 + plan.tile_item.size() * 4 +
+                                   plan.panel_col0.size() * 4 + plan.panel_off.size() * 4 + plan.panel_ent.size() * 4);
     st.irregular_part_bytes = (int64_t)(plan.irr_col.size() * 4 + plan.irr_val.size() * 2 + plan.irr_wave.size() * 4 +
                                         plan.irr_row.size() * 4);
     {
@@ -854,7 +991,21 @@ int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t*
     // dense-fragment part
     const int W = p.geo.win_rows, NW = p.geo.nw, K = p.geo.tile_k, CPL = p.geo.cpl;
     const int64_t n_win = (int64_t)p.win_row.size() / W;
-    for (int64_t w = 0; w < n_win; ++w) {
+    for (int64_t w = 0; w < n_win && p.geo.panel; ++w) {
+        const uint32_t t0 = p.win_tile_off[w], nt = p.win_tile_off[w + 1] - t0;
+        for (uint32_t g = 0; g < (uint32_t)kPanelGroups; ++g)
+            for (uint32_t t = 0; t < nt; ++t)
+                for (uint32_t h = 0; h < 2; ++h) {
+                    const size_t unit = (size_t)t0 * 2 * kPanelGroups + ((size_t)g * nt + t) * 2 + h;
+                    for (uint32_t q = p.panel_off[unit]; q < p.panel_off[unit + 1]; ++q) {
+                        const uint32_t addr = p.panel_ent[q] >> 16, lane = addr / 16, k = h * 16 + (lane / 32) * 8 + (addr % 16) / 2;
+                        const int32_t row = p.win_row[(size_t)w * W + g * 32 + lane % 32];
+                        if (row < 0 || addr >= 1024 || (addr & 1)) return RSH_ERR_INVALID_CSR;
+                        ent.push_back({row, p.tile_colid[(size_t)(t0 + t) * K + k], (uint16_t)(p.panel_ent[q] & 0xffffu), 0});
+                    }
+                }
+    }
+    for (int64_t w = 0; w < n_win && !p.geo.panel; ++w) {
         for (uint32_t t = p.win_tile_off[w]; t < p.win_tile_off[w + 1]; ++t)
             for (int sw = 0; sw < NW; ++sw) {
                 const uint64_t* m = &p.tile_mask[((size_t)t * NW + sw) * CPL];

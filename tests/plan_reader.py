@@ -16,15 +16,50 @@ numpy, following only the layout documented in the public header:
   ids are irr_row[dst .. dst+count); kind 1 -- count consecutive entries of one row,
   the row being dst itself or, when info has bit 2 set, the row whose combine entry
   (row, first slot, parts, stride) covers scratch slot dst; kind 2 -- no entries.
+
+Panel form (window_rows == 128): a window is four row groups of 32 rows, a fragment is 32 condensed
+columns = two K steps of 16; the entries of (row group g, fragment t, K step h) of window w are the
+words panel_ent[panel_off[u] .. panel_off[u+1]) with u = 8 * t0 + (g * nt + (t - t0)) * 2 + h
+(t0 = win_tile_off[w], nt = the window's fragment count); a word is value bits | address << 16 with
+address = ((r + 32 * (k // 8)) * 8 + k % 8) * 2 for row r of the group and column k of the K step.
 """
 from __future__ import annotations
 
 import numpy as np
 
 
+def panel_entries(win_row, win_tile_off, tile_colid, panel_off, panel_ent):
+    """(rows, cols, value bits) of the dense-fragment part of a plan in the panel form."""
+    rows, cols, vals = [], [], []
+    n_win = len(win_row) // 128
+    for w in range(n_win):
+        t0, t1 = int(win_tile_off[w]), int(win_tile_off[w + 1])
+        nt = t1 - t0
+        for g in range(4):
+            for t in range(nt):
+                for h in range(2):
+                    u = 8 * t0 + (g * nt + t) * 2 + h
+                    for q in range(int(panel_off[u]), int(panel_off[u + 1])):
+                        word = int(panel_ent[q])
+                        addr = word >> 16
+                        assert addr % 2 == 0 and addr < 1024
+                        lane, j = addr // 16, (addr % 16) // 2
+                        r, k = lane % 32, 16 * h + 8 * (lane // 32) + j
+                        row = int(win_row[128 * w + 32 * g + r])
+                        assert row >= 0, "an entry in an absent window row"
+                        rows.append(row)
+                        cols.append(int(tile_colid[32 * (t0 + t) + k]))
+                        vals.append(word & 0xFFFF)
+    return rows, cols, vals
+
+
 def entries_from_arrays(win_row, win_tile_off, tile_colid, tile_mask, tile_val_off, tile_val,
                         irr_col, irr_val, irr_wave, irr_row, combine, n_scratch_slots, window_rows=16, tile_k=16):
     rows, cols, vals, paths = [], [], [], []
+    if window_rows == 128:          # panel form: the caller passes (panel_off, panel_ent) in place of the bitmap arrays
+        rows, cols, vals = panel_entries(win_row, win_tile_off, tile_colid, tile_mask, tile_val)
+        paths = [0] * len(rows)
+        win_row = []
     W, NW = window_rows, window_rows // 16
     K, Q = tile_k, tile_k // 4
     n_win = len(win_row) // W

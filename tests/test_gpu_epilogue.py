@@ -77,7 +77,7 @@ def test_reduced_configs_all_routings(k, mode, epi):
 
 
 @pytest.mark.parametrize("N", [16, 32, 48, 64, 96, 128, 256, 512, 1024])
-@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "w64_all_tile", "w32_all_tile", "k32_w64_all_tile"])
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "w64_all_tile", "w32_all_tile", "k32_w64_all_tile", "w128_all_tile"])
 def test_feature_widths(N, mode):
     A, _, _ = make_config(3, small=True)
     B = dense_B(A.n_cols, N, "normal", seed=N)
@@ -88,7 +88,7 @@ def test_feature_widths(N, mode):
     check(C16, C16b, C32, Z, S, bias, True, f"N={N} {mode}")
 
 
-@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "tiny_items", "tiny_slices", "w64_all_tile", "w32_all_tile"])
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "tiny_items", "tiny_slices", "w64_all_tile", "w32_all_tile", "w128_split"])
 @pytest.mark.parametrize("name", list(edge_matrices()))
 def test_edge_cases(name, mode):
     A = edge_matrices()[name]
@@ -220,7 +220,7 @@ def test_fused_transposed_product(k):
     plan.destroy()
 
 
-@pytest.mark.parametrize("mode", ["all_tile_k16", "all_tile_w64", "all_irregular", "hybrid"])
+@pytest.mark.parametrize("mode", ["all_tile_k16", "all_tile_w64", "all_tile_w128", "all_irregular", "hybrid"])
 @pytest.mark.parametrize("what", ["a_subnormal", "b_subnormal"])
 def test_binary16_subnormal_operands_and_outputs(what, mode):
     """Subnormal operands through the fused epilogue: with one operand subnormal and the other of

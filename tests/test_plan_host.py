@@ -417,3 +417,96 @@ def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
     assert "c abi ok" in res.stdout
+
+
+# ---------------------------------------------------------------------------
+# tall windows in the panel form (window_rows = 128)
+# ---------------------------------------------------------------------------
+PANEL_MODES = {
+    "w128_hybrid": dict(window_rows=128),
+    "w128_all_tile": dict(window_rows=128, force_path=2),
+    "w128_split": dict(window_rows=128, force_path=2, max_tiles_per_item=3),
+    "w128_no_reorder": dict(window_rows=128, force_path=2, reorder=0),
+}
+
+
+@pytest.mark.parametrize("mode", list(PANEL_MODES))
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_panel_form_decodes_bit_exactly_and_reads_back_independently(k, mode):
+    A, N, _ = make_config(k, small=True)
+    p = host_plan(A, N, **PANEL_MODES[mode])
+    st = p.stats()
+    assert st["window_rows"] == 128 and st["tile_k"] == 32
+    row_ptr, col_idx, val, path = p.decode()
+    assert np.array_equal(row_ptr, A.row_ptr) and np.array_equal(col_idx, A.col_idx)
+    assert np.array_equal(val, A.val.view(np.uint16))
+    assert int((path == 0).sum()) == st["nnz_tile"] and int((path == 1).sum()) == st["nnz_irregular"]
+    a = arrays_of(p)
+    poff, pent = p.array(B_.RSH_ARR_PANEL_OFF), p.array(B_.RSH_ARR_PANEL_ENT)
+    assert a["TILE_MASK"].size == 0 and a["TILE_VAL"].size == 0
+    rows, cols, vals, paths = rstile.entries_from_arrays(
+        a["WIN_ROW"], a["WIN_TILE_OFF"], a["TILE_COLID"], poff, None, pent,
+        a["IRR_COL"], a["IRR_VAL"], a["IRR_WAVE"], a["IRR_ROW"], a["COMBINE"], st["n_scratch_slots"],
+        window_rows=128, tile_k=32)
+    assert rows.size == A.nnz
+    rp, ci, v, _ = rstile.csr_from_entries(rows, cols, vals, paths, A.n_rows, A.n_cols)
+    assert np.array_equal(rp, A.row_ptr) and np.array_equal(ci, A.col_idx) and np.array_equal(v, A.val.view(np.uint16))
+
+
+@pytest.mark.parametrize("mode", list(PANEL_MODES))
+@pytest.mark.parametrize("k", [2, 3, 5])
+def test_panel_form_invariants(k, mode):
+    A, N, _ = make_config(k, small=True)
+    p = host_plan(A, N, **PANEL_MODES[mode])
+    a, st = arrays_of(p), p.stats()
+    n_win, n_tiles = st["n_windows"], st["n_tiles"]
+    off = a["WIN_TILE_OFF"].astype(np.int64)
+    poff = p.array(B_.RSH_ARR_PANEL_OFF).astype(np.int64)
+    pent = p.array(B_.RSH_ARR_PANEL_ENT)
+    col0 = p.array(B_.RSH_ARR_PANEL_COL0)
+    colid = a["TILE_COLID"].reshape(n_tiles, 32)
+    win_row = a["WIN_ROW"].reshape(n_win, 128)
+    assert poff.size == 8 * n_tiles + 1 and poff[0] == 0 and poff[-1] == st["nnz_tile"]
+    assert np.all(np.diff(poff) >= 0) and np.diff(poff).max(initial=0) <= 512
+    assert pent.size >= st["nnz_tile"] + 512, "the entry stream is padded for whole rounds of 64 lanes"
+    for w in range(n_win):
+        t0, nt = off[w], off[w + 1] - off[w]
+        cols_w = colid[t0:t0 + nt].reshape(-1)
+        distinct = np.unique(cols_w)
+        if nt:
+            assert np.array_equal(cols_w[:distinct.size], distinct) and np.all(cols_w[distinct.size:] == distinct[-1])
+        one_run = nt > 0 and distinct.size == 32 * nt and distinct[-1] - distinct[0] == distinct.size - 1
+        assert col0[w] == (distinct[0] if one_run else -1)
+        for g in range(4):
+            for t in range(nt):
+                for h in range(2):
+                    u = 8 * t0 + (g * nt + t) * 2 + h
+                    words = pent[poff[u]:poff[u + 1]].astype(np.int64)
+                    addr = words >> 16
+                    assert np.all(np.diff(addr) > 0), "entries of a unit are stored by ascending, distinct cell address"
+                    assert np.all(addr % 2 == 0) and np.all(addr < 1024)
+                    lane, j = addr // 16, (addr % 16) // 2
+                    kcol = 32 * t + 16 * h + 8 * (lane // 32) + j
+                    assert np.all(kcol < distinct.size), "padding columns carry no entries"
+                    assert np.all(win_row[w, 32 * g + lane % 32] >= 0), "absent rows carry no entries"
+    # work items cover every fragment of every window exactly once
+    items = a["TILE_ITEM"].reshape(-1, 4).astype(np.int64)
+    seen = np.zeros(n_tiles, dtype=np.int64)
+    for win, b, e, dst in items:
+        assert off[win] <= b <= e <= off[win + 1]
+        seen[b:e] += 1
+    assert np.all(seen == 1)
+    rounds = -(-int(np.diff(poff).max(initial=0)) // 64)
+    assert rounds <= 8
+
+
+def test_window_height_is_chosen_by_column_sharing():
+    """Rows that all name the same columns (a pruned weight matrix) get the tallest windows; a
+    stencil in natural order, where merged windows share nothing, keeps 16-row windows."""
+    A5, N5, _ = make_config(5, small=True)
+    p5 = host_plan(A5, N5)
+    A3, N3, _ = make_config(3, small=True)
+    p3 = host_plan(A3, N3)
+    assert p3.stats()["window_rows"] == 16
+    if p5.stats()["n_windows"] * p5.stats()["window_rows"] >= 64 * 16:
+        assert p5.stats()["window_rows"] == 128
