@@ -53,17 +53,18 @@ typedef struct {
 
 /* Planning options.  Obtain defaults with rsh_plan_opts_default, then override. */
 typedef struct {
-    int32_t window_rows;  /* W of Algorithm 1: 16, 32, 64 or 128.  Up to 64 a window is W/16 sub-windows of 16
-                             rows (one MFMA N-extent each) that share one condensed column space; the W/16
-                             waves of a workgroup share each staged B tile.  128 selects the panel form for
-                             tall windows (four row groups of 32 rows on v_mfma_f32_32x32x16_f16, entries
+    int32_t window_rows;  /* W of Algorithm 1: 16, 32, 64, 128 or 256.  Up to 64 a window is W/16 sub-windows of
+                             16 rows (one MFMA N-extent each) that share one condensed column space; the W/16
+                             waves of a workgroup share each staged B tile.  128 and 256 select the panel form
+                             for tall windows (W/32 row groups of 32 rows on v_mfma_f32_32x32x16_f16, entries
                              stored with their cell address instead of a bitmap; see rsh_plan_array).
                              0 (default) = choose: starting from 16, W doubles while merging neighbouring
                              windows (a sample of them) keeps the merged windows' distinct columns within
                              0.6 of the sum                                                           */
     int32_t tile_k;       /* K, condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16) or 32
                              (v_mfma_f32_16x16x32_f16); 0 (default) = 16 for 16-row windows, else 32;
-                             128-row windows always take 32 (two K steps of v_mfma_f32_32x32x16_f16)  */
+                             windows of 128 or 256 rows always take 32 (two K steps of
+                             v_mfma_f32_32x32x16_f16)                                                 */
     int32_t tau_nnz;      /* Algorithm 1 row-length threshold; -1 = estimate from the matrix     */
     int32_t tau_inc;      /* Algorithm 1 column-gain threshold; -1 = estimate                    */
     int32_t partition;    /* 0 = Algorithm 1 exactly as printed (contiguous windows, head-row test);
@@ -262,20 +263,24 @@ int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
  *   RSH_ARR_TILE_ITEM    uint32 [n_items*4]     {window, first tile, end tile, dst}: dst ==
  *                                               0xffffffff -> rows of C; else first scratch slot
  *                                               of a W-slot partial block
- * Panel form of the dense-fragment part (window_rows == 128; TILE_MASK, TILE_VAL_OFF and TILE_VAL are
- * then empty).  A window is four row groups of 32 rows; a fragment is 32 condensed columns = two K
- * steps of 16; the entries of (row group g, fragment t, K step h) form one unit, the 32 x 16 operand
- * of one v_mfma_f32_32x32x16_f16.  With t0 = WIN_TILE_OFF[w] and nt the window's fragment count, the
- * unit has index 8*t0 + (g*nt + (t - t0))*2 + h, so that the units of one row group are consecutive:
+ * Panel form of the dense-fragment part (window_rows == 128 or 256; TILE_MASK, TILE_VAL_OFF and
+ * TILE_VAL are then empty).  A window is G = W/32 row groups of 32 rows; a fragment is 32 condensed
+ * columns = two K steps of 16; the entries of (row group g, fragment t, K step h) form one unit, the
+ * 32 x 16 operand of one v_mfma_f32_32x32x16_f16.  With t0 = WIN_TILE_OFF[w] and nt the window's
+ * fragment count, the unit has index 2*G*t0 + (g*nt + (t - t0))*2 + h, so that the units of one row
+ * group are consecutive:
  *   RSH_ARR_PANEL_COL0   int32  [n_windows]     first column of a window whose condensed columns are
  *                                               one run of consecutive columns filling whole
  *                                               fragments (column ids are then computed), else -1
- *   RSH_ARR_PANEL_OFF    uint32 [8*n_tiles+1]   start of each unit's entries in PANEL_ENT
+ *   RSH_ARR_PANEL_OFF    uint32 [2*G*n_tiles+1] start of each unit's entries in PANEL_ENT, a multiple
+ *                                               of 4 (a lane fetches four entries with one load)
  *   RSH_ARR_PANEL_ENT    uint32 []              one word per stored entry: bits 0..15 the binary16
  *                                               value, bits 16..31 the byte address of its cell in
  *                                               the operand as the instruction holds it:
  *                                               ((r + 32*(k/8))*8 + k%8)*2 for row r of the group and
- *                                               column k (0..15) of the K step; ascending in a unit
+ *                                               column k (0..15) of the K step; ascending in a unit.
+ *                                               A unit is padded to a multiple of 4 words with words
+ *                                               whose address field is >= 1024 (no entry)
  * Irregular part (RS-Tile "residual part", Section 3.2):
  *   RSH_ARR_IRR_COL      int32  []              column ids, CSR order inside a row
  *   RSH_ARR_IRR_VAL      uint16 []              binary16 values, same order

@@ -71,6 +71,7 @@ int upload_plan(rsh_plan& p) {
     if ((rc = upload_array(h.panel_col0, &d.panel_col0))) return rc;
     if ((rc = upload_array(h.panel_off, &d.panel_off))) return rc;
     if ((rc = upload_array(h.panel_ent, &d.panel_ent))) return rc;
+    d.n_panel_ent = (uint32_t)h.panel_ent.size();
     if ((rc = upload_array(h.irr_col, &d.irr_col))) return rc;
     if ((rc = upload_array(h.irr_val, &d.irr_val))) return rc;
     if ((rc = upload_array(h.irr_wave, &d.irr_wave))) return rc;
@@ -133,8 +134,9 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     if (o.run_width != 0 && (o.run_width < N || o.run_width % 16 != 0 || o.run_width > 4096)) return RSH_ERR_BAD_OPTION;
     N = o.run_width != 0 ? o.run_width : auto_run_width(N);   // operands of another width are copied
     o.run_width = N;
-    if ((o.window_rows != 0 && o.window_rows != 16 && o.window_rows != 32 && o.window_rows != 64 && o.window_rows != 128) ||
-        (o.tile_k != 0 && o.tile_k != 16 && o.tile_k != 32) || (o.window_rows == 128 && o.tile_k == 16))
+    if ((o.window_rows != 0 && o.window_rows != 16 && o.window_rows != 32 && o.window_rows != 64 && o.window_rows != 128 &&
+         o.window_rows != 256) ||
+        (o.tile_k != 0 && o.tile_k != 16 && o.tile_k != 32) || (o.window_rows >= 128 && o.tile_k == 16))
         return RSH_ERR_BAD_OPTION;
     if (o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2) return RSH_ERR_BAD_OPTION;
     if (o.reorder < 0 || o.reorder > 3 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
@@ -215,7 +217,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
             o.window_rows = rsh::choose_window_rows(*csr, part);
             if (o.window_rows != rsh::kW) rsh::partition_rows(*csr, o, h.order, tau_nnz, tau_inc, part, threads);
         }
-        if (o.tile_k == 0 || o.window_rows == rsh::kPanelRows) o.tile_k = o.window_rows == rsh::kW ? 16 : 32;
+        if (o.tile_k == 0 || o.window_rows >= rsh::kPanelMinRows) o.tile_k = o.window_rows == rsh::kW ? 16 : 32;
         h.geo = rsh::make_geometry(N, o.window_rows, o.tile_k);
         h.opts = o;
         const double ms_partition = ms_since(t0);

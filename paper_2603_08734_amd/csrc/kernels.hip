@@ -690,17 +690,30 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 // ---------------------------------------------------------------------------
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-template <int NCH32>
+#ifdef RSH_PANEL_TRACE
+// developer build only: per wave, cycles spent between a round's barrier and the next (own work) and
+// waiting at the barrier
+__device__ unsigned long long g_panel_trace[4 * 4096];
+extern "C" int rsh_debug_panel_trace(unsigned long long* out) {
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_panel_trace), sizeof(g_panel_trace)) == hipSuccess ? 0 : 6;
+}
+#endif
+
+// NG = row groups (waves) per window: 4 (128 rows) or 8 (256 rows)
+template <int NCH32, int NG>
 struct PanelGeom {
     static constexpr int P = 32 * NCH32;                      // features per panel
+    static constexpr int THREADS = 64 * NG;
     static constexpr int TPR = P / 8;                         // 16-byte pieces per staged B row
     static constexpr int LDB = P >= 64 ? P + 32 : 32;         // LDS row stride in halves: rows 16 banks apart (mod 64)
     static constexpr int PIECES = kPanelK * TPR;              // pieces of one staged tile
-    static constexpr int NLD = (PIECES + 255) / 256;          // pieces per thread
-    static constexpr int TILE_HALVES = kPanelK * LDB;
-    static constexpr int LOOP_BYTES = 2 * TILE_HALVES * 2 + kPanelGroups * 2 * 512 * 2;   // two B tiles + the waves' operand tiles
+    static constexpr int NLD = (PIECES + THREADS - 1) / THREADS;   // pieces per thread
+    static constexpr int IDLE = NLD * THREADS - PIECES;       // threads without a piece (narrow panels) stage into spare space
+    static constexpr int TILE_HALVES = kPanelK * LDB + 8 * IDLE;
+    static constexpr int WAVE_A_BYTES = 2 * 1024 + 256;       // a wave's two operand tiles and a spare word per lane
+    static constexpr int LOOP_BYTES = 2 * TILE_HALVES * 2 + NG * WAVE_A_BYTES;   // two B tiles + the waves' operand tiles
     static constexpr int STAGE_STRIDE = 36;                   // floats per staged output row (32 + pad)
-    static constexpr int STAGE_BYTES = kPanelGroups * 32 * STAGE_STRIDE * 4;
+    static constexpr int STAGE_BYTES = NG * 32 * STAGE_STRIDE * 4;
     static constexpr int SMEM_BYTES = LOOP_BYTES > STAGE_BYTES ? LOOP_BYTES : STAGE_BYTES;
 };
 
@@ -711,21 +724,30 @@ __device__ __forceinline__ void panel_store(const OutFused& o, size_t row, int N
     __builtin_nontemporal_store(finish4(o, f, v), reinterpret_cast<uint2_t*>(o.C + row * N + f));
 }
 
-// R = rounds of 64 entries a unit may need (a plan-wide bound: 2, 4 or 8)
-template <int NCH32, int R, class OUT>
-__global__ __launch_bounds__(256) void rsh_panel_kernel(
+// R = 16-byte loads per lane (four entries each, 256 per wave) that cover the largest unit: 1 or 2
+template <int NCH32, int NG, int R, class OUT>
+__global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
     const uint4* __restrict__ items, XcdSplit xs, const int32_t* __restrict__ win_row,
     const uint32_t* __restrict__ win_tile_off, const int32_t* __restrict__ win_col0,
     const int32_t* __restrict__ tile_colid, const uint32_t* __restrict__ unit_off,
     const uint32_t* __restrict__ ent, const __half* __restrict__ B, const OUT out,
     float* __restrict__ scratch, int N, int feature0) {
-    using Gm = PanelGeom<NCH32>;
-    constexpr int P = Gm::P, TPR = Gm::TPR, LDB = Gm::LDB, NLD = Gm::NLD, KT = kPanelK;
-    constexpr int LB = 2;    // fragments ahead at which B rows are requested
-    constexpr int LA = 3;    // fragments ahead at which a wave's entries are requested
+    using Gm = PanelGeom<NCH32, NG>;
+    constexpr int P = Gm::P, TPR = Gm::TPR, LDB = Gm::LDB, NLD = Gm::NLD, KT = kPanelK, THREADS = Gm::THREADS;
+#ifndef RSH_PANEL_LB
+#define RSH_PANEL_LB 2
+#endif
+#ifndef RSH_PANEL_SKIP
+#define RSH_PANEL_SKIP 0   // developer timing builds only: 1 no scatter, 2 no B staging, 4 no MFMA, 8 no entry loads, 16 no B loads
+#endif
+#ifndef RSH_PANEL_LA
+#define RSH_PANEL_LA 5
+#endif
+    constexpr int LB = RSH_PANEL_LB;    // fragments ahead at which B rows are requested
+    constexpr int LA = RSH_PANEL_LA;    // fragments ahead at which a wave's entries are requested
     __shared__ __attribute__((aligned(16))) unsigned char smem[Gm::SMEM_BYTES];
     _Float16* const lds_b = reinterpret_cast<_Float16*>(smem);                                  // [2][KT * LDB]
-    _Float16* const lds_a = reinterpret_cast<_Float16*>(smem + 2 * Gm::TILE_HALVES * 2);        // [4 waves][2 K steps][512]
+    unsigned char* const lds_a = smem + 2 * Gm::TILE_HALVES * 2;                                // [4 waves][WAVE_A_BYTES]
 
     const int lane = threadIdx.x & 63;
     const int g = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // row group of this wave
@@ -743,7 +765,7 @@ __global__ __launch_bounds__(256) void rsh_panel_kernel(
     const int32_t col0 = win_col0[win];
     const uint32_t steps = t_end - t_begin;
     const int panel = feature0 + blockIdx.y * P;
-    const int row = win_row[(size_t)win * kPanelRows + g * 32 + (lane & 31)];   // lane n (and n + 32) <-> row n of the group
+    const int row = win_row[(size_t)win * (32 * NG) + g * 32 + (lane & 31)];   // lane n (and n + 32) <-> row n of the group
 
     float16_t acc[NCH32], acc2[NCH32];
 #pragma unroll
@@ -753,18 +775,17 @@ __global__ __launch_bounds__(256) void rsh_panel_kernel(
 
     if (steps > 0) {
         const uint32_t last = steps - 1;
-        // ---- staging of B rows: thread tix takes 16-byte piece j*256 + tix of the KT x TPR pieces ----
+        // ---- staging of B rows: thread tix takes 16-byte piece j*THREADS + tix of the KT x TPR pieces ----
         const int tix = threadIdx.x;
         int ld_row[NLD];
         uint32_t ld_lds[NLD], ld_byte[NLD];
-        bool ld_on[NLD];
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            const int piece = j * 256 + tix;
+            const int piece = j * THREADS + tix;
             ld_row[j] = (piece / TPR) & (KT - 1);
             const int cp = piece % TPR;
-            ld_on[j] = piece < Gm::PIECES;
-            ld_lds[j] = (uint32_t)(ld_row[j] * LDB + cp * 8);
+            // threads past the tile's pieces (narrow panels) stage what they loaded into spare space behind the tile
+            ld_lds[j] = piece < Gm::PIECES ? (uint32_t)(ld_row[j] * LDB + cp * 8) : (uint32_t)(KT * LDB + (piece - Gm::PIECES) * 8);
             // a piece past the last feature (partial last panel) reads the panel's first piece; its
             // products land in features that are never stored
             ld_byte[j] = panel + 8 * cp < N ? 16u * (uint32_t)cp : 0u;
@@ -772,60 +793,81 @@ __global__ __launch_bounds__(256) void rsh_panel_kernel(
         const char* Bbytes = reinterpret_cast<const char*>(B + panel);
         const uint32_t row_bytes = 2u * (uint32_t)N;
         const bool run = col0 >= 0;                                   // columns are col0, col0 + 1, ...: no ids to fetch
-        auto column_of = [&](uint32_t step, int j, int fetched) -> uint32_t {
-            return run ? (uint32_t)col0 + (t_begin - t0 + step) * KT + (uint32_t)ld_row[j] : (uint32_t)fetched;
-        };
-        auto fetch_colid = [&](uint32_t step, int j) -> int {
-            return run ? 0 : tile_colid[(size_t)(t_begin + min(step, last)) * KT + ld_row[j]];
-        };
-        // ---- this wave's entry stream ----
-        const uint32_t unit0 = 8u * t0 + ((uint32_t)g * nt + (t_begin - t0)) * 2u;
-        _Float16* const my_a = lds_a + g * 1024;
+        // ---- this wave's entry stream and operand tiles ----
+        const uint32_t unit0 = 2u * NG * t0 + ((uint32_t)g * nt + (t_begin - t0)) * 2u;
+        unsigned char* const my_a = lds_a + g * Gm::WAVE_A_BYTES;     // [0, 1024) K step 0, [1024, 2048) K step 1, then 256 spare bytes
+        const uint32_t spare = 2048u + 4u * (uint32_t)lane;           // where a lane without an entry writes
         const int g4 = lane >> 4, rr4 = (lane & 15) >> 2, ss4 = lane & 3;
         const int tr_off = (8 * (g4 >> 1) + rr4) * LDB + 16 * (g4 & 1) + 4 * ss4;
 
         uint4_t breg[4][NLD];
-        uint32_t areg[4][2][R];
-        uint32_t cnt_ring[4][2];
-        int cid_n[NLD];
-        uint32_t off_n[3];
+        uint4_t areg[8][2][R];
+        uint32_t cnt_ring[8][2];
+        int cid_ring[4][NLD];   // column ids of the rows a thread stages, by fragment mod 4 (gathered windows only)
 
-        auto load_offsets = [&](uint32_t step, uint32_t (&o)[3]) {
-            const uint32_t* p = unit_off + unit0 + 2u * min(step, last);
-            o[0] = p[0];
-            o[1] = p[1];
-            o[2] = p[2];
+        // Offsets of the units of eight fragments at a time: lane i < 17 holds unit_off[first unit + i].
+        // Fetched with a vector load one round of eight fragments ahead (a scalar load would have to be
+        // waited for at the next LDS wait: the two share a counter).  Past the item's last fragment
+        // the index stops at the end of its last unit, so later fragments have no entries.
+        auto request_offsets = [&](uint32_t first_step) -> uint32_t {
+            return unit_off[unit0 + min(2u * first_step + (uint32_t)(lane & 31), 2u * last + 2u)];
         };
-        auto issue_entries = [&](uint32_t step, const uint32_t (&o)[3], uint32_t (&a)[2][R], uint32_t (&cnt)[2]) {
-            const bool live = step < steps;
-            cnt[0] = live ? o[1] - o[0] : 0u;
-            cnt[1] = live ? o[2] - o[1] : 0u;
+        // Entries are fetched four per lane with 16-byte loads (few, wide requests: the vector memory
+        // path takes as long over a 4-byte load as over a 16-byte one).  Lanes past the unit's last
+        // quad repeat it -- the same cache line, no further traffic -- and scatter nothing.
+        auto issue_entries = [&](uint32_t o0, uint32_t o1, uint32_t o2, uint4_t (&a)[2][R], uint32_t (&cnt)[2]) {
+            cnt[0] = (o1 - o0) >> 2;   // quads
+            cnt[1] = (o2 - o1) >> 2;
+            const uint4_t* p0 = reinterpret_cast<const uint4_t*>(ent + o0);   // wave-uniform, 16-byte aligned
+            const uint4_t* p1 = reinterpret_cast<const uint4_t*>(ent + o1);
+            const uint32_t last0 = max(cnt[0], 1u) - 1u, last1 = max(cnt[1], 1u) - 1u;
+            if (RSH_PANEL_SKIP & 8) return;
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int q = 0; q < R; ++q) a[0][q] = p0[min((uint32_t)(64 * q + lane), last0)];
 #pragma unroll
-                for (int q = 0; q < R; ++q) a[h][q] = ent[o[h] + (uint32_t)(64 * q + lane)];   // unconditional: the stream is padded
+            for (int q = 0; q < R; ++q) a[1][q] = p1[min((uint32_t)(64 * q + lane), last1)];
+        };
+        // Column ids are requested a round before the rows they name and ahead of that round's other
+        // requests: the wait for them then leaves every later request in flight.
+        auto fetch_colids = [&](uint32_t step, int (&cid)[NLD]) {
+            if (!run) {
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) cid[j] = tile_colid[(size_t)(t_begin + min(step, last)) * KT + ld_row[j]];
+            }
         };
         auto issue_b = [&](uint32_t step, const int (&cid)[NLD], uint4_t (&b)[NLD]) {
-            const uint32_t sc = min(step, last);
+            const uint32_t first_col = (uint32_t)col0 + (t_begin - t0 + min(step, last)) * KT;
+            if (RSH_PANEL_SKIP & 16) return;
 #pragma unroll
-            for (int j = 0; j < NLD; ++j)
-                b[j] = *reinterpret_cast<const uint4_t*>(Bbytes + (column_of(sc, j, cid[j]) * row_bytes + ld_byte[j]));
+            for (int j = 0; j < NLD; ++j) {
+                const uint32_t c = run ? first_col + (uint32_t)ld_row[j] : (uint32_t)cid[j];
+                b[j] = *reinterpret_cast<const uint4_t*>(Bbytes + (c * row_bytes + ld_byte[j]));
+            }
         };
         auto stage_b = [&](const uint4_t (&b)[NLD], int buf) {
             _Float16* sb = lds_b + buf * Gm::TILE_HALVES;
+            if (RSH_PANEL_SKIP & 2) return;
 #pragma unroll
-            for (int j = 0; j < NLD; ++j)
-                if (ld_on[j]) *reinterpret_cast<uint4_t*>(sb + ld_lds[j]) = b[j];
+            for (int j = 0; j < NLD; ++j) *reinterpret_cast<uint4_t*>(sb + ld_lds[j]) = b[j];
         };
-        auto scatter = [&](const uint32_t (&a)[2][R], const uint32_t (&cnt)[2]) {
-            *reinterpret_cast<uint4_t*>(my_a + lane * 8) = (uint4_t){0u, 0u, 0u, 0u};
-            *reinterpret_cast<uint4_t*>(my_a + 512 + lane * 8) = (uint4_t){0u, 0u, 0u, 0u};
+        // Entries into the zeroed operand tiles.  No branches: a lane without a quad of the unit writes
+        // into its own spare word instead (as do the entries that pad a unit to a whole quad).
+        auto scatter = [&](const uint4_t (&a)[2][R], const uint32_t (&cnt)[2]) {
+            if (RSH_PANEL_SKIP & 1) return;
+            *reinterpret_cast<uint4_t*>(my_a + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
+            *reinterpret_cast<uint4_t*>(my_a + 1024 + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int q = 0; q < R; ++q)
-                    if ((uint32_t)(64 * q + lane) < cnt[h])
-                        *reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(my_a + 512 * h) + (a[h][q] >> 16)) = (uint16_t)a[h][q];
+                for (int q = 0; q < R; ++q) {
+                    const bool on = (uint32_t)(64 * q + lane) < cnt[h];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t w = a[h][q][i];
+                        const uint32_t at = on ? 1024u * h + (w >> 16) : spare;
+                        *reinterpret_cast<uint16_t*>(my_a + at) = (uint16_t)w;
+                    }
+                }
         };
         auto block_barrier = [&]() {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -834,41 +876,58 @@ __global__ __launch_bounds__(256) void rsh_panel_kernel(
         };
 
         // ---- prologue: entries of fragments 0 .. LA-1, B rows of fragments 0 .. LB-1 in flight; fragment 0 staged ----
+        uint32_t ovec;
         {
-            int cid0[NLD];
+            const uint32_t ov0 = request_offsets(0u);
+            ovec = request_offsets((uint32_t)LA);
 #pragma unroll
-            for (int d = 0; d < LB; ++d) {
+            for (int d = 0; d < LB + 1; ++d) fetch_colids((uint32_t)d, cid_ring[d & 3]);
 #pragma unroll
-                for (int j = 0; j < NLD; ++j) cid0[j] = fetch_colid((uint32_t)d, j);
-                issue_b((uint32_t)d, cid0, breg[d]);
-            }
+            for (int d = 0; d < LB; ++d) issue_b((uint32_t)d, cid_ring[d], breg[d]);
+            uint32_t o[2 * LA + 1];
 #pragma unroll
-            for (int j = 0; j < NLD; ++j) cid_n[j] = fetch_colid((uint32_t)LB, j);
+            for (int i = 0; i <= 2 * LA; ++i) o[i] = (uint32_t)__builtin_amdgcn_readlane((int)ov0, i);
 #pragma unroll
-            for (int d = 0; d < LA; ++d) {
-                uint32_t o[3];
-                load_offsets((uint32_t)d, o);
-                issue_entries((uint32_t)d, o, areg[d], cnt_ring[d]);
-            }
-            load_offsets((uint32_t)LA, off_n);
+            for (int d = 0; d < LA; ++d) issue_entries(o[2 * d], o[2 * d + 1], o[2 * d + 2], areg[d], cnt_ring[d]);
             stage_b(breg[0], 0);
             scatter(areg[0], cnt_ring[0]);
             block_barrier();
         }
 
-        for (uint32_t base = 0; base < steps; base += 4) {
+#ifdef RSH_PANEL_TRACE
+        unsigned long long tr_work = 0, tr_wait = 0, tr_mark = __builtin_amdgcn_s_memtime();
+        unsigned long long tr_p1 = 0, tr_p2 = 0;
+#define RSH_TRACE_POINT(acc_)                                                 \
+    {                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                    \
+        const unsigned long long tp_ = __builtin_amdgcn_s_memtime();          \
+        acc_ += tp_ - tr_last;                                                \
+        tr_last = tp_;                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                    \
+    }
+#else
+#define RSH_TRACE_POINT(acc_)
+#endif
+        for (uint32_t base = 0; base < steps; base += 8) {
+            uint32_t o[17];   // unit offsets of fragments base + LA .. base + LA + 7
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int i = 0; i < 17; ++i) o[i] = (uint32_t)__builtin_amdgcn_readlane((int)ovec, i);
+            ovec = request_offsets(base + 8u + (uint32_t)LA);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
                 const uint32_t s = base + (uint32_t)u;
                 // operands of fragment s (scattered during the previous round)
-                const half8_t a0 = *reinterpret_cast<const half8_t*>(my_a + lane * 8);
-                const half8_t a1 = *reinterpret_cast<const half8_t*>(my_a + 512 + lane * 8);
-                // requests: B rows of fragment s + LB (their column ids arrived a round ago), then the
-                // ids of fragment s + LB + 1, then this wave's entries of fragment s + LA
-                issue_b(s + LB, cid_n, breg[(u + LB) & 3]);
-#pragma unroll
-                for (int j = 0; j < NLD; ++j) cid_n[j] = fetch_colid(s + LB + 1, j);
-                issue_entries(s + LA, off_n, areg[(u + LA) & 3], cnt_ring[(u + LA) & 3]);
+                const half8_t a0 = *reinterpret_cast<const half8_t*>(my_a + lane * 16);
+                const half8_t a1 = *reinterpret_cast<const half8_t*>(my_a + 1024 + lane * 16);
+                // requests: the column ids of fragment s + LB + 1, the B rows of fragment s + LB (their
+                // ids were requested a round ago), this wave's entries of fragment s + LA
+                fetch_colids(s + LB + 1, cid_ring[(u + LB + 1) & 3]);
+                issue_b(s + LB, cid_ring[(u + LB) & 3], breg[(u + LB) & 3]);
+                issue_entries(o[2 * u], o[2 * u + 1], o[2 * u + 2], areg[(u + LA) & 7], cnt_ring[(u + LA) & 7]);
+#if defined(RSH_PANEL_TRACE) && RSH_PANEL_TRACE > 1
+                unsigned long long tr_last = tr_mark;
+                RSH_TRACE_POINT(tr_p1)
+#endif
                 // multiply fragment s out of LDS
                 const _Float16* sb = lds_b + (u & 1) * Gm::TILE_HALVES + tr_off;
 #pragma unroll
@@ -880,17 +939,32 @@ __global__ __launch_bounds__(256) void rsh_panel_kernel(
                         const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                             (short4_t __attribute__((address_space(3)))*)(sb + (16 * h + 4) * LDB + 32 * c)));
                         const half8_t b_frag = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        if (RSH_PANEL_SKIP & 4) {
+                            acc[c][0] += (float)b_frag[0] + (float)(h ? a1 : a0)[0];
+                            continue;
+                        }
                         acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b_frag, h ? a1 : a0, acc[c], 0, 0, 0);
                     }
+#if defined(RSH_PANEL_TRACE) && RSH_PANEL_TRACE > 1
+                RSH_TRACE_POINT(tr_p2)
+#endif
                 // fragment s + 1: B rows into the other buffer, entries into the operand tiles
                 stage_b(breg[(u + 1) & 3], (u + 1) & 1);
-                scatter(areg[(u + 1) & 3], cnt_ring[(u + 1) & 3]);
-                // scalar loads go last (an LDS wait also waits for them), then the round's barrier
-                __builtin_amdgcn_sched_barrier(0);
-                load_offsets(s + LA + 1, off_n);
+                scatter(areg[(u + 1) & 7], cnt_ring[(u + 1) & 7]);
+#ifdef RSH_PANEL_TRACE
+                {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+                    const unsigned long long t1 = __builtin_amdgcn_s_memtime();
+                    tr_work += t1 - tr_mark;
+                    block_barrier();
+                    tr_mark = __builtin_amdgcn_s_memtime();
+                    tr_wait += tr_mark - t1;
+                }
+#else
                 block_barrier();
+#endif
             }
-            if ((base & 31u) == 28u) {   // 32 fragments = 1024 condensed columns: second level
+            if ((base & 31u) == 24u) {   // 32 fragments = 1024 condensed columns: second level
 #pragma unroll
                 for (int c = 0; c < NCH32; ++c) {
                     acc2[c] += acc[c];
@@ -899,6 +973,14 @@ __global__ __launch_bounds__(256) void rsh_panel_kernel(
                 }
             }
         }
+#ifdef RSH_PANEL_TRACE
+        if (lane == 0 && item < 1024u) {
+            g_panel_trace[(item * 4 + g) * 4 + 0] = tr_work;
+            g_panel_trace[(item * 4 + g) * 4 + 1] = tr_wait;
+            g_panel_trace[(item * 4 + g) * 4 + 2] = steps | (tr_p1 << 20);
+            g_panel_trace[(item * 4 + g) * 4 + 3] = tr_p2;
+        }
+#endif
     }
 
     // ---- output: each wave's 32 rows x 32 features take a turn through LDS and leave as whole lines ----
@@ -1131,20 +1213,21 @@ static int launch_tile_nw(const DevicePlan& d, const void* B, const OUT& out, hi
 
 // Panels of 128 features in one launch; what remains (N not a multiple of 128) in a launch of its own
 // with a panel of 32, 64 or 128 features, the features past N masked.
-template <int NCH32, int R, class OUT>
+template <int NCH32, int NG, int R, class OUT>
 static void launch_panel_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
     uint32_t longest = 0;
     for (int x = 0; x < 8; ++x) longest = std::max(longest, d.tile_split.start[x + 1] - d.tile_split.start[x]);
-    hipLaunchKernelGGL((rsh_panel_kernel<NCH32, R, OUT>), dim3(8u * longest, (unsigned)panels), dim3(256), 0, st,
+    hipLaunchKernelGGL((rsh_panel_kernel<NCH32, NG, R, OUT>), dim3(8u * longest, (unsigned)panels), dim3(64 * NG), 0, st,
                        (const uint4*)d.tile_item, d.tile_split, d.win_row, d.win_tile_off, d.panel_col0, d.tile_colid,
                        d.panel_off, d.panel_ent, (const __half*)B, out, d.scratch, d.geo.N, feature0);
 }
 template <int NCH32, class OUT>
 static int launch_panel_r(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
-    switch (d.geo.panel_rounds) {
-        case 2: launch_panel_t<NCH32, 2>(d, B, out, st, feature0, panels); return RSH_OK;
-        case 4: launch_panel_t<NCH32, 4>(d, B, out, st, feature0, panels); return RSH_OK;
-        case 8: launch_panel_t<NCH32, 8>(d, B, out, st, feature0, panels); return RSH_OK;
+    switch (d.geo.panel_rounds * 16 + d.geo.panel_groups) {
+        case 16 + 4: launch_panel_t<NCH32, 4, 1>(d, B, out, st, feature0, panels); return RSH_OK;
+        case 32 + 4: launch_panel_t<NCH32, 4, 2>(d, B, out, st, feature0, panels); return RSH_OK;
+        case 16 + 8: launch_panel_t<NCH32, 8, 1>(d, B, out, st, feature0, panels); return RSH_OK;
+        case 32 + 8: launch_panel_t<NCH32, 8, 2>(d, B, out, st, feature0, panels); return RSH_OK;
         default: return RSH_ERR_BAD_OPTION;
     }
 }

@@ -21,6 +21,7 @@ struct DevicePlan {
     int32_t* panel_col0 = nullptr;
     uint32_t* panel_off = nullptr;
     uint32_t* panel_ent = nullptr;
+    uint32_t n_panel_ent = 0;   // words in panel_ent (tail padding included)
     int32_t* irr_col = nullptr;
     uint16_t* irr_val = nullptr;
     uint32_t* irr_wave = nullptr;

@@ -8,11 +8,10 @@
 namespace rsh {
 
 constexpr int kW = 16;  // rows per sub-window (MFMA N extent); a window is nw of them
-constexpr int kMaxWindowRows = 128;
-// Tall windows ("panel" form, window_rows == 128): four row groups of 32 rows (the N extent of
-// v_mfma_f32_32x32x16_f16), fragments of 32 condensed columns = two MFMA K steps of 16.
-constexpr int kPanelRows = 128;
-constexpr int kPanelGroups = 4;
+constexpr int kMaxWindowRows = 256;
+// Tall windows ("panel" form, window_rows == 128 or 256): four or eight row groups of 32 rows (the N
+// extent of v_mfma_f32_32x32x16_f16), fragments of 32 condensed columns = two MFMA K steps of 16.
+constexpr int kPanelMinRows = 128;
 constexpr int kPanelK = 32;
 constexpr uint32_t kNoDst = 0xffffffffu;
 // irregular wave descriptor {start, count, dst, info}; info = kind | flags | L << 8 | R << 16
@@ -34,8 +33,9 @@ struct Geometry {
     int nw = 1;         // sub-windows (waves) per window = win_rows / 16
     int tile_k = 16;    // condensed columns per fragment: 16 (v_mfma_f32_16x16x16_f16) or 32 (..._16x16x32_f16)
     int cpl = 4;        // cells per MFMA lane = bitmap words per sub-fragment = tile_k / 4
-    int panel = 0;      // 1 = tall windows in the panel form (win_rows == 128, tile_k == 32)
-    int panel_rounds = 0; // panel form: ceil(largest number of entries of a 32 x 16 unit / 64), rounded up to 2, 4 or 8
+    int panel = 0;      // 1 = tall windows in the panel form (win_rows == 128 or 256, tile_k == 32)
+    int panel_groups = 0; // panel form: row groups of 32 rows per window = win_rows / 32
+    int panel_rounds = 0; // panel form: 16-byte loads per lane that cover the largest unit (256 entries each): 1 or 2
 };
 Geometry make_geometry(int N, int window_rows, int tile_k);
 
@@ -62,7 +62,7 @@ struct HostPlan {
     std::vector<uint32_t> tile_item;  // 4 per item
     // panel form of the dense-fragment part (replaces tile_mask / tile_val_off / tile_val)
     std::vector<int32_t> panel_col0;  // per window: first column if its condensed columns are one run, else -1
-    std::vector<uint32_t> panel_off;  // per 32 x 16 unit: start of its entries (one more at the end)
+    std::vector<uint32_t> panel_off;  // per 32 x 16 unit: start of its entries, a multiple of 4 (one more at the end)
     std::vector<uint32_t> panel_ent;  // (byte address in the operand tile << 16) | binary16 bits
     // irregular part
     std::vector<int32_t> irr_col;

@@ -40,7 +40,8 @@ Geometry make_geometry(int N, int window_rows, int tile_k) {
     g.tile_panel = 16;
     while (g.tile_panel < 256 && g.tile_panel * 2 <= N) g.tile_panel *= 2;   // widest panel of the tile kernel
     g.tile_nch = g.tile_panel / 16;
-    g.panel = window_rows == kPanelRows ? 1 : 0;
+    g.panel = window_rows >= kPanelMinRows ? 1 : 0;
+    g.panel_groups = g.panel ? window_rows / 32 : 0;
     return g;
 }
 
@@ -114,33 +115,34 @@ static int64_t union_size(const rsh_csr_t& a, const int32_t* rows, int n, std::v
 
 // Sampled test of whether taller windows pay.  Taller windows share one staged B tile among
 // more MFMA waves, which helps only when the merged windows name mostly the same columns.  Up
-// to 512 groups of eight consecutive 16-row windows are measured: distinct columns of the single
-// windows (u[0]), of the pairs (u[1]), of the groups of four (u[2]) and of the whole group (u[3]).
+// to 512 groups of sixteen consecutive 16-row windows are measured: distinct columns of the single
+// windows (u[0]), of the pairs (u[1]), of the groups of four (u[2]), eight (u[3]) and sixteen (u[4]).
 // The height doubles while the merged windows keep within 0.6 of the columns of their parts.
 int choose_window_rows(const rsh_csr_t& a, const Partition& part16) {
     const int64_t n_win = (int64_t)part16.win_row.size() / kW;
     if (n_win < 64) return kW;
-    const int64_t n_groups = n_win / 8, n_samples = std::min<int64_t>(512, n_groups);
+    constexpr int kLevels = 5, kSpan = 16;
+    const int64_t n_groups = n_win / kSpan, n_samples = std::min<int64_t>(512, n_groups);
     // seen[level][c] = last (sample, unit) stamp under which column c was counted at that merge level
-    std::vector<int64_t> seen[4];
+    std::vector<int64_t> seen[kLevels];
     for (auto& v : seen) v.assign((size_t)a.n_cols, -1);
-    int64_t u[4] = {0, 0, 0, 0};
+    int64_t u[kLevels] = {0, 0, 0, 0, 0};
     for (int64_t s = 0; s < n_samples; ++s) {
-        const int32_t* rows = &part16.win_row[(size_t)((s * n_groups / n_samples) * 8 * kW)];
-        for (int i = 0; i < 8 * kW; ++i) {
+        const int32_t* rows = &part16.win_row[(size_t)((s * n_groups / n_samples) * kSpan * kW)];
+        for (int i = 0; i < kSpan * kW; ++i) {
             const int32_t r = rows[i];
             if (r < 0) continue;
             for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
                 const size_t c = (size_t)a.col_idx[p];
-                for (int level = 0; level < 4; ++level) {
-                    const int64_t stamp = ((8 * s + i / kW) >> level);
+                for (int level = 0; level < kLevels; ++level) {
+                    const int64_t stamp = ((kSpan * s + i / kW) >> level);
                     if (seen[level][c] != stamp) seen[level][c] = stamp, ++u[level];
                 }
             }
         }
     }
     int rows = kW;
-    for (int level = 1; level < 4 && u[level] * 10 <= u[level - 1] * 6; ++level) rows *= 2;
+    for (int level = 1; level < kLevels && u[level] * 10 <= u[level - 1] * 6; ++level) rows *= 2;
     return rows;
 }
 
@@ -317,7 +319,7 @@ XcdSplit split_by_cost(const std::vector<uint32_t>& cost) {
 static inline uint32_t round_up_to(uint32_t x, uint32_t m) { return (x + m - 1u) / m * m; }   // m = 4 or 8
 
 struct WinEntry {
-    uint64_t key;  // col << 7 | window row
+    uint64_t key;  // col << 8 | window row
     uint16_t val;
 };
 
@@ -327,7 +329,7 @@ static void gather_window(const rsh_csr_t& a, const int32_t* rows, int W, std::v
     for (int r = 0; r < W; ++r) {
         if (rows[r] < 0) continue;
         for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p)
-            ent.push_back({((uint64_t)(uint32_t)a.col_idx[p] << 7) | (uint64_t)r, a.val_f16[p]});
+            ent.push_back({((uint64_t)(uint32_t)a.col_idx[p] << 8) | (uint64_t)r, a.val_f16[p]});
     }
     std::sort(ent.begin(), ent.end(), [](const WinEntry& x, const WinEntry& y) { return x.key < y.key; });
 }
@@ -409,30 +411,48 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
 // the instruction wants it in registers (lane = row + 32 * (k / 8), element k % 8, 16 bytes per lane):
 // the kernel scatters a unit's entries into a zeroed 1 KB tile and reads the operand back with one
 // 16-byte read per lane, so the work per unit grows with its entries, not with its 512 cells (the
-// bitmap form expands cell by cell).  Units are stored row group by row group, so that the stream
-// a wave reads is contiguous: unit (g, t, h) of window w is 8 * first_fragment(w) +
+// bitmap form expands cell by cell).  A unit is padded to a multiple of four entries (one 16-byte
+// load per lane fetches four); padding entries carry an address past the tile (>= 1024) that the
+// kernel's scatter sends to a spare word.  Units are stored row group by row group, so that the
+// stream a wave reads is contiguous: unit (g, t, h) of window w is 8 * first_fragment(w) +
 // (g * fragments(w) + (t - first_fragment(w))) * 2 + h.
 // ---------------------------------------------------------------------------
+static inline uint32_t panel_unit_of(uint32_t row, uint32_t u, uint32_t nt) {
+    return ((row / 32) * nt + u / kPanelK) * 2 + (u % kPanelK) / 16;
+}
+
 static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads,
                               int64_t* sum_cols, int64_t* nnz_tile) {
-    constexpr int W = kPanelRows, G = kPanelGroups;
+    const int W = plan.geo.win_rows, G = plan.geo.panel_groups;
     constexpr uint32_t K = kPanelK;
     const int64_t n_win = (int64_t)part.win_row.size() / W;
-    // pass 1: fragments and entries per window
+    // pass 1: fragments and padded entries per window
     std::vector<uint32_t> win_tiles((size_t)n_win);
-    std::vector<uint64_t> win_ent((size_t)n_win);
+    std::vector<uint64_t> win_ent((size_t)n_win), win_real((size_t)n_win);
     std::vector<int64_t> win_cols((size_t)n_win);
     parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
         std::vector<WinEntry> ent;
+        std::vector<uint32_t> cnt;
         for (int64_t w = b; w < e; ++w) {
             gather_window(a, &part.win_row[w * W], W, ent);
             int64_t u = 0;
             uint64_t prev_col = ~0ull;
             for (const WinEntry& x : ent)
-                if ((x.key >> 7) != prev_col) prev_col = x.key >> 7, ++u;
-            win_cols[w] = u;
-            win_tiles[w] = (uint32_t)((u + K - 1) / K);
-            win_ent[w] = ent.size();
+                if ((x.key >> 8) != prev_col) prev_col = x.key >> 8, ++u;
+            const uint32_t nt = (uint32_t)((u + K - 1) / K);
+            cnt.assign((size_t)nt * 2 * G, 0);
+            u = -1;
+            prev_col = ~0ull;
+            for (const WinEntry& x : ent) {
+                if ((x.key >> 8) != prev_col) prev_col = x.key >> 8, ++u;
+                ++cnt[panel_unit_of((uint32_t)(x.key & 255), (uint32_t)u, nt)];
+            }
+            uint64_t padded = 0;
+            for (uint32_t c : cnt) padded += (c + 3u) & ~3u;
+            win_cols[w] = u + 1;
+            win_tiles[w] = nt;
+            win_real[w] = ent.size();
+            win_ent[w] = padded;
         }
     });
     plan.win_tile_off.assign((size_t)n_win + 1, 0);
@@ -443,13 +463,14 @@ static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPla
         plan.win_tile_off[w + 1] = (uint32_t)t;
         win_ent_off[w + 1] = win_ent_off[w] + win_ent[w];
         *sum_cols += win_cols[w];
+        *nnz_tile += (int64_t)win_real[w];
     }
     if (win_ent_off[n_win] >= (1ull << 31)) return RSH_ERR_TOO_LARGE;
     const size_t n_tiles = plan.win_tile_off[n_win], n_units = n_tiles * 2 * G;
     plan.tile_colid.assign(n_tiles * K, 0);
     plan.panel_col0.assign((size_t)n_win, -1);
     plan.panel_off.assign(n_units + 1, 0);
-    plan.panel_ent.assign((size_t)win_ent_off[n_win] + 64 * 8, 0);   // tail pad: lanes read whole rounds of 64
+    plan.panel_ent.assign((size_t)win_ent_off[n_win] + 512, 0);   // tail pad: a lane may read the quad after an empty unit
     plan.tile_mask.clear();
     plan.tile_val_off.clear();
     plan.tile_val.clear();
@@ -457,25 +478,25 @@ static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPla
     std::vector<uint32_t> win_max_unit((size_t)n_win, 0);
     parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
         std::vector<WinEntry> ent;
-        std::vector<uint32_t> unit_of, cnt;
+        std::vector<uint32_t> unit_of, start, fill;
         for (int64_t w = b; w < e; ++w) {
             gather_window(a, &part.win_row[w * W], W, ent);
             const uint32_t t0 = plan.win_tile_off[w], nt = plan.win_tile_off[w + 1] - t0;
             if (nt == 0) continue;
+            const size_t nu = (size_t)nt * 2 * G;
             unit_of.resize(ent.size());
-            cnt.assign((size_t)nt * 2 * G + 1, 0);
+            start.assign(nu + 1, 0);
             int64_t u = -1;
             uint64_t prev_col = ~0ull;
             for (size_t i = 0; i < ent.size(); ++i) {
-                const uint64_t c = ent[i].key >> 7;
+                const uint64_t c = ent[i].key >> 8;
                 if (c != prev_col) {
                     prev_col = c;
                     ++u;
                     plan.tile_colid[(size_t)t0 * K + (size_t)u] = (int32_t)c;
                 }
-                const uint32_t t = (uint32_t)u / K, k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 127);
-                unit_of[i] = ((r / 32) * nt + t) * 2 + k / 16;
-                ++cnt[unit_of[i] + 1];
+                unit_of[i] = panel_unit_of((uint32_t)(ent[i].key & 255), (uint32_t)u, nt);
+                ++start[unit_of[i] + 1];
             }
             const int64_t n_u = u + 1;
             for (int64_t k = n_u; k < (int64_t)nt * K; ++k)   // padding columns repeat the last valid one
@@ -484,36 +505,37 @@ static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPla
             if (n_u == (int64_t)nt * K && plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)] - plan.tile_colid[(size_t)t0 * K] == n_u - 1)
                 plan.panel_col0[(size_t)w] = plan.tile_colid[(size_t)t0 * K];
             uint32_t most = 0;
-            for (size_t q = 1; q < cnt.size(); ++q) {
-                most = std::max(most, cnt[q]);
-                cnt[q] += cnt[q - 1];
+            for (size_t q = 1; q <= nu; ++q) {   // start[q] = padded entries of units before q
+                const uint32_t padded = (start[q] + 3u) & ~3u;
+                most = std::max(most, padded);
+                start[q] = start[q - 1] + padded;
             }
             win_max_unit[(size_t)w] = most;
             const size_t ub = (size_t)t0 * 2 * G;
-            for (size_t q = 0; q + 1 < cnt.size(); ++q) plan.panel_off[ub + q] = (uint32_t)(win_ent_off[w] + cnt[q]);
+            for (size_t q = 0; q < nu; ++q) plan.panel_off[ub + q] = (uint32_t)(win_ent_off[w] + start[q]);
             // entries arrive sorted by (column, row); inside a unit they are stored by cell address
             uint32_t* out = &plan.panel_ent[(size_t)win_ent_off[w]];
+            fill.assign(start.begin(), start.end() - 1);
             u = -1;
             prev_col = ~0ull;
             for (size_t i = 0; i < ent.size(); ++i) {
-                if ((ent[i].key >> 7) != prev_col) prev_col = ent[i].key >> 7, ++u;
-                const uint32_t k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 127);
+                if ((ent[i].key >> 8) != prev_col) prev_col = ent[i].key >> 8, ++u;
+                const uint32_t k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 255);
                 const uint32_t lane = (r % 32) + 32 * ((k % 16) / 8), addr = (lane * 8 + k % 8) * 2;
-                out[cnt[unit_of[i]]++] = (addr << 16) | ent[i].val;
+                out[fill[unit_of[i]]++] = (addr << 16) | ent[i].val;
             }
-            // cnt[q] is now the end of unit q
-            for (size_t q = 0; q + 1 < cnt.size(); ++q) {
-                uint32_t* ub_ = out + (q ? cnt[q - 1] : 0u);
-                std::sort(ub_, out + cnt[q]);
+            for (size_t q = 0; q < nu; ++q) {
+                std::sort(out + start[q], out + fill[q]);
+                // padding: address 1024 * (2 - h) + 4 * j lands in the wave's spare words behind its two tiles
+                const uint32_t h = (uint32_t)(q & 1);
+                for (uint32_t j = 0; fill[q] < start[q + 1]; ++j) out[fill[q]++] = (1024u * (2u - h) + 4u * j) << 16;
             }
         }
     });
     plan.panel_off[n_units] = (uint32_t)win_ent_off[n_win];
     uint32_t most = 0;
     for (uint32_t m : win_max_unit) most = std::max(most, m);
-    const int rounds = (int)((most + 63) / 64);
-    plan.geo.panel_rounds = rounds <= 2 ? 2 : rounds <= 4 ? 4 : 8;
-    *nnz_tile = (int64_t)win_ent_off[n_win];
+    plan.geo.panel_rounds = most <= 256 ? 1 : 2;   // 16-byte loads per lane that cover the largest unit
     return RSH_OK;
 }
 
@@ -544,13 +566,13 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 cnt.clear();
                 uint64_t prev_col = ~0ull;
                 for (const WinEntry& x : ent) {
-                    const uint64_t c = x.key >> 7;
+                    const uint64_t c = x.key >> 8;
                     if (c != prev_col) {
                         prev_col = c;
                         if (u % K == 0) cnt.insert(cnt.end(), (size_t)NW, 0u);
                         ++u;
                     }
-                    ++cnt[cnt.size() - (size_t)NW + (size_t)((x.key & 127) >> 4)];
+                    ++cnt[cnt.size() - (size_t)NW + (size_t)((x.key & 255) >> 4)];
                 }
                 uint32_t v = 0;
                 for (uint32_t c : cnt) v += round_up_to(c, CPL);
@@ -590,14 +612,14 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 int64_t u = -1;
                 uint64_t prev_col = ~0ull;
                 for (size_t i = 0; i < ent.size(); ++i) {
-                    const uint64_t c = ent[i].key >> 7;
+                    const uint64_t c = ent[i].key >> 8;
                     if (c != prev_col) {
                         prev_col = c;
                         ++u;
                         plan.tile_colid[(size_t)t0 * K + (size_t)u] = (int32_t)c;
                     }
                     ucol[i] = (uint32_t)u;
-                    const uint32_t t = (uint32_t)u / K, k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 127);
+                    const uint32_t t = (uint32_t)u / K, k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 255);
                     plan.tile_mask[((size_t)(t0 + t) * NW + (r >> 4)) * CPL + (k % CPL)] |= 1ull << ((k / CPL) * 16 + (r & 15));
                 }
                 // padding columns of the last fragment repeat its last valid column
@@ -616,7 +638,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 }
                 // values: position = (entries of lower lanes) + (entries of this lane in lower words)
                 for (size_t i = 0; i < ent.size(); ++i) {
-                    const uint32_t t = ucol[i] / K, k = ucol[i] % K, r = (uint32_t)(ent[i].key & 127);
+                    const uint32_t t = ucol[i] / K, k = ucol[i] % K, r = (uint32_t)(ent[i].key & 255);
                     const uint32_t lane = (k / CPL) * 16 + (r & 15), word = k % CPL;
                     const size_t sub = (size_t)(t0 + t) * NW + (r >> 4);
                     const uint64_t* m = &plan.tile_mask[sub * CPL];
@@ -638,8 +660,10 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     if (t_max <= 0 && geo.panel) {
         // Tall windows: a workgroup sums an item's fragments in two levels (every 1024 condensed
         // columns the running sums are added to a second set), so an item may be long; windows are
-        // only cut to hand every compute unit about two workgroups, never below 1024 columns.
-        t_max = std::max<int64_t>(1024 / kPanelK, (n_tiles + 511) / 512);
+        // only cut to hand every compute unit the workgroups it can hold (two of 128 rows, one of
+        // 256), never below 1024 columns.
+        const int64_t target_items = geo.win_rows >= 256 ? 256 : 512;
+        t_max = std::max<int64_t>(1024 / kPanelK, (n_tiles + target_items - 1) / target_items);
     } else if (t_max <= 0) {
         int64_t per = (n_tiles + 4095) / 4096, p2 = 1;
         while (p2 < per) p2 <<= 1;
@@ -993,14 +1017,15 @@ int decode_plan(const HostPlan& p, int64_t* row_ptr, int32_t* col_idx, uint16_t*
     const int64_t n_win = (int64_t)p.win_row.size() / W;
     for (int64_t w = 0; w < n_win && p.geo.panel; ++w) {
         const uint32_t t0 = p.win_tile_off[w], nt = p.win_tile_off[w + 1] - t0;
-        for (uint32_t g = 0; g < (uint32_t)kPanelGroups; ++g)
+        for (uint32_t g = 0; g < (uint32_t)p.geo.panel_groups; ++g)
             for (uint32_t t = 0; t < nt; ++t)
                 for (uint32_t h = 0; h < 2; ++h) {
-                    const size_t unit = (size_t)t0 * 2 * kPanelGroups + ((size_t)g * nt + t) * 2 + h;
+                    const size_t unit = (size_t)t0 * 2 * p.geo.panel_groups + ((size_t)g * nt + t) * 2 + h;
                     for (uint32_t q = p.panel_off[unit]; q < p.panel_off[unit + 1]; ++q) {
                         const uint32_t addr = p.panel_ent[q] >> 16, lane = addr / 16, k = h * 16 + (lane / 32) * 8 + (addr % 16) / 2;
+                        if (addr >= 1024) continue;   // padding of the unit to four entries
                         const int32_t row = p.win_row[(size_t)w * W + g * 32 + lane % 32];
-                        if (row < 0 || addr >= 1024 || (addr & 1)) return RSH_ERR_INVALID_CSR;
+                        if (row < 0 || (addr & 1)) return RSH_ERR_INVALID_CSR;
                         ent.push_back({row, p.tile_colid[(size_t)(t0 + t) * K + k], (uint16_t)(p.panel_ent[q] & 0xffffu), 0});
                     }
                 }

@@ -17,35 +17,39 @@ numpy, following only the layout documented in the public header:
   the row being dst itself or, when info has bit 2 set, the row whose combine entry
   (row, first slot, parts, stride) covers scratch slot dst; kind 2 -- no entries.
 
-Panel form (window_rows == 128): a window is four row groups of 32 rows, a fragment is 32 condensed
-columns = two K steps of 16; the entries of (row group g, fragment t, K step h) of window w are the
-words panel_ent[panel_off[u] .. panel_off[u+1]) with u = 8 * t0 + (g * nt + (t - t0)) * 2 + h
+Panel form (window_rows == 128 or 256): a window is G = 4 or 8 row groups of 32 rows, a fragment is 32
+condensed columns = two K steps of 16; the entries of (row group g, fragment t, K step h) of window w
+are the words panel_ent[panel_off[u] .. panel_off[u+1]) with u = 2 * G * t0 + (g * nt + (t - t0)) * 2 + h
 (t0 = win_tile_off[w], nt = the window's fragment count); a word is value bits | address << 16 with
-address = ((r + 32 * (k // 8)) * 8 + k % 8) * 2 for row r of the group and column k of the K step.
+address = ((r + 32 * (k // 8)) * 8 + k % 8) * 2 for row r of the group and column k of the K step;
+units start at multiples of four words and are padded with words whose address is >= 1024.
 """
 from __future__ import annotations
 
 import numpy as np
 
 
-def panel_entries(win_row, win_tile_off, tile_colid, panel_off, panel_ent):
+def panel_entries(win_row, win_tile_off, tile_colid, panel_off, panel_ent, window_rows=128):
     """(rows, cols, value bits) of the dense-fragment part of a plan in the panel form."""
     rows, cols, vals = [], [], []
-    n_win = len(win_row) // 128
+    G = window_rows // 32
+    n_win = len(win_row) // window_rows
     for w in range(n_win):
         t0, t1 = int(win_tile_off[w]), int(win_tile_off[w + 1])
         nt = t1 - t0
-        for g in range(4):
+        for g in range(G):
             for t in range(nt):
                 for h in range(2):
-                    u = 8 * t0 + (g * nt + t) * 2 + h
+                    u = 2 * G * t0 + (g * nt + t) * 2 + h
                     for q in range(int(panel_off[u]), int(panel_off[u + 1])):
                         word = int(panel_ent[q])
                         addr = word >> 16
-                        assert addr % 2 == 0 and addr < 1024
+                        if addr >= 1024:              # padding of the unit to four words
+                            continue
+                        assert addr % 2 == 0
                         lane, j = addr // 16, (addr % 16) // 2
                         r, k = lane % 32, 16 * h + 8 * (lane // 32) + j
-                        row = int(win_row[128 * w + 32 * g + r])
+                        row = int(win_row[window_rows * w + 32 * g + r])
                         assert row >= 0, "an entry in an absent window row"
                         rows.append(row)
                         cols.append(int(tile_colid[32 * (t0 + t) + k]))
@@ -56,8 +60,8 @@ def panel_entries(win_row, win_tile_off, tile_colid, panel_off, panel_ent):
 def entries_from_arrays(win_row, win_tile_off, tile_colid, tile_mask, tile_val_off, tile_val,
                         irr_col, irr_val, irr_wave, irr_row, combine, n_scratch_slots, window_rows=16, tile_k=16):
     rows, cols, vals, paths = [], [], [], []
-    if window_rows == 128:          # panel form: the caller passes (panel_off, panel_ent) in place of the bitmap arrays
-        rows, cols, vals = panel_entries(win_row, win_tile_off, tile_colid, tile_mask, tile_val)
+    if window_rows >= 128:          # panel form: the caller passes (panel_off, panel_ent) in place of the bitmap arrays
+        rows, cols, vals = panel_entries(win_row, win_tile_off, tile_colid, tile_mask, tile_val, window_rows)
         paths = [0] * len(rows)
         win_row = []
     W, NW = window_rows, window_rows // 16

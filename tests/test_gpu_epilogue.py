@@ -77,7 +77,7 @@ def test_reduced_configs_all_routings(k, mode, epi):
 
 
 @pytest.mark.parametrize("N", [16, 32, 48, 64, 96, 128, 256, 512, 1024])
-@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "w64_all_tile", "w32_all_tile", "k32_w64_all_tile", "w128_all_tile"])
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "w64_all_tile", "w32_all_tile", "k32_w64_all_tile", "w128_all_tile", "w256_split"])
 def test_feature_widths(N, mode):
     A, _, _ = make_config(3, small=True)
     B = dense_B(A.n_cols, N, "normal", seed=N)

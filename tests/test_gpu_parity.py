@@ -59,6 +59,8 @@ OPTION_SETS = {
     "w128": dict(window_rows=128),
     "w128_all_tile": dict(window_rows=128, force_path=2),
     "w128_split": dict(window_rows=128, force_path=2, max_tiles_per_item=3),
+    "w256_all_tile": dict(window_rows=256, force_path=2),
+    "w256_split": dict(window_rows=256, force_path=2, max_tiles_per_item=3),
     "all_irregular": dict(force_path=1),
     "all_tile": dict(force_path=2),
     "alg1_literal": dict(partition=0),
@@ -81,7 +83,7 @@ def test_reduced_configs_all_routings(k, mode):
 
 
 @pytest.mark.parametrize("N", [16, 32, 48, 64, 96, 128, 256, 512, 1024])
-@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "w64_all_tile", "w32_all_tile", "w128_all_tile", "w128_split"])
+@pytest.mark.parametrize("mode", ["hybrid", "all_irregular", "all_tile", "w64_all_tile", "w32_all_tile", "w128_all_tile", "w128_split", "w256_all_tile"])
 def test_feature_widths(N, mode):
     A, _, _ = make_config(3, small=True)
     B = dense_B(A.n_cols, N, "normal", seed=N)
@@ -120,7 +122,7 @@ def edge_matrices():
 
 
 @pytest.mark.parametrize("mode", ["hybrid", "no_reorder", "all_irregular", "all_tile", "alg1_literal", "tiny_items", "tiny_slices",
-                                  "w64_all_tile", "w32_all_tile", "w128_all_tile", "w128_split"])
+                                  "w64_all_tile", "w32_all_tile", "w128_all_tile", "w128_split", "w256_split"])
 @pytest.mark.parametrize("name", list(edge_matrices()))
 def test_edge_cases(name, mode):
     A = edge_matrices()[name]
@@ -190,7 +192,7 @@ FULL_SIZE_CASES = [
     (4, 0, dict(reorder=2, window_rows=32, tile_k=16)),                               # tree walk only, two waves per window
     (5, 0, dict(window_rows=16, tile_k=32, max_tiles_per_item=7)),                    # many partial blocks per window
     (5, 0, dict(window_rows=64)),                                                     # the bitmap form on the workload whose default is the panel form
-    (5, 0, dict(window_rows=128, max_tiles_per_item=40)),                             # panel form, seven partial blocks per window
+    (5, 0, dict(window_rows=128, max_tiles_per_item=40)),                             # panel form with 128-row windows, seven partial blocks per window
     (3, 0, dict(window_rows=128)),                                                    # panel form with gathered (not consecutive) columns
     (4, 208, dict(window_rows=128)),                                                  # panel form: a full feature panel and a masked one
     (2, 160, dict(reorder=0)),                                                        # a full and a partial panel in the irregular kernel
@@ -286,13 +288,13 @@ def test_random_matrices_with_random_options():
         r, c = np.nonzero(mask)
         A = from_coo(r, c, rng.standard_normal(r.size), n_rows, n_cols)
         N = int(rng.choice([16, 32, 64, 80, 100, 128, 160, 256]))
-        opts = dict(window_rows=int(rng.choice([16, 32, 64, 128])), tile_k=int(rng.choice([16, 32])), partition=int(rng.integers(0, 2)),
+        opts = dict(window_rows=int(rng.choice([16, 32, 64, 128, 256])), tile_k=int(rng.choice([16, 32])), partition=int(rng.integers(0, 2)),
                     reorder=int(rng.integers(0, 2)), force_path=int(rng.choice([0, 0, 1, 2])),
                     max_tiles_per_item=int(rng.choice([0, 1, 4])), max_nnz_per_slice=int(rng.choice([0, 20, 70])),
                     xcd_partition_nnz=int(rng.choice([0, -1, 30])), hub_windows=int(rng.integers(0, 2)),
                     long_row_nnz=int(rng.choice([0, 10])), min_reuse=float(rng.choice([0.0, 1.25, 2.5])))
-        if opts["window_rows"] == 128:
-            opts["tile_k"] = 0                                    # 128-row windows have one fragment width
+        if opts["window_rows"] >= 128:
+            opts["tile_k"] = 0                                    # tall windows have one fragment width
         B = dense_B(n_cols, N, "normal", seed=case)
         print(f"case random={case} shape=({n_rows},{n_cols}) nnz={A.nnz} N={N} opts={opts}", flush=True)
         (C,), _ = gpu_spmm(A, B, N, **opts)
@@ -489,6 +491,7 @@ SUBNORMAL_MODES = {
     "all_tile_k32": dict(force_path=2, tile_k=32),
     "all_tile_w64": dict(force_path=2, window_rows=64, tile_k=32, max_tiles_per_item=3),
     "all_tile_w128": dict(force_path=2, window_rows=128, max_tiles_per_item=5),
+    "all_tile_w256": dict(force_path=2, window_rows=256),
     "all_irregular": dict(force_path=1, xcd_partition_nnz=150, max_nnz_per_slice=96),   # short rows, slices, column-group pieces
     "hybrid": dict(),
 }
@@ -532,7 +535,7 @@ def test_binary16_subnormal_operands(what, mode, N):
         assert np.array_equal(C[single].astype(np.float64), C_ref[single])
 
 
-@pytest.mark.parametrize("mode", ["all_tile", "k32_all_tile", "w64_all_tile", "w128_all_tile", "all_irregular", "hybrid"])
+@pytest.mark.parametrize("mode", ["all_tile", "k32_all_tile", "w64_all_tile", "w128_all_tile", "w256_all_tile", "all_irregular", "hybrid"])
 def test_stored_zeros(mode):
     """Stored explicit zeros (+0 and -0 bit patterns) stay entries of the plan and contribute nothing:
     a row whose stored values are all zero, and an element whose terms all vanish, must come out as
@@ -561,7 +564,7 @@ def test_stored_zeros(mode):
     plan.destroy()
 
 
-@pytest.mark.parametrize("mode", ["all_tile", "w128_all_tile", "all_irregular", "hybrid"])
+@pytest.mark.parametrize("mode", ["all_tile", "w128_all_tile", "w256_all_tile", "all_irregular", "hybrid"])
 def test_b_byte_offsets_above_2_31(mode):
     """The kernels address a row of B as a 32-bit byte offset from a 64-bit base.  With 2^21 - 1
     columns and N = 1024 (2048-byte rows) the offsets of the upper half of B lie in [2^31, 2^32):
