@@ -690,15 +690,6 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 // ---------------------------------------------------------------------------
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-#ifdef RSH_PANEL_TRACE
-// developer build only: per wave, cycles spent between a round's barrier and the next (own work) and
-// waiting at the barrier
-__device__ unsigned long long g_panel_trace[4 * 4096];
-extern "C" int rsh_debug_panel_trace(unsigned long long* out) {
-    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_panel_trace), sizeof(g_panel_trace)) == hipSuccess ? 0 : 6;
-}
-#endif
-
 // NG = row groups (waves) per window: 4 (128 rows) or 8 (256 rows)
 template <int NCH32, int NG>
 struct PanelGeom {
@@ -734,17 +725,8 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
     float* __restrict__ scratch, int N, int feature0) {
     using Gm = PanelGeom<NCH32, NG>;
     constexpr int P = Gm::P, TPR = Gm::TPR, LDB = Gm::LDB, NLD = Gm::NLD, KT = kPanelK, THREADS = Gm::THREADS;
-#ifndef RSH_PANEL_LB
-#define RSH_PANEL_LB 2
-#endif
-#ifndef RSH_PANEL_SKIP
-#define RSH_PANEL_SKIP 0   // developer timing builds only: 1 no scatter, 2 no B staging, 4 no MFMA, 8 no entry loads, 16 no B loads
-#endif
-#ifndef RSH_PANEL_LA
-#define RSH_PANEL_LA 5
-#endif
-    constexpr int LB = RSH_PANEL_LB;    // fragments ahead at which B rows are requested
-    constexpr int LA = RSH_PANEL_LA;    // fragments ahead at which a wave's entries are requested
+    constexpr int LB = 2;    // fragments ahead at which B rows are requested
+    constexpr int LA = 3;    // fragments ahead at which a wave's entries are requested (1 .. 5 measure alike)
     __shared__ __attribute__((aligned(16))) unsigned char smem[Gm::SMEM_BYTES];
     _Float16* const lds_b = reinterpret_cast<_Float16*>(smem);                                  // [2][KT * LDB]
     unsigned char* const lds_a = smem + 2 * Gm::TILE_HALVES * 2;                                // [4 waves][WAVE_A_BYTES]
@@ -796,21 +778,20 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
         // ---- this wave's entry stream and operand tiles ----
         const uint32_t unit0 = 2u * NG * t0 + ((uint32_t)g * nt + (t_begin - t0)) * 2u;
         unsigned char* const my_a = lds_a + g * Gm::WAVE_A_BYTES;     // [0, 1024) K step 0, [1024, 2048) K step 1, then 256 spare bytes
-        const uint32_t spare = 2048u + 4u * (uint32_t)lane;           // where a lane without an entry writes
         const int g4 = lane >> 4, rr4 = (lane & 15) >> 2, ss4 = lane & 3;
         const int tr_off = (8 * (g4 >> 1) + rr4) * LDB + 16 * (g4 & 1) + 4 * ss4;
 
         uint4_t breg[4][NLD];
-        uint4_t areg[8][2][R];
-        uint32_t cnt_ring[8][2];
+        uint4_t areg[4][2][R];
+        uint32_t cnt_ring[4][2];
         int cid_ring[4][NLD];   // column ids of the rows a thread stages, by fragment mod 4 (gathered windows only)
 
-        // Offsets of the units of eight fragments at a time: lane i < 17 holds unit_off[first unit + i].
-        // Fetched with a vector load one round of eight fragments ahead (a scalar load would have to be
+        // Offsets of the units of four fragments at a time: lane i < 9 holds unit_off[first unit + i].
+        // Fetched with a vector load one round of four fragments ahead (a scalar load would have to be
         // waited for at the next LDS wait: the two share a counter).  Past the item's last fragment
         // the index stops at the end of its last unit, so later fragments have no entries.
         auto request_offsets = [&](uint32_t first_step) -> uint32_t {
-            return unit_off[unit0 + min(2u * first_step + (uint32_t)(lane & 31), 2u * last + 2u)];
+            return unit_off[unit0 + min(2u * first_step + (uint32_t)(lane & 15), 2u * last + 2u)];
         };
         // Entries are fetched four per lane with 16-byte loads (few, wide requests: the vector memory
         // path takes as long over a 4-byte load as over a 16-byte one).  Lanes past the unit's last
@@ -821,7 +802,6 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
             const uint4_t* p0 = reinterpret_cast<const uint4_t*>(ent + o0);   // wave-uniform, 16-byte aligned
             const uint4_t* p1 = reinterpret_cast<const uint4_t*>(ent + o1);
             const uint32_t last0 = max(cnt[0], 1u) - 1u, last1 = max(cnt[1], 1u) - 1u;
-            if (RSH_PANEL_SKIP & 8) return;
 #pragma unroll
             for (int q = 0; q < R; ++q) a[0][q] = p0[min((uint32_t)(64 * q + lane), last0)];
 #pragma unroll
@@ -837,7 +817,6 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
         };
         auto issue_b = [&](uint32_t step, const int (&cid)[NLD], uint4_t (&b)[NLD]) {
             const uint32_t first_col = (uint32_t)col0 + (t_begin - t0 + min(step, last)) * KT;
-            if (RSH_PANEL_SKIP & 16) return;
 #pragma unroll
             for (int j = 0; j < NLD; ++j) {
                 const uint32_t c = run ? first_col + (uint32_t)ld_row[j] : (uint32_t)cid[j];
@@ -846,26 +825,25 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
         };
         auto stage_b = [&](const uint4_t (&b)[NLD], int buf) {
             _Float16* sb = lds_b + buf * Gm::TILE_HALVES;
-            if (RSH_PANEL_SKIP & 2) return;
 #pragma unroll
             for (int j = 0; j < NLD; ++j) *reinterpret_cast<uint4_t*>(sb + ld_lds[j]) = b[j];
         };
-        // Entries into the zeroed operand tiles.  No branches: a lane without a quad of the unit writes
-        // into its own spare word instead (as do the entries that pad a unit to a whole quad).
+        // Entries into the zeroed operand tiles.  Lanes without a quad of the unit are masked off (the
+        // LDS spends its time per active lane); the entries that pad a unit to a whole quad carry
+        // addresses in the spare words behind the tiles.
         auto scatter = [&](const uint4_t (&a)[2][R], const uint32_t (&cnt)[2]) {
-            if (RSH_PANEL_SKIP & 1) return;
             *reinterpret_cast<uint4_t*>(my_a + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
             *reinterpret_cast<uint4_t*>(my_a + 1024 + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int q = 0; q < R; ++q) {
-                    const bool on = (uint32_t)(64 * q + lane) < cnt[h];
+                    if ((uint32_t)(64 * q + lane) < cnt[h]) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const uint32_t w = a[h][q][i];
-                        const uint32_t at = on ? 1024u * h + (w >> 16) : spare;
-                        *reinterpret_cast<uint16_t*>(my_a + at) = (uint16_t)w;
+                        for (int i = 0; i < 4; ++i) {
+                            const uint32_t w = a[h][q][i];
+                            *reinterpret_cast<uint16_t*>(my_a + 1024u * h + (w >> 16)) = (uint16_t)w;
+                        }
                     }
                 }
         };
@@ -894,27 +872,13 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
             block_barrier();
         }
 
-#ifdef RSH_PANEL_TRACE
-        unsigned long long tr_work = 0, tr_wait = 0, tr_mark = __builtin_amdgcn_s_memtime();
-        unsigned long long tr_p1 = 0, tr_p2 = 0;
-#define RSH_TRACE_POINT(acc_)                                                 \
-    {                                                                         \
-        __builtin_amdgcn_sched_barrier(0);                                    \
-        const unsigned long long tp_ = __builtin_amdgcn_s_memtime();          \
-        acc_ += tp_ - tr_last;                                                \
-        tr_last = tp_;                                                        \
-        __builtin_amdgcn_sched_barrier(0);                                    \
-    }
-#else
-#define RSH_TRACE_POINT(acc_)
-#endif
-        for (uint32_t base = 0; base < steps; base += 8) {
-            uint32_t o[17];   // unit offsets of fragments base + LA .. base + LA + 7
+        for (uint32_t base = 0; base < steps; base += 4) {
+            uint32_t o[9];   // unit offsets of fragments base + LA .. base + LA + 3
 #pragma unroll
-            for (int i = 0; i < 17; ++i) o[i] = (uint32_t)__builtin_amdgcn_readlane((int)ovec, i);
-            ovec = request_offsets(base + 8u + (uint32_t)LA);
+            for (int i = 0; i < 9; ++i) o[i] = (uint32_t)__builtin_amdgcn_readlane((int)ovec, i);
+            ovec = request_offsets(base + 4u + (uint32_t)LA);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 4; ++u) {
                 const uint32_t s = base + (uint32_t)u;
                 // operands of fragment s (scattered during the previous round)
                 const half8_t a0 = *reinterpret_cast<const half8_t*>(my_a + lane * 16);
@@ -923,11 +887,7 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
                 // ids were requested a round ago), this wave's entries of fragment s + LA
                 fetch_colids(s + LB + 1, cid_ring[(u + LB + 1) & 3]);
                 issue_b(s + LB, cid_ring[(u + LB) & 3], breg[(u + LB) & 3]);
-                issue_entries(o[2 * u], o[2 * u + 1], o[2 * u + 2], areg[(u + LA) & 7], cnt_ring[(u + LA) & 7]);
-#if defined(RSH_PANEL_TRACE) && RSH_PANEL_TRACE > 1
-                unsigned long long tr_last = tr_mark;
-                RSH_TRACE_POINT(tr_p1)
-#endif
+                issue_entries(o[2 * u], o[2 * u + 1], o[2 * u + 2], areg[(u + LA) & 3], cnt_ring[(u + LA) & 3]);
                 // multiply fragment s out of LDS
                 const _Float16* sb = lds_b + (u & 1) * Gm::TILE_HALVES + tr_off;
 #pragma unroll
@@ -939,32 +899,14 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
                         const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                             (short4_t __attribute__((address_space(3)))*)(sb + (16 * h + 4) * LDB + 32 * c)));
                         const half8_t b_frag = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        if (RSH_PANEL_SKIP & 4) {
-                            acc[c][0] += (float)b_frag[0] + (float)(h ? a1 : a0)[0];
-                            continue;
-                        }
                         acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b_frag, h ? a1 : a0, acc[c], 0, 0, 0);
                     }
-#if defined(RSH_PANEL_TRACE) && RSH_PANEL_TRACE > 1
-                RSH_TRACE_POINT(tr_p2)
-#endif
                 // fragment s + 1: B rows into the other buffer, entries into the operand tiles
                 stage_b(breg[(u + 1) & 3], (u + 1) & 1);
-                scatter(areg[(u + 1) & 7], cnt_ring[(u + 1) & 7]);
-#ifdef RSH_PANEL_TRACE
-                {
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-                    const unsigned long long t1 = __builtin_amdgcn_s_memtime();
-                    tr_work += t1 - tr_mark;
-                    block_barrier();
-                    tr_mark = __builtin_amdgcn_s_memtime();
-                    tr_wait += tr_mark - t1;
-                }
-#else
+                scatter(areg[(u + 1) & 3], cnt_ring[(u + 1) & 3]);
                 block_barrier();
-#endif
             }
-            if ((base & 31u) == 24u) {   // 32 fragments = 1024 condensed columns: second level
+            if ((base & 31u) == 28u) {   // 32 fragments = 1024 condensed columns: second level
 #pragma unroll
                 for (int c = 0; c < NCH32; ++c) {
                     acc2[c] += acc[c];
@@ -973,14 +915,6 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
                 }
             }
         }
-#ifdef RSH_PANEL_TRACE
-        if (lane == 0 && item < 1024u) {
-            g_panel_trace[(item * 4 + g) * 4 + 0] = tr_work;
-            g_panel_trace[(item * 4 + g) * 4 + 1] = tr_wait;
-            g_panel_trace[(item * 4 + g) * 4 + 2] = steps | (tr_p1 << 20);
-            g_panel_trace[(item * 4 + g) * 4 + 3] = tr_p2;
-        }
-#endif
     }
 
     // ---- output: each wave's 32 rows x 32 features take a turn through LDS and leave as whole lines ----
