@@ -17,15 +17,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
-
-# HBM bytes per rsh_spmm call measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE of the
-# dominant kernel, scaled by a copy kernel of known size); filled in from profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    (2, "irregular"): int((3681.7 + 742.3) * 1e6),   # profiles/spmm_rmat_gcn_2e20.md
-    (3, "tile"): int((322.7 + 226.5) * 1e6),         # profiles/spmm_stencil27_96.md
-    (4, "tile"): int((1420.6 + 536.9) * 1e6),        # profiles/spmm_hidden_communities_524288.md
-    (5, "tile"): int((255.7 + 117.4) * 1e6),         # profiles/spmm_pruned_llm_28672x8192.md
-}
+# What a gather of 256-byte rows from a table of 67-537 MB sustained on this part in a microbenchmark
+# (8 loads in flight per 16-lane team): the rate a kernel bound by random row fetches can be held to.
+GATHER_CEILING_GBPS = 7200.0
 
 
 ABLATIONS = {
@@ -99,7 +93,17 @@ def main() -> int:
                          "line with a row per setting (the paper's Sections 4.3.2 and 4.3.3 on synthetic data)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB (for scaling profiler traffic counters)")
+    ap.add_argument("--summarize-profile", metavar="DIR", default=None,
+                    help="no benchmark: turn the rocprofv3 output under DIR (sub-directories stats, pmc_fetch, pmc_write, "
+                         "pmc_sq of the same bench.py command, each with its .log) into the summary --profile-out")
+    ap.add_argument("--profile-out", default=None, help="summary file to write (under profiles/)")
+    ap.add_argument("--profile-args", default="", help="the bench.py arguments the profiled command was run with")
     args = ap.parse_args()
+    if args.summarize_profile:
+        from paper_2603_08734_amd import profiles
+        data = profiles.summarize(args.summarize_profile, args.profile_out, args.profile_args)
+        print(json.dumps(data))
+        return 0
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU (no sharding, no collectives); run with --gpus 1",
               file=sys.stderr)
@@ -165,21 +169,32 @@ def main() -> int:
             acc[k] += t[k]
     kernel_ms = {k: v / n_prof for k, v in acc.items()}
     dominant = max(("tile", "irregular"), key=lambda k: kernel_ms[k])
+    # the dense-fragment part runs in the panel kernel for windows of 128 rows and more
+    kernel_name = "rsh_irregular_kernel" if dominant == "irregular" else ("rsh_panel_kernel" if st["window_rows"] >= 128 else "rsh_tile_kernel")
     if dominant == "irregular":
         alg_bytes = st["irregular_part_bytes"] + 2 * N * st["cols_irregular"] + 4 * N * st["rows_irregular"]
     else:
         alg_bytes = st["tile_part_bytes"] + 2 * N * st["cols_tile"] + 4 * N * st["rows_tile"]
     achieved = alg_bytes / (kernel_ms[dominant] * 1e-3) / 1e9 if kernel_ms[dominant] > 0 else 0.0
     bytes_min = st["plan_bytes"] + 2 * N * st["cols_all"] + 4 * N * A.n_rows
-    roofline = {"bound": "hbm", "kernel": "rsh_%s_kernel" % dominant, "achieved": round(achieved, 1),
+    # counter traffic per launch: only from a profile summary made for exactly this workload, width,
+    # plan options and library build (profiles/*.md); otherwise null
+    from paper_2603_08734_amd import build as lib_build, profiles
+    measured = profiles.lookup(A.meta["name"], N, opts, kernel_name)
+    roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dominant)),
+                "traffic": measured[0] if measured else None,
                 "algorithmic_bytes": int(alg_bytes), "kernel_ms": round(kernel_ms[dominant], 4)}
-    if roofline["traffic"] and kernel_ms[dominant] > 0:
-        # what the memory system actually moved per launch (counters, profiles/) over this run's kernel time
-        moved = roofline["traffic"] / (kernel_ms[dominant] * 1e-3) / 1e9
+    if measured and kernel_ms[dominant] > 0:
+        # what the memory system moved per launch (counters) over this run's kernel time
+        moved = measured[0] / (kernel_ms[dominant] * 1e-3) / 1e9
+        roofline["traffic_source"] = "profiles/%s: %s" % (measured[1], measured[2])
         roofline["traffic_GBps"] = round(moved, 1)
         roofline["traffic_frac"] = round(moved / HBM_PEAK_GBPS, 4)
+        if dominant == "irregular":
+            # a kernel of random 256-byte row fetches: its moved bytes against what such fetches sustain
+            roofline["gather_ceiling_GBps"] = GATHER_CEILING_GBPS
+            roofline["traffic_over_gather_ceiling"] = round(moved / GATHER_CEILING_GBPS, 4)
 
     # work the matrix cores are given: every W x K fragment is multiplied out in full, zeros included
     mfma = None
@@ -197,6 +212,7 @@ def main() -> int:
         "config": {"workload": A.meta["name"], "rows": A.n_rows, "cols": A.n_cols, "nnz": A.nnz, "N": N,
                    "seed": 0, "csr_checksum": A.checksum(), "plan_options": opts},
         "roofline": roofline,
+        "library_sources": lib_build.source_digest(),
         "tile_mfma": mfma,
         "hbm_useful_GBps": round(bytes_min / (ms_per_step * 1e-3) / 1e9, 1),
         "bytes_min": int(bytes_min),

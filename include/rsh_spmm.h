@@ -100,6 +100,10 @@ typedef struct {
                              decode, row order) then refers to A^T; B has n_rows rows, C has n_cols rows */
     int32_t upload;       /* 1 = copy the plan to the current HIP device; 0 = host-only plan    */
     int32_t threads;      /* host threads used for planning; 0 = all available                  */
+    int32_t side_stream;  /* 1 = the dense-fragment kernel is enqueued on a stream of the plan's own, forked from
+                             and joined to the caller's stream by events, so that it may run beside the
+                             residual-row kernel (the two write disjoint rows of C, Section 3.1);
+                             0 (default) = all kernels in order on the caller's stream                 */
 } rsh_plan_opts_t;
 
 /* What the planner built (host side, for tests, logs and the benchmark). */

@@ -47,6 +47,9 @@ void free_device(rsh::DevicePlan& d) {
                     d.b_pad, d.c_pad, d.bias_pad};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    if (d.ev_fork) (void)hipEventDestroy((hipEvent_t)d.ev_fork);
+    if (d.ev_join) (void)hipEventDestroy((hipEvent_t)d.ev_join);
+    if (d.side) (void)hipStreamDestroy((hipStream_t)d.side);
     d = rsh::DevicePlan{};
 }
 
@@ -85,6 +88,16 @@ int upload_plan(rsh_plan& p) {
         if (!hip_ok(hipMalloc(&d.c_pad, (size_t)std::max<int64_t>(1, h.n_rows) * np * 4))) return RSH_ERR_OOM;
         if (!hip_ok(hipMalloc((void**)&d.bias_pad, np * 4))) return RSH_ERR_OOM;
     }
+    if (h.opts.side_stream) {   // default priority, like every stream this library touches
+        hipStream_t side = nullptr;
+        hipEvent_t fork = nullptr, join = nullptr;
+        if (!hip_ok(hipStreamCreateWithFlags(&side, hipStreamNonBlocking))) return RSH_ERR_HIP;
+        d.side = side;
+        if (!hip_ok(hipEventCreateWithFlags(&fork, hipEventDisableTiming))) return RSH_ERR_HIP;
+        d.ev_fork = fork;
+        if (!hip_ok(hipEventCreateWithFlags(&join, hipEventDisableTiming))) return RSH_ERR_HIP;
+        d.ev_join = join;
+    }
     if (!hip_ok(hipGetDevice(&p.device))) return RSH_ERR_HIP;
     p.uploaded = true;
     return RSH_OK;
@@ -120,6 +133,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->transpose = 0;
     o->upload = 1;
     o->threads = 0;
+    o->side_stream = 0;
     return RSH_OK;
 }
 
@@ -141,7 +155,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     if (o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2) return RSH_ERR_BAD_OPTION;
     if (o.reorder < 0 || o.reorder > 3 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
-    if (o.threads < 0 || o.transpose < 0 || o.transpose > 1) return RSH_ERR_BAD_OPTION;
+    if (o.threads < 0 || o.transpose < 0 || o.transpose > 1 || o.side_stream < 0 || o.side_stream > 1) return RSH_ERR_BAD_OPTION;
 
     const auto t_all = std::chrono::steady_clock::now();
     auto t0 = t_all;

@@ -1179,12 +1179,22 @@ static int launch_panels(const DevicePlan& d, const void* B, const OUT& out, hip
 
 template <class OUT>
 static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* stream, void* const* events) {
-    hipStream_t st = (hipStream_t)stream;
+    const hipStream_t caller = (hipStream_t)stream;
     auto mark = [&](int i) {
-        if (events) (void)hipEventRecord((hipEvent_t)events[i], st);
+        if (events) (void)hipEventRecord((hipEvent_t)events[i], caller);
     };
     mark(0);
     int rc = RSH_OK;
+    // The dense-fragment kernel and the residual-row kernel write disjoint rows of C, so the first
+    // may run on the plan's side stream (forked from and joined to the caller's stream by events)
+    // beside the second; the combine pass waits for both.  Per-kernel timing runs them in order.
+    const bool forked = d.side && !events && d.n_tile_items > 0 && d.n_irr_waves > 0;
+    if (forked) {
+        if (hipEventRecord((hipEvent_t)d.ev_fork, caller) != hipSuccess ||
+            hipStreamWaitEvent((hipStream_t)d.side, (hipEvent_t)d.ev_fork, 0) != hipSuccess)
+            return RSH_ERR_HIP;
+    }
+    hipStream_t st = forked ? (hipStream_t)d.side : caller;
     if (d.n_tile_items > 0 && d.geo.panel) {
         rc = launch_panels(d, B, out, st);
         if (rc != RSH_OK) return rc;
@@ -1207,6 +1217,8 @@ static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* 
         }
         if (rc != RSH_OK) return rc;
     }
+    if (forked && hipEventRecord((hipEvent_t)d.ev_join, (hipStream_t)d.side) != hipSuccess) return RSH_ERR_HIP;
+    st = caller;
     mark(1);
     if (d.n_irr_waves > 0) {
         switch (d.geo.irr_tpr) {
@@ -1218,6 +1230,7 @@ static int launch_all(const DevicePlan& d, const void* B, const OUT& out, void* 
         }
     }
     mark(2);
+    if (forked && hipStreamWaitEvent(caller, (hipEvent_t)d.ev_join, 0) != hipSuccess) return RSH_ERR_HIP;
     if (d.n_combine > 0) {
         const uint32_t n = (uint32_t)d.n_combine;
         hipLaunchKernelGGL(rsh_combine_kernel<OUT>, dim3((n + kWavesPerBlock - 1) / kWavesPerBlock), dim3(64 * kWavesPerBlock),

@@ -34,6 +34,10 @@ struct DevicePlan {
     void* b_pad = nullptr;      // binary16 [n_cols][geo.N]
     void* c_pad = nullptr;      // fp32 (or binary16) [n_rows][geo.N]
     float* bias_pad = nullptr;  // fp32 [geo.N]
+    // optional second stream for the dense-fragment kernel (rsh_plan_opts_t::side_stream)
+    void* side = nullptr;       // hipStream_t
+    void* ev_fork = nullptr;    // hipEvent_t: caller's stream -> side stream
+    void* ev_join = nullptr;    // hipEvent_t: side stream -> caller's stream
 };
 
 // Enqueue the tile, irregular and combine kernels on `stream` (a hipStream_t).  When

@@ -625,3 +625,35 @@ def test_null_b_is_refused_when_the_wide_copy_would_read_it():
         if want == binding.RSH_OK:
             assert torch.all(C == 0)
         plan.destroy()
+
+
+@pytest.mark.parametrize("k,opts", [(2, dict(xcd_partition_nnz=32, max_tiles_per_item=3)), (4, dict(long_row_nnz=22)), (5, dict(long_row_nnz=230))],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_side_stream_gives_the_same_bits(k, opts):
+    """side_stream = 1 puts the dense-fragment kernel on a stream of the plan's own beside the
+    residual-row kernel (disjoint rows of C, Section 3.1): same kernels, same sums, so the result
+    must equal the single-stream result bit for bit, call after call, and meet the oracle bound."""
+    torch = _torch()
+    from paper_2603_08734_amd import Plan
+    A, N, dist = make_config(k, small=True)
+    B = dense_B(A.n_cols, N, dist, seed=60 + k)
+    Bd = torch.from_numpy(B.view(np.int16)).cuda().view(torch.float16)
+    p0 = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, side_stream=0, **opts)
+    p1 = Plan(A.row_ptr, A.col_idx, A.val, A.n_cols, N, side_stream=1, **opts)
+    st = p1.stats()
+    print(f"case side-stream config={k} nnz_tile={st['nnz_tile']} nnz_irregular={st['nnz_irregular']}", flush=True)
+    assert st["nnz_tile"] > 0 and st["nnz_irregular"] > 0, "the case must run both kernels"
+    C0 = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+    p0.spmm(Bd, C0)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    for rep in range(3):
+        C1 = torch.full((A.n_rows, N), float("nan"), dtype=torch.float32, device="cuda")
+        with torch.cuda.stream(stream):
+            p1.spmm(Bd, C1, stream=stream.cuda_stream)
+        stream.synchronize()
+        assert torch.equal(C0.view(torch.int32), C1.view(torch.int32)), f"call {rep} differs from the single-stream result"
+    C_ref, S, _ = oracle.spmm(A.row_ptr, A.col_idx, A.val, B)
+    assert_parity(C1.cpu().numpy(), C_ref, S, f"side stream, config {k}")
+    p0.destroy()
+    p1.destroy()
