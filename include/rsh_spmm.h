@@ -126,6 +126,13 @@ typedef struct {
     int32_t window_rows, tile_k;               /* W and K actually used                          */
     int64_t schedule_cols_given, schedule_cols_found; /* distinct columns per run of 256 consecutive windows,
                                                   summed, in plan order and in clustered order (0 = not tried) */
+    int64_t singleton_entries, singleton_rows; /* entries of windows in columns that one row of the window names;
+                                                  window rows holding at least one such entry         */
+    int64_t bytes_method;                      /* bytes one product moves under the routing as built: plan +
+                                                  2N per distinct column of each window and per residual entry
+                                                  + 4N per row of C + 8N per partial row                 */
+    int64_t bytes_method_element_level;        /* the same if those entries went to the residual path
+                                                  (element-level routing): fewer plan bytes, 8N more per such row */
     double reorder_cost_given, reorder_cost_found; /* Section 3.4 objective of the given order and of the
                                                   order the heuristic found (the lower one is used) */
     double ms_validate, ms_reorder, ms_partition, ms_pack, ms_worklist, ms_upload, ms_total;

@@ -67,7 +67,8 @@ class rsh_plan_stats_t(ctypes.Structure):
                     "tile_part_bytes", "irregular_part_bytes", "cols_all", "cols_tile", "cols_irregular",
                     "rows_tile", "rows_irregular")] +
                 [("tau_nnz", ctypes.c_int32), ("tau_inc", ctypes.c_int32), ("window_rows", ctypes.c_int32), ("tile_k", ctypes.c_int32)] +
-                [(n, ctypes.c_int64) for n in ("schedule_cols_given", "schedule_cols_found")] +
+                [(n, ctypes.c_int64) for n in ("schedule_cols_given", "schedule_cols_found", "singleton_entries", "singleton_rows",
+                                               "bytes_method", "bytes_method_element_level")] +
                 [(n, ctypes.c_double) for n in ("reorder_cost_given", "reorder_cost_found", "ms_validate", "ms_reorder", "ms_partition", "ms_pack",
                                                 "ms_worklist", "ms_upload", "ms_total")])
 

@@ -74,6 +74,8 @@ struct HostPlan {
     std::vector<uint32_t> combine;  // 4 per entry
     int64_t n_scratch_slots = 0;
 
+    std::vector<int64_t> win_single_entries, win_single_rows;   // per window: entries in single-row columns, rows holding one
+
     rsh_plan_stats_t stats{};
 };
 

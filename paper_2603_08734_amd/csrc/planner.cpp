@@ -336,6 +336,24 @@ static void gather_window(const rsh_csr_t& a, const int32_t* rows, int W, std::v
 
 static inline int popc64(uint64_t x) { return __builtin_popcountll(x); }
 
+// Columns that a single row of the window names (entries sorted by column, then row): how many
+// there are and how many of the window's rows hold at least one.  These are the entries that an
+// element-level routing would send to the residual path instead.
+static void count_singletons(const std::vector<WinEntry>& ent, int64_t* entries, int64_t* rows) {
+    uint64_t row_seen[4] = {0, 0, 0, 0};
+    int64_t n = 0;
+    for (size_t i = 0; i < ent.size(); ++i) {
+        const bool first = i == 0 || (ent[i - 1].key >> 8) != (ent[i].key >> 8);
+        const bool last = i + 1 == ent.size() || (ent[i + 1].key >> 8) != (ent[i].key >> 8);
+        if (first && last) {
+            ++n;
+            row_seen[(ent[i].key & 255) >> 6] |= 1ull << (ent[i].key & 63);
+        }
+    }
+    *entries = n;
+    *rows = popc64(row_seen[0]) + popc64(row_seen[1]) + popc64(row_seen[2]) + popc64(row_seen[3]);
+}
+
 // Order in which windows are issued.  Windows that run at the same time on one XCD should
 // gather overlapping B rows, so that a row fetched for one is an L2 hit for the others.  For a
 // square matrix the window holding row j is a natural neighbour of every window that reads
@@ -453,6 +471,7 @@ static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPla
             win_tiles[w] = nt;
             win_real[w] = ent.size();
             win_ent[w] = padded;
+            count_singletons(ent, &plan.win_single_entries[(size_t)w], &plan.win_single_rows[(size_t)w]);
         }
     });
     plan.win_tile_off.assign((size_t)n_win + 1, 0);
@@ -547,6 +566,8 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     plan.win_row = part.win_row;
 
     int64_t sum_cols = 0, n_tiles = 0, nnz_tile = 0;
+    plan.win_single_entries.assign((size_t)n_win, 0);
+    plan.win_single_rows.assign((size_t)n_win, 0);
     if (geo.panel) {
         const int rc = pack_panel_windows(a, part, plan, threads, &sum_cols, &nnz_tile);
         if (rc != RSH_OK) return rc;
@@ -579,6 +600,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 win_tiles[w] = (uint32_t)(cnt.size() / (size_t)NW);
                 win_vals[w] = v;
                 win_cols[w] = u;
+                count_singletons(ent, &plan.win_single_entries[(size_t)w], &plan.win_single_rows[(size_t)w]);
             }
         });
         plan.win_tile_off.assign((size_t)n_win + 1, 0);
@@ -972,6 +994,24 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                               plan.panel_ent.size() * 4 + plan.irr_col.size() * 4 + plan.irr_val.size() * 2 +
                               plan.irr_wave.size() * 4 + plan.irr_row.size() * 4 + plan.combine.size() * 4);
     st.csr_bytes = 6 * a.nnz + 8 * (a.n_rows + 1);
+    // What the product has to move under the routing as built (rows are routed whole, Section 3.1):
+    // the plan once, a row of B per distinct column of every window and per residual entry, every
+    // row of C once, partial rows written and read back.  And under element-level routing, where a
+    // window's single-row columns would go to the residual path: their plan bytes change from a
+    // fragment column (column id, a column of bitmap bits, the value: 4 + W/8 + 2, or the 4-byte
+    // entry of the panel form plus its share of a column id) to a residual entry (6), their rows
+    // of B are fetched either way, and every row that is then written by both kernels costs one
+    // more read and write of its row of C.
+    {
+        int64_t single_entries = 0, single_rows = 0;
+        for (int64_t w = 0; w < n_win; ++w) single_entries += plan.win_single_entries[(size_t)w], single_rows += plan.win_single_rows[(size_t)w];
+        const int64_t Nf = geo.N;
+        st.singleton_entries = single_entries;
+        st.singleton_rows = single_rows;
+        st.bytes_method = st.plan_bytes + 2 * Nf * (sum_cols + nnz_irr) + 4 * Nf * a.n_rows + 2 * 4 * Nf * slots;
+        const int64_t per_tile_entry = geo.panel ? 4 + 4 : 4 + geo.win_rows / 8 + 2;
+        st.bytes_method_element_level = st.bytes_method - (per_tile_entry - 6) * single_entries + 2 * 4 * Nf * single_rows;
+    }
     st.tile_part_bytes = (int64_t)(plan.win_row.size() * 4 + plan.tile_colid.size() * 4 + plan.tile_mask.size() * 8 +
                                    plan.tile_val_off.size() * 4 + plan.tile_val.size() * 2 + plan.tile_item.size() * 4 +
                                    plan.panel_col0.size() * 4 + plan.panel_off.size() * 4 + plan.panel_ent.size() * 4);

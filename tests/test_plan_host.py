@@ -520,3 +520,20 @@ def test_window_height_is_chosen_by_column_sharing():
     assert p3.stats()["window_rows"] == 16
     if p5.stats()["n_windows"] * p5.stats()["window_rows"] >= 64 * 16:
         assert p5.stats()["window_rows"] == 256
+
+
+@pytest.mark.parametrize("opts", [dict(window_rows=16), dict(window_rows=64, tile_k=32), dict(window_rows=128)], ids=str)
+def test_single_row_columns_are_counted(opts):
+    """Statistic behind the element-level routing question: 32 rows share columns 0..7; rows 0..19 also
+    hold one column of their own.  Those 20 entries sit in columns that one row of their window names."""
+    r = np.concatenate([np.repeat(np.arange(32), 8), np.arange(20)])
+    c = np.concatenate([np.tile(np.arange(8), 32), 100 + np.arange(20)])
+    A = from_coo(r, c, np.ones(r.size), 32, 200)
+    N = 64
+    p = host_plan(A, N, force_path=2, reorder=0, **opts)
+    st = p.stats()
+    assert st["singleton_entries"] == 20 and st["singleton_rows"] == 20
+    want = st["plan_bytes"] + 2 * N * (st["sum_window_cols"] + st["nnz_irregular"]) + 4 * N * A.n_rows + 8 * N * st["n_scratch_slots"]
+    assert st["bytes_method"] == want
+    per_entry = 8 if opts["window_rows"] >= 128 else 4 + opts["window_rows"] // 8 + 2
+    assert st["bytes_method_element_level"] == want - (per_entry - 6) * 20 + 8 * N * 20
