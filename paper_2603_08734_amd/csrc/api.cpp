@@ -32,13 +32,64 @@ double ms_since(std::chrono::steady_clock::time_point t0) {
     return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
 }
 
+// Host -> device copies of the plan's arrays go through two pinned staging buffers: a chunk is
+// copied into one (by all planning threads) while the DMA engine drains the other.  Copies straight
+// from the pageable vectors ran at about 1.3 GB/s (164 ms for the 209 MB of the R-MAT plan).
+struct Uploader {
+    static constexpr size_t kChunk = (size_t)16 << 20;
+    char* stage[2] = {nullptr, nullptr};
+    hipEvent_t done[2] = {nullptr, nullptr};
+    hipStream_t stream = nullptr;
+    int turn = 0, threads = 1;
+    bool used[2] = {false, false};
+
+    int open(int n_threads) {
+        threads = n_threads;
+        if (!hip_ok(hipStreamCreateWithFlags(&stream, hipStreamNonBlocking))) return RSH_ERR_HIP;
+        for (int i = 0; i < 2; ++i) {
+            if (!hip_ok(hipHostMalloc((void**)&stage[i], kChunk, hipHostMallocDefault))) return RSH_ERR_OOM;
+            if (!hip_ok(hipEventCreateWithFlags(&done[i], hipEventDisableTiming))) return RSH_ERR_HIP;
+        }
+        return RSH_OK;
+    }
+    int copy(void* dst, const void* src, size_t bytes) {
+        for (size_t at = 0; at < bytes; at += kChunk) {
+            const size_t n = std::min(kChunk, bytes - at);
+            if (used[turn] && !hip_ok(hipEventSynchronize(done[turn]))) return RSH_ERR_HIP;
+            char* to = stage[turn];
+            const char* from = static_cast<const char*>(src) + at;
+            rsh::parallel_chunks((int64_t)((n + 65535) / 65536), threads, [&](int64_t b, int64_t e, int) {
+                const size_t lo = (size_t)b * 65536, hi = std::min(n, (size_t)e * 65536);
+                if (hi > lo) std::memcpy(to + lo, from + lo, hi - lo);
+            });
+            if (!hip_ok(hipMemcpyAsync(static_cast<char*>(dst) + at, to, n, hipMemcpyHostToDevice, stream))) return RSH_ERR_HIP;
+            if (!hip_ok(hipEventRecord(done[turn], stream))) return RSH_ERR_HIP;
+            used[turn] = true;
+            turn ^= 1;
+        }
+        return RSH_OK;
+    }
+    int close() {
+        int rc = RSH_OK;
+        if (stream && !hip_ok(hipStreamSynchronize(stream))) rc = RSH_ERR_HIP;
+        for (int i = 0; i < 2; ++i) {
+            if (done[i]) (void)hipEventDestroy(done[i]);
+            if (stage[i]) (void)hipHostFree(stage[i]);
+            done[i] = nullptr;
+            stage[i] = nullptr;
+        }
+        if (stream) (void)hipStreamDestroy(stream);
+        stream = nullptr;
+        return rc;
+    }
+};
+
 template <class T>
-int upload_array(const std::vector<T>& h, T** d) {
+int upload_array(Uploader& up, const std::vector<T>& h, T** d) {
     *d = nullptr;
     const size_t bytes = (h.size() ? h.size() : 1) * sizeof(T);
     if (!hip_ok(hipMalloc((void**)d, bytes))) return RSH_ERR_OOM;
-    if (!h.empty() && !hip_ok(hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice))) return RSH_ERR_HIP;
-    return RSH_OK;
+    return h.empty() ? RSH_OK : up.copy(*d, h.data(), h.size() * sizeof(T));
 }
 
 void free_device(rsh::DevicePlan& d) {
@@ -63,23 +114,29 @@ int upload_plan(rsh_plan& p) {
     d.n_scratch_slots = h.n_scratch_slots;
     d.tile_split = h.tile_split;
     d.irr_split = h.irr_split;
-    int rc;
-    if ((rc = upload_array(h.win_row, &d.win_row))) return rc;
-    if ((rc = upload_array(h.win_tile_off, &d.win_tile_off))) return rc;
-    if ((rc = upload_array(h.tile_colid, &d.tile_colid))) return rc;
-    if ((rc = upload_array(h.tile_mask, &d.tile_mask))) return rc;
-    if ((rc = upload_array(h.tile_val_off, &d.tile_val_off))) return rc;
-    if ((rc = upload_array(h.tile_val, &d.tile_val))) return rc;
-    if ((rc = upload_array(h.tile_item, &d.tile_item))) return rc;
-    if ((rc = upload_array(h.panel_col0, &d.panel_col0))) return rc;
-    if ((rc = upload_array(h.panel_off, &d.panel_off))) return rc;
-    if ((rc = upload_array(h.panel_ent, &d.panel_ent))) return rc;
+    Uploader up;
+    struct Closer {
+        Uploader& u;
+        ~Closer() { (void)u.close(); }
+    } closer{up};
+    int rc = up.open(h.opts.threads > 0 ? h.opts.threads : rsh::hardware_threads());
+    if (rc) return rc;
+    if ((rc = upload_array(up, h.win_row, &d.win_row))) return rc;
+    if ((rc = upload_array(up, h.win_tile_off, &d.win_tile_off))) return rc;
+    if ((rc = upload_array(up, h.tile_colid, &d.tile_colid))) return rc;
+    if ((rc = upload_array(up, h.tile_mask, &d.tile_mask))) return rc;
+    if ((rc = upload_array(up, h.tile_val_off, &d.tile_val_off))) return rc;
+    if ((rc = upload_array(up, h.tile_val, &d.tile_val))) return rc;
+    if ((rc = upload_array(up, h.tile_item, &d.tile_item))) return rc;
+    if ((rc = upload_array(up, h.panel_col0, &d.panel_col0))) return rc;
+    if ((rc = upload_array(up, h.panel_off, &d.panel_off))) return rc;
+    if ((rc = upload_array(up, h.panel_ent, &d.panel_ent))) return rc;
     d.n_panel_ent = (uint32_t)h.panel_ent.size();
-    if ((rc = upload_array(h.irr_col, &d.irr_col))) return rc;
-    if ((rc = upload_array(h.irr_val, &d.irr_val))) return rc;
-    if ((rc = upload_array(h.irr_wave, &d.irr_wave))) return rc;
-    if ((rc = upload_array(h.irr_row, &d.irr_row))) return rc;
-    if ((rc = upload_array(h.combine, &d.combine))) return rc;
+    if ((rc = upload_array(up, h.irr_col, &d.irr_col))) return rc;
+    if ((rc = upload_array(up, h.irr_val, &d.irr_val))) return rc;
+    if ((rc = upload_array(up, h.irr_wave, &d.irr_wave))) return rc;
+    if ((rc = upload_array(up, h.irr_row, &d.irr_row))) return rc;
+    if ((rc = upload_array(up, h.combine, &d.combine))) return rc;
     const size_t sbytes = (size_t)std::max<int64_t>(1, h.n_scratch_slots) * (size_t)h.geo.N * sizeof(float);
     if (!hip_ok(hipMalloc((void**)&d.scratch, sbytes))) return RSH_ERR_OOM;
     if (d.n_user != h.geo.N) {
@@ -98,6 +155,7 @@ int upload_plan(rsh_plan& p) {
         if (!hip_ok(hipEventCreateWithFlags(&join, hipEventDisableTiming))) return RSH_ERR_HIP;
         d.ev_join = join;
     }
+    if ((rc = up.close())) return rc;   // every copy has landed
     if (!hip_ok(hipGetDevice(&p.device))) return RSH_ERR_HIP;
     p.uploaded = true;
     return RSH_OK;

@@ -20,10 +20,13 @@
 //     path wherever they stand, so they get no neighbours and are no one's candidate (they end up
 //     among the isolated rows at the tail); scoring them was most of the cost on heavy-tailed
 //     matrices and changed nothing;
-//   * the found order replaces the given one only if it lowers the objective by >= 3 %.
+//   * the found order replaces the given one only if it lowers the objective by >= 3 %;
+//   * before the search, a sample of rows is tested for whether the best window around a row could
+//     pass the partition's reuse test at all; if hardly any does, the given order is kept as it is.
 #include "plan.hpp"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <numeric>
 
@@ -116,89 +119,149 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     auto takes_part = [&](int64_t r) { return a.row_ptr[r + 1] - a.row_ptr[r] <= skip_above; };
 
     // ---- step I: inverted index (column -> rows) over feature columns ----------------------
-    // column-major copy of the pattern, restricted to columns that may serve as features
-    std::vector<int64_t> col_ptr((size_t)a.n_cols + 1, 0);
-    for (int64_t j = 0; j < a.n_cols; ++j) {
-        const int32_t d = col_deg[(size_t)j];
-        col_ptr[(size_t)j + 1] = col_ptr[(size_t)j] + ((d >= 2 && d <= kMaxFeatureDegree) ? d : 0);
-    }
-    std::vector<int32_t> col_rows((size_t)col_ptr[(size_t)a.n_cols]);
-    std::vector<int64_t> col_end((size_t)a.n_cols, 0);   // end of the filled part of each posting list
-    {
-        std::vector<int64_t> fill(col_ptr.begin(), col_ptr.end() - 1);
+    // column-major copy of the pattern, restricted to columns that may serve as features (and, for
+    // the sampled test below, to the columns marked in `only`)
+    std::vector<int64_t> col_ptr, col_end;   // posting list of column j: col_rows[col_ptr[j] .. col_end[j])
+    std::vector<int32_t> col_rows;
+    auto build_index = [&](const std::vector<uint8_t>* only) {
+        auto listed = [&](int64_t j) {
+            const int32_t d = col_deg[(size_t)j];
+            return d >= 2 && d <= kMaxFeatureDegree && (!only || (*only)[(size_t)j]);
+        };
+        col_ptr.assign((size_t)a.n_cols + 1, 0);
+        for (int64_t j = 0; j < a.n_cols; ++j) col_ptr[(size_t)j + 1] = col_ptr[(size_t)j] + (listed(j) ? col_deg[(size_t)j] : 0);
+        col_rows.assign((size_t)col_ptr[(size_t)a.n_cols], 0);
+        col_end.assign(col_ptr.begin(), col_ptr.end() - 1);
         for (int64_t r = 0; r < n; ++r) {
             if (!takes_part(r)) continue;
             for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
                 const int32_t j = a.col_idx[p];
-                const int32_t d = col_deg[(size_t)j];
-                if (d >= 2 && d <= kMaxFeatureDegree) col_rows[(size_t)fill[(size_t)j]++] = (int32_t)r;
+                if (listed(j)) col_rows[(size_t)col_end[(size_t)j]++] = (int32_t)r;
             }
         }
-        // posting lists of columns that lost rows are shorter than their slot: close the gaps
-        for (int64_t j = 0; j < a.n_cols; ++j) col_end[(size_t)j] = fill[(size_t)j];
-    }
+    };
+    // the (at most kMaxFeatures) lowest-degree eligible columns of a row
+    auto features_of = [&](int64_t r, std::pair<int32_t, int32_t> (&feat)[kMaxFeatures]) {
+        int nf = 0;
+        for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
+            const int32_t j = a.col_idx[p], d = col_deg[(size_t)j];
+            if (d < 2 || d > kMaxFeatureDegree) continue;
+            std::pair<int32_t, int32_t> f(d, j);
+            if (nf < kMaxFeatures) feat[nf++] = f;
+            else {
+                int worst = 0;
+                for (int i = 1; i < nf; ++i)
+                    if (feat[i] > feat[worst]) worst = i;
+                if (f < feat[worst]) feat[worst] = f;
+            }
+        }
+        return nf;
+    };
 
     // ---- step II: top-k neighbours per row ---------------------------------------------------
+    struct RowScratch {
+        std::vector<int32_t> cand;
+        std::vector<std::pair<int32_t, int32_t>> counted;   // (-shared features, row)
+        std::vector<std::pair<double, int32_t>> scored;     // (-affinity, row), best first after the call
+    };
+    // candidates of row r through the inverted index, scored; the best `keep` come first in ws.scored
+    auto score_row = [&](int64_t r, size_t keep, RowScratch& ws) {
+        std::pair<int32_t, int32_t> feat[kMaxFeatures];
+        const int nf = features_of(r, feat);
+        ws.cand.clear();
+        for (int i = 0; i < nf; ++i) {
+            const int32_t j = feat[i].second;
+            const int64_t cb = col_ptr[(size_t)j], ce = col_end[(size_t)j];
+            // scan at most kScanPerFeature rows of the posting list, centred on r's own position
+            const int64_t len = ce - cb;
+            int64_t lo = cb;
+            if (len > kScanPerFeature) {
+                const int64_t me = std::lower_bound(col_rows.begin() + cb, col_rows.begin() + ce, (int32_t)r) - col_rows.begin();
+                lo = std::max(cb, std::min(ce - kScanPerFeature, me - kScanPerFeature / 2));
+            }
+            const int64_t hi = std::min(ce, lo + kScanPerFeature);
+            for (int64_t q = lo; q < hi; ++q)
+                if (col_rows[(size_t)q] != (int32_t)r) ws.cand.push_back(col_rows[(size_t)q]);
+        }
+        std::sort(ws.cand.begin(), ws.cand.end());
+        ws.counted.clear();
+        for (size_t i = 0; i < ws.cand.size();) {
+            size_t j = i;
+            while (j < ws.cand.size() && ws.cand[j] == ws.cand[i]) ++j;
+            ws.counted.emplace_back(-(int32_t)(j - i), ws.cand[i]);
+            i = j;
+        }
+        if ((int)ws.counted.size() > kMaxCandidates) {
+            std::partial_sort(ws.counted.begin(), ws.counted.begin() + kMaxCandidates, ws.counted.end());
+            ws.counted.resize(kMaxCandidates);
+        }
+        ws.scored.clear();
+        for (auto& c : ws.counted) {
+            const double sc = sim((int32_t)r, c.second);
+            if (sc > 0.0) ws.scored.emplace_back(-sc, c.second);
+        }
+        keep = std::min(keep, ws.scored.size());
+        std::partial_sort(ws.scored.begin(), ws.scored.begin() + keep, ws.scored.end());
+        return keep;
+    };
+
+    // Is there anything to find?  Under the cost-guided partition a window only survives when its
+    // rows reuse columns (stored entries / distinct columns >= min_reuse).  For a sample of rows the
+    // best window the search could build around the row -- the row and its most similar candidates
+    // -- is put to that test; when fewer than a hundredth of the sampled rows pass, the search has
+    // nothing to offer over the given order (a heavy-tailed graph whose rows share hardly any
+    // column; a matrix whose columns are all too frequent to serve as features) and is skipped.
+    // The sample only needs the posting lists of its own feature columns, so the full index is
+    // built after the test.
+    bool searched = false;
+    if (o.partition == 1 && o.force_path == 0 && o.min_reuse > 1.f && o.reorder == 1) {
+        constexpr int64_t kSamples = 2048;
+        std::vector<int64_t> takes;
+        for (int64_t r = 0; r < n; ++r)
+            if (takes_part(r) && a.row_ptr[r + 1] > a.row_ptr[r]) takes.push_back(r);
+        const int64_t n_s = std::min<int64_t>(kSamples, (int64_t)takes.size());
+        std::vector<uint8_t> mark((size_t)a.n_cols, 0);
+        for (int64_t q = 0; q < n_s; ++q) {
+            std::pair<int32_t, int32_t> feat[kMaxFeatures];
+            const int nf = features_of(takes[(size_t)(q * (int64_t)takes.size() / n_s)], feat);
+            for (int i = 0; i < nf; ++i) mark[(size_t)feat[i].second] = 1;
+        }
+        build_index(&mark);
+        searched = true;
+        std::atomic<int64_t> pass{0};
+        parallel_chunks(n_s, threads, [&](int64_t b, int64_t e, int) {
+            RowScratch ws;
+            std::vector<int32_t> cols;
+            for (int64_t q = b; q < e; ++q) {
+                const int64_t r = takes[(size_t)(q * (int64_t)takes.size() / n_s)];
+                const size_t got = score_row(r, (size_t)o.window_rows - 1, ws);
+                int64_t entries = a.row_ptr[r + 1] - a.row_ptr[r];
+                cols.assign(a.col_idx + a.row_ptr[r], a.col_idx + a.row_ptr[r + 1]);
+                for (size_t i = 0; i < got; ++i) {
+                    const int32_t u = ws.scored[i].second;
+                    entries += a.row_ptr[u + 1] - a.row_ptr[u];
+                    cols.insert(cols.end(), a.col_idx + a.row_ptr[u], a.col_idx + a.row_ptr[u + 1]);
+                }
+                std::sort(cols.begin(), cols.end());
+                const int64_t distinct = std::unique(cols.begin(), cols.end()) - cols.begin();
+                if ((double)entries >= (double)o.min_reuse * (double)distinct) ++pass;
+            }
+        });
+        if (n_s > 0 && pass.load() * 100 < n_s) return RSH_OK;   // order stays the given one, objective not evaluated
+    }
+    (void)searched;
+    build_index(nullptr);
+
     std::vector<int32_t> nbr((size_t)n * (size_t)K, -1);
     std::vector<float> nbr_sim((size_t)n * (size_t)K, 0.f);
     parallel_dynamic(n, threads, 1024, [&](int64_t b, int64_t e, int) {
-        std::vector<int32_t> cand;
-        std::vector<std::pair<int32_t, int32_t>> counted;   // (-shared features, row)
-        std::vector<std::pair<double, int32_t>> scored;
+        RowScratch ws;
         for (int64_t r = b; r < e; ++r) {
             if (!takes_part(r)) continue;
-            // the row's lowest-degree eligible columns
-            std::pair<int32_t, int32_t> feat[kMaxFeatures];
-            int nf = 0;
-            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) {
-                const int32_t j = a.col_idx[p], d = col_deg[(size_t)j];
-                if (d < 2 || d > kMaxFeatureDegree) continue;
-                std::pair<int32_t, int32_t> f(d, j);
-                if (nf < kMaxFeatures) feat[nf++] = f;
-                else {
-                    int worst = 0;
-                    for (int i = 1; i < nf; ++i)
-                        if (feat[i] > feat[worst]) worst = i;
-                    if (f < feat[worst]) feat[worst] = f;
-                }
-            }
-            cand.clear();
-            for (int i = 0; i < nf; ++i) {
-                const int32_t j = feat[i].second;
-                const int64_t cb = col_ptr[(size_t)j], ce = col_end[(size_t)j];
-                // scan at most kScanPerFeature rows of the posting list, centred on r's own position
-                const int64_t len = ce - cb;
-                int64_t lo = cb;
-                if (len > kScanPerFeature) {
-                    const int64_t me = std::lower_bound(col_rows.begin() + cb, col_rows.begin() + ce, (int32_t)r) - col_rows.begin();
-                    lo = std::max(cb, std::min(ce - kScanPerFeature, me - kScanPerFeature / 2));
-                }
-                const int64_t hi = std::min(ce, lo + kScanPerFeature);
-                for (int64_t q = lo; q < hi; ++q)
-                    if (col_rows[(size_t)q] != (int32_t)r) cand.push_back(col_rows[(size_t)q]);
-            }
-            std::sort(cand.begin(), cand.end());
-            counted.clear();
-            for (size_t i = 0; i < cand.size();) {
-                size_t j = i;
-                while (j < cand.size() && cand[j] == cand[i]) ++j;
-                counted.emplace_back(-(int32_t)(j - i), cand[i]);
-                i = j;
-            }
-            if ((int)counted.size() > kMaxCandidates) {
-                std::partial_sort(counted.begin(), counted.begin() + kMaxCandidates, counted.end());
-                counted.resize(kMaxCandidates);
-            }
-            scored.clear();
-            for (auto& c : counted) {
-                const double s = sim((int32_t)r, c.second);
-                if (s > 0.0) scored.emplace_back(-s, c.second);
-            }
-            const size_t keep = std::min<size_t>((size_t)K, scored.size());
-            std::partial_sort(scored.begin(), scored.begin() + keep, scored.end());
+            const size_t keep = score_row(r, (size_t)K, ws);
             for (size_t i = 0; i < keep; ++i) {
-                nbr[(size_t)r * K + i] = scored[i].second;
-                nbr_sim[(size_t)r * K + i] = (float)-scored[i].first;
+                nbr[(size_t)r * K + i] = ws.scored[i].second;
+                nbr_sim[(size_t)r * K + i] = (float)-ws.scored[i].first;
             }
         }
     });
