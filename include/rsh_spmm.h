@@ -104,6 +104,12 @@ typedef struct {
                              and joined to the caller's stream by events, so that it may run beside the
                              residual-row kernel (the two write disjoint rows of C, Section 3.1);
                              0 (default) = all kernels in order on the caller's stream                 */
+    int32_t device_scoring; /* where the reordering search takes the affinities of Algorithm 3, step II:
+                             0 = host threads, 1 = a kernel on the current HIP device (the host still finds the
+                             candidates and picks the best knn_k; an error if the device cannot be used),
+                             2 (default) = the device when upload != 0 and the matrix has at least 131072
+                             rows, else the host.  Both take the same binary64 operations in the same order:
+                             neighbour lists, row order and plan do not depend on this option           */
 } rsh_plan_opts_t;
 
 /* What the planner built (host side, for tests, logs and the benchmark). */
@@ -251,6 +257,19 @@ int rsh_plan_decode(const rsh_plan_t *plan, int64_t *row_ptr, int32_t *col_idx, 
 /* The row processing order pi produced by the reordering stage: order[i] is the
  * original id of the i-th row.  order is caller-allocated [n_rows]. */
 int rsh_plan_row_order(const rsh_plan_t *plan, int32_t *order);
+
+/*
+ * The neighbour lists of the reordering search alone (Section 3.4, Algorithm 3, steps I-II:
+ * candidates through the inverted index over representative columns, then the knn_k most similar
+ * under the degree-weighted Jaccard affinity), for inspection and for comparing the host and the
+ * device scorer.  csr: host arrays as for rsh_plan_create.  opts: NULL = defaults; knn_k, alpha,
+ * partition, force_path, long_row_nnz, threads and device_scoring are used (device_scoring = 2
+ * decides as rsh_plan_create does with upload = 1).  nbr, nbr_sim: caller-allocated host arrays
+ * [n_rows * knn_k]; the neighbours of row r, most similar first (ties by row id), start at
+ * r * knn_k; unused slots hold -1 and 0.  With device_scoring = 1 a HIP device must be current;
+ * device memory for the pattern is allocated and freed inside the call.
+ */
+int rsh_reorder_knn(const rsh_csr_t *csr, const rsh_plan_opts_t *opts, int32_t *nbr, float *nbr_sim);
 
 /*
  * Read-only access to the host mirror of one plan array (exactly the bytes the

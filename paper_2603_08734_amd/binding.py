@@ -33,7 +33,7 @@ _ARRAY_DTYPES = {
 
 EXPORTED_SYMBOLS = [
     "rsh_plan_opts_default", "rsh_plan_create", "rsh_spmm", "rsh_spmm_noalloc", "rsh_spmm_f16", "rsh_spmm_profile", "rsh_copy_probe", "rsh_plan_destroy", "rsh_plan_stats",
-    "rsh_plan_decode", "rsh_plan_row_order", "rsh_plan_array", "rsh_plan_teams_per_wave",
+    "rsh_plan_decode", "rsh_plan_row_order", "rsh_reorder_knn", "rsh_plan_array", "rsh_plan_teams_per_wave",
     "rsh_struct_sizes", "rsh_status_string", "rsh_last_hip_error",
 ]
 
@@ -50,7 +50,8 @@ class rsh_plan_opts_t(ctypes.Structure):
                 ("max_nnz_per_slice", ctypes.c_int32), ("force_path", ctypes.c_int32),
                 ("min_reuse", ctypes.c_float), ("long_row_nnz", ctypes.c_int32),
                 ("window_schedule", ctypes.c_int32), ("hub_windows", ctypes.c_int32), ("xcd_partition_nnz", ctypes.c_int32), ("run_width", ctypes.c_int32), ("transpose", ctypes.c_int32), ("upload", ctypes.c_int32),
-                ("threads", ctypes.c_int32), ("side_stream", ctypes.c_int32)]
+                ("threads", ctypes.c_int32), ("side_stream", ctypes.c_int32),
+                ("device_scoring", ctypes.c_int32)]
 
 
 class rsh_kernel_times_t(ctypes.Structure):
@@ -100,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.rsh_plan_stats.argtypes = [vp, ctypes.POINTER(rsh_plan_stats_t)]
         L.rsh_plan_decode.argtypes = [vp, vp, vp, vp, vp]
         L.rsh_plan_row_order.argtypes = [vp, vp]
+        L.rsh_reorder_knn.argtypes = [ctypes.POINTER(rsh_csr_t), ctypes.POINTER(rsh_plan_opts_t), vp, vp]
         L.rsh_plan_array.argtypes = [vp, i32, ctypes.POINTER(vp), i64p]
         L.rsh_plan_teams_per_wave.argtypes = [vp, ctypes.POINTER(i32)]
         L.rsh_struct_sizes.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
@@ -145,6 +147,26 @@ def rsh_copy_probe(src, dst, nbytes: int, stream=None) -> None:
         stream = torch.cuda.current_stream().cuda_stream
     _check(lib().rsh_copy_probe(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), int(nbytes),
                                 ctypes.c_void_p(stream)))
+
+
+def rsh_reorder_knn(row_ptr, col_idx, n_cols: int, opts: rsh_plan_opts_t | None = None, **kw):
+    """Neighbour lists of the reordering search (rsh_reorder_knn): (ids int32 [n_rows, knn_k], affinities
+    float32 [n_rows, knn_k])."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    if opts is None:
+        opts = rsh_plan_opts_default()
+    for k, v in kw.items():
+        if not hasattr(opts, k):
+            raise TypeError(f"unknown plan option {k}")
+        setattr(opts, k, v)
+    n_rows = row_ptr.shape[0] - 1
+    val = np.zeros(col_idx.shape[0], dtype=np.uint16)
+    csr = rsh_csr_t(n_rows, int(n_cols), int(col_idx.shape[0]), row_ptr.ctypes.data, col_idx.ctypes.data, val.ctypes.data)
+    nbr = np.empty((n_rows, opts.knn_k), dtype=np.int32)
+    sim = np.empty((n_rows, opts.knn_k), dtype=np.float32)
+    _check(lib().rsh_reorder_knn(ctypes.byref(csr), ctypes.byref(opts), nbr.ctypes.data, sim.ctypes.data))
+    return nbr, sim
 
 
 class Plan:

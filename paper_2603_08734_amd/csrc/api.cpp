@@ -20,6 +20,10 @@ namespace {
 
 thread_local std::string g_hip_error;
 
+// device_scoring = 2: below this many rows the device's set-up (pattern upload, pinned tables)
+// costs more than the host threads need for the affinities
+constexpr int64_t kDeviceScoringRows = 131072;
+
 
 bool hip_ok(hipError_t e) {
     if (e == hipSuccess) return true;
@@ -192,6 +196,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->upload = 1;
     o->threads = 0;
     o->side_stream = 0;
+    o->device_scoring = 2;
     return RSH_OK;
 }
 
@@ -214,6 +219,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     if (o.reorder < 0 || o.reorder > 3 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.threads < 0 || o.transpose < 0 || o.transpose > 1 || o.side_stream < 0 || o.side_stream > 1) return RSH_ERR_BAD_OPTION;
+    if (o.device_scoring < 0 || o.device_scoring > 2) return RSH_ERR_BAD_OPTION;
 
     const auto t_all = std::chrono::steady_clock::now();
     auto t0 = t_all;
@@ -269,6 +275,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         h.stats.ms_validate = ms_since(t0);
 
         t0 = std::chrono::steady_clock::now();
+        if (o.device_scoring == 2) o.device_scoring = (o.upload && csr->n_rows >= kDeviceScoringRows) ? 1 : 0;
         if (o.reorder) {
             rc = rsh::reorder_rows(*csr, o, col_deg, h.order, threads, &h.stats.reorder_cost_given, &h.stats.reorder_cost_found);
             if (rc) throw rc;
@@ -480,6 +487,43 @@ int rsh_plan_decode(const rsh_plan_t* plan, int64_t* row_ptr, int32_t* col_idx, 
     } catch (...) {
         return RSH_ERR_OOM;
     }
+}
+
+int rsh_reorder_knn(const rsh_csr_t* csr, const rsh_plan_opts_t* opts, int32_t* nbr, float* nbr_sim) {
+    if (!csr || !nbr || !nbr_sim) return RSH_ERR_NULL;
+    rsh_plan_opts_t o;
+    rsh_plan_opts_default(&o);
+    if (opts) o = *opts;
+    if (o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f) || o.threads < 0 || o.device_scoring < 0 || o.device_scoring > 2 ||
+        o.partition < 0 || o.partition > 1 || o.force_path < 0 || o.force_path > 2 || o.long_row_nnz < 0)
+        return RSH_ERR_BAD_OPTION;
+    int rc = rsh::validate_csr(*csr);
+    if (rc) return rc;
+    if (csr->nnz >= (1ll << 31) || csr->n_rows >= (1ll << 31) - 1 || csr->n_cols >= (1ll << 31)) return RSH_ERR_TOO_LARGE;
+    try {
+        const int threads = o.threads > 0 ? o.threads : rsh::hardware_threads();
+        if (o.device_scoring == 2) o.device_scoring = csr->n_rows >= kDeviceScoringRows ? 1 : 0;
+        if (o.window_rows == 0) o.window_rows = rsh::kW;
+        std::vector<int32_t> col_deg, order;
+        rsh::column_degrees(*csr, col_deg, threads);
+        rsh::KnnLists lists;
+        double given, found;
+        rc = rsh::reorder_rows(*csr, o, col_deg, order, threads, &given, &found, &lists);
+        if (rc) return rc;
+        const size_t cells = (size_t)csr->n_rows * (size_t)o.knn_k;
+        if (lists.nbr.size() != cells) {   // fewer than three rows or no entries: nobody has neighbours
+            std::fill(nbr, nbr + cells, -1);
+            std::fill(nbr_sim, nbr_sim + cells, 0.f);
+        } else {
+            std::memcpy(nbr, lists.nbr.data(), cells * sizeof(int32_t));
+            std::memcpy(nbr_sim, lists.sim.data(), cells * sizeof(float));
+        }
+    } catch (const std::bad_alloc&) {
+        return RSH_ERR_OOM;
+    } catch (...) {
+        return RSH_ERR_OOM;
+    }
+    return RSH_OK;
 }
 
 int rsh_plan_row_order(const rsh_plan_t* plan, int32_t* order) {

@@ -1089,6 +1089,63 @@ int launch_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
 }
 
 // ---------------------------------------------------------------------------
+// planning: affinity of candidate row pairs (Section 3.4, Algorithm 3 step II)
+// ---------------------------------------------------------------------------
+// One thread per pair (rows[p / 64], cand[p]) of a table with 64 candidate slots per row (an unused
+// slot holds -1 and scores 0).  The degree-weighted Jaccard affinity w(S_r & S_u) / w(S_r | S_u) is
+// taken in binary64 exactly as the host planner takes it: the shared columns' weights are added in
+// ascending column order, the union's weight is row_w[r] + row_w[u] - that sum, and the quotient is
+// one IEEE division -- so the scores, and the neighbour lists chosen from them, equal the host's
+// bit for bit.  The 64 lanes of a wave share the row r, whose columns they all re-read from cache.
+__global__ __launch_bounds__(256) void rsh_score_pairs_kernel(const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+                                                              const double* __restrict__ w, const double* __restrict__ row_w,
+                                                              const int32_t* __restrict__ rows, const int32_t* __restrict__ cand,
+                                                              double* __restrict__ score, uint32_t n_pairs) {
+    const uint32_t p = blockIdx.x * 256u + threadIdx.x;
+    if (p >= n_pairs) return;
+    const int32_t u = cand[p];
+    double s = 0.0;
+    if (u >= 0) {
+        const int32_t r = rows[p >> 6];
+        int64_t i = row_ptr[r], j = row_ptr[u];
+        const int64_t ie = row_ptr[r + 1], je = row_ptr[u + 1];
+        double inter = 0.0;
+        if (i < ie && j < je) {
+            int32_t ci = col_idx[i], cj = col_idx[j];
+            for (;;) {
+                if (ci < cj) {
+                    if (++i == ie) break;
+                    ci = col_idx[i];
+                } else if (cj < ci) {
+                    if (++j == je) break;
+                    cj = col_idx[j];
+                } else {
+                    inter += w[ci];
+                    ++i;
+                    ++j;
+                    if (i == ie || j == je) break;
+                    ci = col_idx[i];
+                    cj = col_idx[j];
+                }
+            }
+        }
+        const double uni = row_w[r] + row_w[u] - inter;
+        s = uni > 0.0 ? inter / uni : 0.0;
+    }
+    score[p] = s;
+}
+
+int launch_score_pairs(const int64_t* row_ptr, const int32_t* col_idx, const double* w, const double* row_w, const int32_t* rows,
+                       const int32_t* cand, double* score, int64_t n_table_rows, void* stream) {
+    if (n_table_rows <= 0) return RSH_OK;
+    if (n_table_rows > (1 << 24)) return RSH_ERR_TOO_LARGE;   // pairs are counted in 32 bits
+    const uint32_t n_pairs = (uint32_t)n_table_rows * 64u;
+    hipLaunchKernelGGL(rsh_score_pairs_kernel, dim3((n_pairs + 255) / 256), dim3(256), 0, (hipStream_t)stream, row_ptr, col_idx, w,
+                       row_w, rows, cand, score, n_pairs);
+    return hipGetLastError() == hipSuccess ? RSH_OK : RSH_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
 // Grid size: 8 x the number of blocks the largest XCD part needs.

@@ -63,4 +63,11 @@ int launch_narrow_rows(const void* src, void* dst, int64_t rows, int n, int n_pa
 // Plain device-to-device copy of `bytes` (multiple of 16) used to calibrate traffic counters.
 int launch_copy_probe(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
 
+// Planning, Algorithm 3 step II on the device: score[64 * i + c] = weighted Jaccard affinity of rows
+// rows[i] and cand[64 * i + c] (0 where cand holds -1), in binary64 with the host planner's order of
+// operations.  All pointers are device memory; the CSR pattern, column weights w and row weight
+// sums row_w are the ones the host scorer uses.  At most 2^24 table rows per call.
+int launch_score_pairs(const int64_t* row_ptr, const int32_t* col_idx, const double* w, const double* row_w, const int32_t* rows,
+                       const int32_t* cand, double* score, int64_t n_table_rows, void* stream);
+
 }  // namespace rsh

@@ -90,8 +90,14 @@ struct Partition {
 int validate_csr(const rsh_csr_t& a);
 void column_degrees(const rsh_csr_t& a, std::vector<int32_t>& deg, int threads);
 void estimate_threshold(int64_t n_rows, int64_t nnz, int32_t* tau_nnz, int32_t* tau_inc);
+// Neighbour lists of Algorithm 3 step II: n_rows x knn_k row ids (-1 = no further neighbour) and affinities.
+struct KnnLists {
+    std::vector<int32_t> nbr;
+    std::vector<float> sim;
+};
+// With `knn_only` the search stops after step II and hands out its lists (the order is left as given).
 int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& col_deg,
-                 std::vector<int32_t>& order, int threads, double* cost_given, double* cost_found);
+                 std::vector<int32_t>& order, int threads, double* cost_given, double* cost_found, KnnLists* knn_only = nullptr);
 void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& order,
                     int32_t tau_nnz, int32_t tau_inc, Partition& out, int threads);
 // Window height for a partition made with 16-row windows: 16, 32 or 64 (see rsh_plan_opts_t::window_rows).

@@ -23,7 +23,16 @@
 //   * the found order replaces the given one only if it lowers the objective by >= 3 %;
 //   * before the search, a sample of rows is tested for whether the best window around a row could
 //     pass the partition's reuse test at all; if hardly any does, the given order is kept as it is.
+//
+// Step II's affinities can be taken on the GPU (rsh_plan_opts_t::device_scoring): the host still
+// finds each row's candidates through the inverted index and picks the best k afterwards, the
+// device scores the (row, candidate) pairs in between, block of rows by block of rows, while the
+// host works on the neighbouring blocks.  Host and device take every affinity with the same
+// binary64 operations in the same order, so both ways give the same lists and the same plan.
+#include "launch.hpp"
 #include "plan.hpp"
+
+#include <hip/hip_runtime_api.h>
 
 #include <algorithm>
 #include <atomic>
@@ -92,10 +101,76 @@ struct Dsu {
     }
 };
 
+// Device side of step II: the CSR pattern, the column weights and the rows' weight sums live on the
+// device for the duration of the search; (rows, candidates) tables go up and score tables come back
+// through two sets of pinned buffers, so that the host fills one while the device works on the other.
+struct DeviceScorer {
+    static constexpr int64_t kBlockRows = 32768;   // table rows per launch: 8 MiB of candidates up, 16 MiB of scores back
+    int64_t* row_ptr = nullptr;
+    int32_t* col_idx = nullptr;
+    double *w = nullptr, *row_w = nullptr;
+    int32_t *rows[2] = {nullptr, nullptr}, *cand[2] = {nullptr, nullptr};
+    double* score[2] = {nullptr, nullptr};
+    int32_t *h_rows[2] = {nullptr, nullptr}, *h_cand[2] = {nullptr, nullptr};
+    double* h_score[2] = {nullptr, nullptr};
+    hipStream_t stream = nullptr;
+    hipEvent_t done[2] = {nullptr, nullptr};
+
+    int open(const rsh_csr_t& a, const std::vector<double>& wv, const std::vector<double>& rwv) {
+        bool ok = hipMalloc((void**)&row_ptr, ((size_t)a.n_rows + 1) * 8) == hipSuccess &&
+                  hipMalloc((void**)&col_idx, std::max<size_t>(4, (size_t)a.nnz * 4)) == hipSuccess &&
+                  hipMalloc((void**)&w, std::max<size_t>(8, wv.size() * 8)) == hipSuccess &&
+                  hipMalloc((void**)&row_w, std::max<size_t>(8, rwv.size() * 8)) == hipSuccess &&
+                  hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) == hipSuccess;   // default priority
+        for (int s = 0; s < 2 && ok; ++s)
+            ok = hipMalloc((void**)&rows[s], kBlockRows * 4) == hipSuccess && hipMalloc((void**)&cand[s], kBlockRows * 64 * 4) == hipSuccess &&
+                 hipMalloc((void**)&score[s], kBlockRows * 64 * 8) == hipSuccess &&
+                 hipHostMalloc((void**)&h_rows[s], kBlockRows * 4, hipHostMallocDefault) == hipSuccess &&
+                 hipHostMalloc((void**)&h_cand[s], kBlockRows * 64 * 4, hipHostMallocDefault) == hipSuccess &&
+                 hipHostMalloc((void**)&h_score[s], kBlockRows * 64 * 8, hipHostMallocDefault) == hipSuccess &&
+                 hipEventCreateWithFlags(&done[s], hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipMemcpy(row_ptr, a.row_ptr, ((size_t)a.n_rows + 1) * 8, hipMemcpyHostToDevice) == hipSuccess &&
+             (a.nnz == 0 || hipMemcpy(col_idx, a.col_idx, (size_t)a.nnz * 4, hipMemcpyHostToDevice) == hipSuccess) &&
+             (wv.empty() || hipMemcpy(w, wv.data(), wv.size() * 8, hipMemcpyHostToDevice) == hipSuccess) &&
+             (rwv.empty() || hipMemcpy(row_w, rwv.data(), rwv.size() * 8, hipMemcpyHostToDevice) == hipSuccess);
+        return ok ? RSH_OK : RSH_ERR_HIP;
+    }
+    // tables of `n` rows in pinned buffer set `s` -> device -> scores back into h_score[s]; asynchronous
+    int submit(int s, int64_t n) {
+        if (hipMemcpyAsync(rows[s], h_rows[s], (size_t)n * 4, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(cand[s], h_cand[s], (size_t)n * 64 * 4, hipMemcpyHostToDevice, stream) != hipSuccess)
+            return RSH_ERR_HIP;
+        const int rc = launch_score_pairs(row_ptr, col_idx, w, row_w, rows[s], cand[s], score[s], n, stream);
+        if (rc) return rc;
+        if (hipMemcpyAsync(h_score[s], score[s], (size_t)n * 64 * 8, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+            hipEventRecord(done[s], stream) != hipSuccess)
+            return RSH_ERR_HIP;
+        return RSH_OK;
+    }
+    int wait(int s) { return hipEventSynchronize(done[s]) == hipSuccess ? RSH_OK : RSH_ERR_HIP; }
+    ~DeviceScorer() {
+        if (stream) (void)hipStreamSynchronize(stream);
+        for (int s = 0; s < 2; ++s) {
+            if (done[s]) (void)hipEventDestroy(done[s]);
+            if (h_score[s]) (void)hipHostFree(h_score[s]);
+            if (h_cand[s]) (void)hipHostFree(h_cand[s]);
+            if (h_rows[s]) (void)hipHostFree(h_rows[s]);
+            if (score[s]) (void)hipFree(score[s]);
+            if (cand[s]) (void)hipFree(cand[s]);
+            if (rows[s]) (void)hipFree(rows[s]);
+        }
+        if (stream) (void)hipStreamDestroy(stream);
+        if (row_w) (void)hipFree(row_w);
+        if (w) (void)hipFree(w);
+        if (col_idx) (void)hipFree(col_idx);
+        if (row_ptr) (void)hipFree(row_ptr);
+    }
+};
+
 }  // namespace
 
 int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector<int32_t>& col_deg,
-                 std::vector<int32_t>& order, int threads, double* cost_given, double* cost_found) {
+                 std::vector<int32_t>& order, int threads, double* cost_given, double* cost_found, KnnLists* knn_only) {
     const int64_t n = a.n_rows;
     *cost_given = *cost_found = 0.0;
     const int K = o.knn_k;
@@ -164,8 +239,9 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
         std::vector<std::pair<int32_t, int32_t>> counted;   // (-shared features, row)
         std::vector<std::pair<double, int32_t>> scored;     // (-affinity, row), best first after the call
     };
-    // candidates of row r through the inverted index, scored; the best `keep` come first in ws.scored
-    auto score_row = [&](int64_t r, size_t keep, RowScratch& ws) {
+    // candidates of row r through the inverted index: the (at most kMaxCandidates) rows that share most
+    // of r's feature columns, in ws.counted
+    auto candidates_of = [&](int64_t r, RowScratch& ws) {
         std::pair<int32_t, int32_t> feat[kMaxFeatures];
         const int nf = features_of(r, feat);
         ws.cand.clear();
@@ -195,6 +271,10 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
             std::partial_sort(ws.counted.begin(), ws.counted.begin() + kMaxCandidates, ws.counted.end());
             ws.counted.resize(kMaxCandidates);
         }
+    };
+    // the candidates scored on the host; the best `keep` come first in ws.scored
+    auto score_row = [&](int64_t r, size_t keep, RowScratch& ws) {
+        candidates_of(r, ws);
         ws.scored.clear();
         for (auto& c : ws.counted) {
             const double sc = sim((int32_t)r, c.second);
@@ -214,7 +294,7 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     // The sample only needs the posting lists of its own feature columns, so the full index is
     // built after the test.
     bool searched = false;
-    if (o.partition == 1 && o.force_path == 0 && o.min_reuse > 1.f && o.reorder == 1) {
+    if (o.partition == 1 && o.force_path == 0 && o.min_reuse > 1.f && o.reorder == 1 && !knn_only) {
         constexpr int64_t kSamples = 2048;
         std::vector<int64_t> takes;
         for (int64_t r = 0; r < n; ++r)
@@ -254,17 +334,82 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
 
     std::vector<int32_t> nbr((size_t)n * (size_t)K, -1);
     std::vector<float> nbr_sim((size_t)n * (size_t)K, 0.f);
-    parallel_dynamic(n, threads, 1024, [&](int64_t b, int64_t e, int) {
-        RowScratch ws;
-        for (int64_t r = b; r < e; ++r) {
-            if (!takes_part(r)) continue;
-            const size_t keep = score_row(r, (size_t)K, ws);
-            for (size_t i = 0; i < keep; ++i) {
-                nbr[(size_t)r * K + i] = ws.scored[i].second;
-                nbr_sim[(size_t)r * K + i] = (float)-ws.scored[i].first;
+    auto keep_lists = [&](int64_t r, size_t keep, const RowScratch& ws) {
+        for (size_t i = 0; i < keep; ++i) {
+            nbr[(size_t)r * K + i] = ws.scored[i].second;
+            nbr_sim[(size_t)r * K + i] = (float)-ws.scored[i].first;
+        }
+    };
+    if (!o.device_scoring) {
+        parallel_dynamic(n, threads, 1024, [&](int64_t b, int64_t e, int) {
+            RowScratch ws;
+            for (int64_t r = b; r < e; ++r)
+                if (takes_part(r)) keep_lists(r, score_row(r, (size_t)K, ws), ws);
+        });
+    } else {
+        std::vector<int32_t> rows_in;   // rows that look for neighbours
+        for (int64_t r = 0; r < n; ++r)
+            if (takes_part(r) && a.row_ptr[r + 1] > a.row_ptr[r]) rows_in.push_back((int32_t)r);
+        DeviceScorer dev;
+        int rc = dev.open(a, w, row_w);
+        if (rc) return rc;
+        constexpr int64_t B = DeviceScorer::kBlockRows;
+        const int64_t n_in = (int64_t)rows_in.size(), n_blocks = (n_in + B - 1) / B;
+        auto fill = [&](int64_t blk, int s) {   // candidate table of a block into pinned set s
+            const int64_t base = blk * B, cnt = std::min(B, n_in - base);
+            parallel_dynamic(cnt, threads, 512, [&](int64_t b, int64_t e, int) {
+                RowScratch ws;
+                for (int64_t i = b; i < e; ++i) {
+                    const int32_t r = rows_in[(size_t)(base + i)];
+                    candidates_of(r, ws);
+                    dev.h_rows[s][i] = r;
+                    int32_t* slot = dev.h_cand[s] + i * 64;
+                    size_t c = 0;
+                    for (; c < ws.counted.size(); ++c) slot[c] = ws.counted[c].second;
+                    for (; c < 64; ++c) slot[c] = -1;
+                }
+            });
+            return cnt;
+        };
+        auto pick = [&](int64_t blk, int s) {   // best k of a block from the scores that came back in set s
+            const int64_t base = blk * B, cnt = std::min(B, n_in - base);
+            parallel_dynamic(cnt, threads, 512, [&](int64_t b, int64_t e, int) {
+                RowScratch ws;
+                for (int64_t i = b; i < e; ++i) {
+                    ws.scored.clear();
+                    for (int c = 0; c < 64; ++c) {
+                        const int32_t u = dev.h_cand[s][i * 64 + c];
+                        const double sc = dev.h_score[s][i * 64 + c];
+                        if (u >= 0 && sc > 0.0) ws.scored.emplace_back(-sc, u);
+                    }
+                    const size_t keep = std::min((size_t)K, ws.scored.size());
+                    std::partial_sort(ws.scored.begin(), ws.scored.begin() + keep, ws.scored.end());
+                    keep_lists(rows_in[(size_t)(base + i)], keep, ws);
+                }
+            });
+        };
+        static_assert(kMaxCandidates == 64, "the device table has 64 candidate slots per row");
+        for (int64_t blk = 0; blk < n_blocks; ++blk) {
+            const int s = (int)(blk & 1);
+            rc = dev.submit(s, fill(blk, s));
+            if (rc) return rc;
+            if (blk > 0) {   // the device scores this block while the host finishes the previous one
+                rc = dev.wait(s ^ 1);
+                if (rc) return rc;
+                pick(blk - 1, s ^ 1);
             }
         }
-    });
+        if (n_blocks > 0) {
+            rc = dev.wait((int)((n_blocks - 1) & 1));
+            if (rc) return rc;
+            pick(n_blocks - 1, (int)((n_blocks - 1) & 1));
+        }
+    }
+    if (knn_only) {
+        knn_only->nbr = std::move(nbr);
+        knn_only->sim = std::move(nbr_sim);
+        return RSH_OK;
+    }
 
     // ---- step III: undirected kNN graph -> maximum-affinity spanning forest -> DFS order ------
     std::vector<Edge> edges;

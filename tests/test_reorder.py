@@ -112,3 +112,64 @@ def test_stages_of_the_reordering_can_be_stopped_early():
     assert cost[3] <= cost[2] + 1e-9
     with pytest.raises(Exception):
         host_plan(A, 64, reorder=4)
+
+
+# --- the neighbour lists of steps I-II on their own (rsh_reorder_knn) --------------------------------
+
+def _oracle_affinity(A, deg, r, u, alpha=0.5):
+    return osim.w_jaccard(osim.row_set(A.row_ptr, A.col_idx, r), osim.row_set(A.row_ptr, A.col_idx, u), deg, alpha)
+
+
+def test_neighbour_lists_equal_brute_force_when_the_index_sees_every_pair():
+    """Rows with at most 4 columns, every column in few rows: all of a row's columns are its features,
+    every posting list is scanned whole and no row has more than 64 candidates, so the candidates are
+    all rows that share a column and the lists must be the exact k nearest under the oracle's
+    affinity (ties by row id)."""
+    from paper_2603_08734_amd.binding import rsh_reorder_knn
+    rng = np.random.default_rng(5)
+    n_rows, n_cols, K = 300, 60, 6
+    keys = np.unique(np.repeat(np.arange(n_rows), 3) * n_cols + rng.integers(0, n_cols, size=3 * n_rows))
+    A = from_coo(keys // n_cols, keys % n_cols, np.ones(keys.size, dtype=np.float16), n_rows, n_cols)
+    deg = osim.column_degree(A.col_idx, n_cols)
+    assert 3 * (deg.max() - 1) <= 64 and deg.min() >= 2
+    nbr, sim = rsh_reorder_knn(A.row_ptr, A.col_idx, n_cols, knn_k=K, device_scoring=0, force_path=2)
+    sets = [osim.row_set(A.row_ptr, A.col_idx, r) for r in range(n_rows)]
+    for r in range(n_rows):
+        scored = []
+        for u in range(n_rows):
+            if u != r and sets[r] & sets[u]:
+                scored.append((-osim.w_jaccard(sets[r], sets[u], deg, 0.5), u))
+        scored.sort()
+        want = scored[:K]
+        got = [(float(sim[r, i]), int(nbr[r, i])) for i in range(K) if nbr[r, i] >= 0]
+        assert len(got) == len(want)
+        # ids may differ only among candidates whose affinities agree to rounding (the oracle sums the
+        # union's weights, the library subtracts the shared weight from the two rows' sums)
+        for (gs, gu), (ws, wu) in zip(got, want):
+            assert abs(gs + ws) <= 1e-6
+            assert gu == wu or abs(_oracle_affinity(A, deg, r, gu) + ws) <= 1e-12
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_neighbour_lists_are_sorted_and_hold_the_oracles_affinities(k):
+    from paper_2603_08734_amd.binding import rsh_reorder_knn
+    A, _, _ = make_config(k, small=True)
+    nbr, sim = rsh_reorder_knn(A.row_ptr, A.col_idx, A.n_cols, device_scoring=0)
+    assert nbr.shape == (A.n_rows, 8)
+    deg = osim.column_degree(A.col_idx, A.n_cols)
+    rng = np.random.default_rng(k)
+    for r in rng.choice(A.n_rows, size=min(A.n_rows, 200), replace=False):
+        ids = nbr[r][nbr[r] >= 0]
+        assert np.all(nbr[r][len(ids):] == -1) and np.all(sim[r][len(ids):] == 0)
+        assert r not in ids and len(set(ids.tolist())) == len(ids)
+        assert np.all(np.diff(sim[r][:len(ids)]) <= 0) and np.all(sim[r][:len(ids)] > 0)
+        for i, u in enumerate(ids):
+            assert abs(_oracle_affinity(A, deg, int(r), int(u)) - float(sim[r, i])) <= 1e-6
+
+
+def test_neighbour_lists_do_not_depend_on_the_thread_count():
+    from paper_2603_08734_amd.binding import rsh_reorder_knn
+    A, _, _ = make_config(2, small=True)
+    a = rsh_reorder_knn(A.row_ptr, A.col_idx, A.n_cols, device_scoring=0, threads=1)
+    b = rsh_reorder_knn(A.row_ptr, A.col_idx, A.n_cols, device_scoring=0, threads=7)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
