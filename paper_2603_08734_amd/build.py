@@ -47,7 +47,7 @@ def needs_build() -> bool:
 
 def build(force: bool = True) -> str:
     if force or needs_build():
-        cmd = [HIPCC, *FLAGS, *os.environ.get("RSH_EXTRA_FLAGS", "").split(), "-o", LIB, *sources(), "-lpthread"]
+        cmd = [HIPCC, *FLAGS, "-o", LIB, *sources(), "-lpthread"]
         subprocess.check_call(cmd)
         with open(STAMP, "w") as f:
             f.write(source_digest() + "\n")

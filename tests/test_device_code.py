@@ -82,3 +82,19 @@ def test_tile_loop_waits_do_not_drain_global_loads(kernels_asm):
     loop = loop[:loop.index("s_endpgm")] if "s_endpgm" in loop else loop
     waits = re.findall(r"s_waitcnt vmcnt\((\d+)\)", loop[:loop.index("s_cbranch_scc")])
     assert waits and all(int(w) > 0 for w in waits), waits
+
+
+def test_panel_kernels_use_the_32_row_mfma_and_transposing_reads(kernels_asm):
+    """Windows of 128 or 256 rows: the product is formed by v_mfma_f32_32x32x16_f16 with the staged
+    B tile read through the transposing LDS load, entries arrive as 16-byte loads, and rows of C
+    leave as streaming 16-byte stores (partial sums as ordinary ones)."""
+    panel = {n: b for n, b in kernels_asm.items() if "rsh_panel_kernel" in n}
+    assert panel
+    for name, body in panel.items():
+        assert "v_mfma_f32_32x32x16_f16" in body and "ds_read_b64_tr_b16" in body, name
+        assert "global_load_dwordx4" in body and "ds_write_b16" in body, name
+        n, nt = _stores(body)   # each kernel holds both ends: rows of C (streaming) and partial sums (ordinary)
+        if "OutPlain" in name:
+            assert n > 0 and nt * 2 == n, f"{name}: {nt} of {n} stores are streaming"
+        else:   # binary16 rows of C are half as wide
+            assert any("global_store_dword" in l and " nt" in l for l in body.splitlines()), name
