@@ -683,9 +683,10 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         // Tall windows: a workgroup sums an item's fragments in two levels (every 1024 condensed
         // columns the running sums are added to a second set), so an item may be long; windows are
         // only cut to hand every compute unit the workgroups it can hold (two of 128 rows, one of
-        // 256), never below 1024 columns.
+        // 256), never below 1024 columns; the cap keeps the second level's chain at a few hundred
+        // additions (an item is at most 1.5 times this long).
         const int64_t target_items = geo.win_rows >= 256 ? 256 : 512;
-        t_max = std::max<int64_t>(1024 / kPanelK, (n_tiles + target_items - 1) / target_items);
+        t_max = std::min<int64_t>(8192, std::max<int64_t>(1024 / kPanelK, (n_tiles + target_items - 1) / target_items));
     } else if (t_max <= 0) {
         int64_t per = (n_tiles + 4095) / 4096, p2 = 1;
         while (p2 < per) p2 <<= 1;
