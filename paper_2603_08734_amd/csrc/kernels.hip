@@ -669,15 +669,18 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 // Tall windows: the panel kernel.  Where many rows name the same columns (a pruned weight matrix:
 // every window covers nearly all columns) the dense-fragment path is bound by its own instructions,
 // not by memory, so this form spends as few as possible per multiply-add:
-//   * a window is 128 rows, one workgroup of four waves, each wave owning a row group of 32 rows and
-//     the whole feature panel (up to 128 features) on v_mfma_f32_32x32x16_f16 -- per transposing LDS
-//     read of B and per expanded cell of A twice the multiply-adds of the 16 x 16 shapes;
-//   * a fragment's 32 B rows are staged in LDS once per workgroup, double-buffered, one barrier per
-//     fragment; rows in flight sit in registers two fragments ahead;
+//   * a window is 128 or 256 rows, one workgroup of four or eight waves, each wave owning a row group
+//     of 32 rows and the whole feature panel (up to 128 features) on v_mfma_f32_32x32x16_f16 -- per
+//     transposing LDS read of B and per expanded cell of A twice the multiply-adds of the 16 x 16 shapes;
+//   * a fragment's 32 B rows are staged in LDS once per workgroup, in one of four tiles (fragment s in
+//     tile s mod 4), two fragments ahead of their use, one barrier per pair of fragments; rows in
+//     flight sit in registers three fragments ahead;
 //   * the stored entries of a 32 x 16 unit carry the byte address of their cell in the MFMA operand,
 //     so the wave scatters them into a zeroed 1 KB LDS tile of its own (work proportional to the
-//     entries) and reads the operand back with one 16-byte read per lane, where the bitmap form
-//     expands cell by cell; a wave's entries are one contiguous stream, fetched three fragments ahead;
+//     entries; two sets of tiles, fragment s in set s mod 2) and reads the operand back with one
+//     16-byte read per lane, where the bitmap form expands cell by cell; a wave's entries are one
+//     contiguous stream, fetched four fragments ahead;
+//   * the LDS reads of a K step's operands are issued one K step before its multiply-adds;
 //   * sums are kept in two levels (every 1024 condensed columns the running sums are added to a
 //     second set and cleared), which bounds the fp32 accumulation chain whatever the item length, so
 //     windows are cut into few, long items and few partial sums cross HBM.
@@ -690,21 +693,24 @@ __global__ __launch_bounds__(NW == 1 ? 64 * kWavesPerBlock : 64 * NW) void rsh_t
 // ---------------------------------------------------------------------------
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-// NG = row groups (waves) per window: 4 (128 rows) or 8 (256 rows)
-template <int NCH32, int NG>
+// NG = row groups per window: 4 (128 rows) or 8 (256 rows); RG = row groups per wave: 1 or 2
+template <int NCH32, int NG, int RG>
 struct PanelGeom {
     static constexpr int P = 32 * NCH32;                      // features per panel
-    static constexpr int THREADS = 64 * NG;
+    static constexpr int WAVES = NG / RG;
+    static constexpr int THREADS = 64 * WAVES;
     static constexpr int TPR = P / 8;                         // 16-byte pieces per staged B row
     static constexpr int LDB = P >= 64 ? P + 32 : 32;         // LDS row stride in halves: rows 16 banks apart (mod 64)
     static constexpr int PIECES = kPanelK * TPR;              // pieces of one staged tile
     static constexpr int NLD = (PIECES + THREADS - 1) / THREADS;   // pieces per thread
     static constexpr int IDLE = NLD * THREADS - PIECES;       // threads without a piece (narrow panels) stage into spare space
     static constexpr int TILE_HALVES = kPanelK * LDB + 8 * IDLE;
-    static constexpr int WAVE_A_BYTES = 2 * 1024 + 256;       // a wave's two operand tiles and a spare word per lane
-    static constexpr int LOOP_BYTES = 2 * TILE_HALVES * 2 + NG * WAVE_A_BYTES;   // two B tiles + the waves' operand tiles
+    static constexpr int NBUF = 4;                            // staged B tiles (fragment s lives in tile s mod 4)
+    static constexpr int SET_A_BYTES = 2 * 1024 + 256;        // one set of a row group's operand tiles (two K steps) and a spare word per lane
+    static constexpr int GROUP_A_BYTES = 2 * SET_A_BYTES;     // two sets: fragment s lives in set s mod 2
+    static constexpr int LOOP_BYTES = NBUF * TILE_HALVES * 2 + NG * GROUP_A_BYTES;
     static constexpr int STAGE_STRIDE = 36;                   // floats per staged output row (32 + pad)
-    static constexpr int STAGE_BYTES = NG * 32 * STAGE_STRIDE * 4;
+    static constexpr int STAGE_BYTES = WAVES * 32 * STAGE_STRIDE * 4;
     static constexpr int SMEM_BYTES = LOOP_BYTES > STAGE_BYTES ? LOOP_BYTES : STAGE_BYTES;
 };
 
@@ -715,24 +721,30 @@ __device__ __forceinline__ void panel_store(const OutFused& o, size_t row, int N
     __builtin_nontemporal_store(finish4(o, f, v), reinterpret_cast<uint2_t*>(o.C + row * N + f));
 }
 
-// R = 16-byte loads per lane (four entries each, 256 per wave) that cover the largest unit: 1 or 2
-template <int NCH32, int NG, int R, class OUT>
-__global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
+// R = 16-byte loads per lane (four entries each, 256 per wave) that cover the largest unit: 1 or 2.
+// RG = row groups per wave.  With RG = 2 one transposing read of the staged B tile feeds two
+// multiply-adds and the LDS traffic per multiply-add falls by a third, but the accumulators of two
+// groups leave room for one wave per SIMD only, and the kernel measured 14 % slower than with
+// RG = 1 (two waves per SIMD): what a step waits for is latency, not LDS bandwidth.  The launchers
+// use RG = 1.
+template <int NCH32, int NG, int R, int RG, class OUT>
+__global__ __launch_bounds__(64 * NG / RG) void rsh_panel_kernel(
     const uint4* __restrict__ items, XcdSplit xs, const int32_t* __restrict__ win_row,
     const uint32_t* __restrict__ win_tile_off, const int32_t* __restrict__ win_col0,
     const int32_t* __restrict__ tile_colid, const uint32_t* __restrict__ unit_off,
     const uint32_t* __restrict__ ent, const __half* __restrict__ B, const OUT out,
     float* __restrict__ scratch, int N, int feature0) {
-    using Gm = PanelGeom<NCH32, NG>;
+    using Gm = PanelGeom<NCH32, NG, RG>;
     constexpr int P = Gm::P, TPR = Gm::TPR, LDB = Gm::LDB, NLD = Gm::NLD, KT = kPanelK, THREADS = Gm::THREADS;
-    constexpr int LB = 2;    // fragments ahead at which B rows are requested
-    constexpr int LA = 3;    // fragments ahead at which a wave's entries are requested (1 .. 5 measure alike)
+    constexpr int LB = 3;    // fragments ahead at which B rows are requested (staged two fragments ahead)
+    constexpr int LA = 4;    // fragments ahead at which a wave's entries are requested (scattered two fragments ahead)
     __shared__ __attribute__((aligned(16))) unsigned char smem[Gm::SMEM_BYTES];
-    _Float16* const lds_b = reinterpret_cast<_Float16*>(smem);                                  // [2][KT * LDB]
-    unsigned char* const lds_a = smem + 2 * Gm::TILE_HALVES * 2;                                // [4 waves][WAVE_A_BYTES]
+    _Float16* const lds_b = reinterpret_cast<_Float16*>(smem);                                  // [NBUF][KT * LDB]
+    unsigned char* const lds_a = smem + Gm::NBUF * Gm::TILE_HALVES * 2;                         // [NG groups][2 sets][SET_A_BYTES]
 
     const int lane = threadIdx.x & 63;
-    const int g = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // row group of this wave
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g0 = wv * RG;                                           // first row group of this wave
     uint32_t item;
     {
         const uint32_t x = blockIdx.x & 7u;
@@ -747,13 +759,17 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
     const int32_t col0 = win_col0[win];
     const uint32_t steps = t_end - t_begin;
     const int panel = feature0 + blockIdx.y * P;
-    const int row = win_row[(size_t)win * (32 * NG) + g * 32 + (lane & 31)];   // lane n (and n + 32) <-> row n of the group
+    int row[RG];   // lane n (and n + 32) <-> row n of the group
+#pragma unroll
+    for (int gi = 0; gi < RG; ++gi) row[gi] = win_row[(size_t)win * (32 * NG) + (g0 + gi) * 32 + (lane & 31)];
 
-    float16_t acc[NCH32], acc2[NCH32];
+    float16_t acc[RG][NCH32], acc2[RG][NCH32];
 #pragma unroll
-    for (int c = 0; c < NCH32; ++c)
+    for (int gi = 0; gi < RG; ++gi)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[c][v] = acc2[c][v] = 0.f;
+        for (int c = 0; c < NCH32; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[gi][c][v] = acc2[gi][c][v] = 0.f;
 
     if (steps > 0) {
         const uint32_t last = steps - 1;
@@ -775,23 +791,25 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
         const char* Bbytes = reinterpret_cast<const char*>(B + panel);
         const uint32_t row_bytes = 2u * (uint32_t)N;
         const bool run = col0 >= 0;                                   // columns are col0, col0 + 1, ...: no ids to fetch
-        // ---- this wave's entry stream and operand tiles ----
-        const uint32_t unit0 = 2u * NG * t0 + ((uint32_t)g * nt + (t_begin - t0)) * 2u;
-        unsigned char* const my_a = lds_a + g * Gm::WAVE_A_BYTES;     // [0, 1024) K step 0, [1024, 2048) K step 1, then 256 spare bytes
+        // ---- this wave's entry streams (one per row group; the units of a group are consecutive) and operand tiles ----
+        const uint32_t unit0 = 2u * NG * t0 + ((uint32_t)g0 * nt + (t_begin - t0)) * 2u;   // group g0 + gi: + 2 * nt * gi
+        unsigned char* const my_a = lds_a + g0 * Gm::GROUP_A_BYTES;   // per group and set: [0, 1024) K step 0, [1024, 2048) K step 1, 256 spare bytes
         const int g4 = lane >> 4, rr4 = (lane & 15) >> 2, ss4 = lane & 3;
         const int tr_off = (8 * (g4 >> 1) + rr4) * LDB + 16 * (g4 & 1) + 4 * ss4;
 
         uint4_t breg[4][NLD];
-        uint4_t areg[4][2][R];
-        uint32_t cnt_ring[4][2];
+        uint4_t areg[4][RG][2][R];
+        uint32_t cnt_ring[4][RG][2];
         int cid_ring[4][NLD];   // column ids of the rows a thread stages, by fragment mod 4 (gathered windows only)
 
-        // Offsets of the units of four fragments at a time: lane i < 9 holds unit_off[first unit + i].
-        // Fetched with a vector load one round of four fragments ahead (a scalar load would have to be
-        // waited for at the next LDS wait: the two share a counter).  Past the item's last fragment
-        // the index stops at the end of its last unit, so later fragments have no entries.
+        // Offsets of the units of four fragments at a time: lane 16 * gi + i, i < 9, holds the offset
+        // of unit (first unit + i) of row group gi.  Fetched with a vector load one round of four
+        // fragments ahead (a scalar load would have to be waited for at the next LDS wait: the two
+        // share a counter).  Past the item's last fragment the index stops at the end of its last
+        // unit, so later fragments have no entries.
         auto request_offsets = [&](uint32_t first_step) -> uint32_t {
-            return unit_off[unit0 + min(2u * first_step + (uint32_t)(lane & 15), 2u * last + 2u)];
+            const uint32_t gi = (uint32_t)(lane >> 4) & (uint32_t)(RG - 1);
+            return unit_off[unit0 + 2u * nt * gi + min(2u * first_step + (uint32_t)(lane & 15), 2u * last + 2u)];
         };
         // Entries are fetched four per lane with 16-byte loads (few, wide requests: the vector memory
         // path takes as long over a 4-byte load as over a 16-byte one).  Lanes past the unit's last
@@ -831,21 +849,25 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
         // Entries into the zeroed operand tiles.  Lanes without a quad of the unit are masked off (the
         // LDS spends its time per active lane); the entries that pad a unit to a whole quad carry
         // addresses in the spare words behind the tiles.
-        auto scatter = [&](const uint4_t (&a)[2][R], const uint32_t (&cnt)[2]) {
-            *reinterpret_cast<uint4_t*>(my_a + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
-            *reinterpret_cast<uint4_t*>(my_a + 1024 + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
+        auto scatter = [&](const uint4_t (&a)[RG][2][R], const uint32_t (&cnt)[RG][2], int set) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int gi = 0; gi < RG; ++gi) {
+                unsigned char* const ta = my_a + gi * Gm::GROUP_A_BYTES + set * Gm::SET_A_BYTES;
+                *reinterpret_cast<uint4_t*>(ta + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
+                *reinterpret_cast<uint4_t*>(ta + 1024 + lane * 16) = (uint4_t){0u, 0u, 0u, 0u};
 #pragma unroll
-                for (int q = 0; q < R; ++q) {
-                    if ((uint32_t)(64 * q + lane) < cnt[h]) {
+                for (int h = 0; h < 2; ++h)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const uint32_t w = a[h][q][i];
-                            *reinterpret_cast<uint16_t*>(my_a + 1024u * h + (w >> 16)) = (uint16_t)w;
+                    for (int q = 0; q < R; ++q) {
+                        if ((uint32_t)(64 * q + lane) < cnt[gi][h]) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const uint32_t w = a[gi][h][q][i];
+                                *reinterpret_cast<uint16_t*>(ta + 1024u * h + (w >> 16)) = (uint16_t)w;
+                            }
                         }
                     }
-                }
+            }
         };
         auto block_barrier = [&]() {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -853,8 +875,38 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
         };
 
-        // ---- prologue: entries of fragments 0 .. LA-1, B rows of fragments 0 .. LB-1 in flight; fragment 0 staged ----
+        // Operands of one K step in registers: the staged B tile through the transposing read (NCH32
+        // operands of 32 features x 16 columns) and each row group's expanded piece of the sparse matrix.
+        struct Operands {
+            half8_t b[NCH32];
+            half8_t a[RG];
+        };
+        auto read_operands = [&](int buf, int set, int h, Operands& x) {
+            const _Float16* sb = lds_b + buf * Gm::TILE_HALVES + tr_off + (16 * h) * LDB;
+#pragma unroll
+            for (int c = 0; c < NCH32; ++c) {
+                const half4_t lo = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (short4_t __attribute__((address_space(3)))*)(sb + 32 * c)));
+                const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (short4_t __attribute__((address_space(3)))*)(sb + 4 * LDB + 32 * c)));
+                x.b[c] = (half8_t){lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            }
+#pragma unroll
+            for (int gi = 0; gi < RG; ++gi)
+                x.a[gi] = *reinterpret_cast<const half8_t*>(my_a + gi * Gm::GROUP_A_BYTES + set * Gm::SET_A_BYTES + 1024 * h + lane * 16);
+        };
+        auto multiply = [&](const Operands& x) {
+#pragma unroll
+            for (int c = 0; c < NCH32; ++c)
+#pragma unroll
+                for (int gi = 0; gi < RG; ++gi)
+                    acc[gi][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x.b[c], x.a[gi], acc[gi][c], 0, 0, 0);
+        };
+
+        // ---- prologue: entries of fragments 0 .. LA-1 and B rows of fragments 0 .. LB-1 requested; fragments 0 and 1
+        //      staged; the operands of fragment 0's first K step in registers ----
         uint32_t ovec;
+        Operands op0, op1;
         {
             const uint32_t ov0 = request_offsets(0u);
             ovec = request_offsets((uint32_t)LA);
@@ -862,93 +914,103 @@ __global__ __launch_bounds__(64 * NG) void rsh_panel_kernel(
             for (int d = 0; d < LB + 1; ++d) fetch_colids((uint32_t)d, cid_ring[d & 3]);
 #pragma unroll
             for (int d = 0; d < LB; ++d) issue_b((uint32_t)d, cid_ring[d], breg[d]);
-            uint32_t o[2 * LA + 1];
 #pragma unroll
-            for (int i = 0; i <= 2 * LA; ++i) o[i] = (uint32_t)__builtin_amdgcn_readlane((int)ov0, i);
+            for (int gi = 0; gi < RG; ++gi) {
+                uint32_t o[2 * LA + 1];
 #pragma unroll
-            for (int d = 0; d < LA; ++d) issue_entries(o[2 * d], o[2 * d + 1], o[2 * d + 2], areg[d], cnt_ring[d]);
+                for (int i = 0; i <= 2 * LA; ++i) o[i] = (uint32_t)__builtin_amdgcn_readlane((int)ov0, 16 * gi + i);
+#pragma unroll
+                for (int d = 0; d < LA; ++d) issue_entries(o[2 * d], o[2 * d + 1], o[2 * d + 2], areg[d][gi], cnt_ring[d][gi]);
+            }
             stage_b(breg[0], 0);
-            scatter(areg[0], cnt_ring[0]);
+            scatter(areg[0], cnt_ring[0], 0);
+            stage_b(breg[1], 1);
+            scatter(areg[1], cnt_ring[1], 1);
             block_barrier();
+            read_operands(0, 0, 0, op0);
         }
 
+        // Step s (fragment s = base + u lives in B tile u and operand set u & 1): the reads of a K step's
+        // operands are issued one K step before its multiply-adds, so that the LDS round trip runs
+        // under the matrix unit's work; what is written in step s (B tile and operand set of fragment
+        // s + 2) is read from step s + 1 on, after the barrier, and overwrites what was last read in
+        // step s - 2 (B tile) or earlier in this wave's own instruction order (operand set).
         for (uint32_t base = 0; base < steps; base += 4) {
-            uint32_t o[9];   // unit offsets of fragments base + LA .. base + LA + 3
+            uint32_t o[RG][9];   // unit offsets of fragments base + LA .. base + LA + 3
 #pragma unroll
-            for (int i = 0; i < 9; ++i) o[i] = (uint32_t)__builtin_amdgcn_readlane((int)ovec, i);
+            for (int gi = 0; gi < RG; ++gi)
+#pragma unroll
+                for (int i = 0; i < 9; ++i) o[gi][i] = (uint32_t)__builtin_amdgcn_readlane((int)ovec, 16 * gi + i);
             ovec = request_offsets(base + 4u + (uint32_t)LA);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const uint32_t s = base + (uint32_t)u;
-                // operands of fragment s (scattered during the previous round)
-                const half8_t a0 = *reinterpret_cast<const half8_t*>(my_a + lane * 16);
-                const half8_t a1 = *reinterpret_cast<const half8_t*>(my_a + 1024 + lane * 16);
+                read_operands(u, u & 1, 1, op1);
                 // requests: the column ids of fragment s + LB + 1, the B rows of fragment s + LB (their
                 // ids were requested a round ago), this wave's entries of fragment s + LA
                 fetch_colids(s + LB + 1, cid_ring[(u + LB + 1) & 3]);
                 issue_b(s + LB, cid_ring[(u + LB) & 3], breg[(u + LB) & 3]);
-                issue_entries(o[2 * u], o[2 * u + 1], o[2 * u + 2], areg[(u + LA) & 3], cnt_ring[(u + LA) & 3]);
-                // multiply fragment s out of LDS
-                const _Float16* sb = lds_b + (u & 1) * Gm::TILE_HALVES + tr_off;
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int c = 0; c < NCH32; ++c) {
-                        const half4_t lo = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4_t __attribute__((address_space(3)))*)(sb + (16 * h) * LDB + 32 * c)));
-                        const half4_t hi = __builtin_bit_cast(half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (short4_t __attribute__((address_space(3)))*)(sb + (16 * h + 4) * LDB + 32 * c)));
-                        const half8_t b_frag = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b_frag, h ? a1 : a0, acc[c], 0, 0, 0);
-                    }
-                // fragment s + 1: B rows into the other buffer, entries into the operand tiles
-                stage_b(breg[(u + 1) & 3], (u + 1) & 1);
-                scatter(areg[(u + 1) & 3], cnt_ring[(u + 1) & 3]);
-                block_barrier();
+                for (int gi = 0; gi < RG; ++gi)
+                    issue_entries(o[gi][2 * u], o[gi][2 * u + 1], o[gi][2 * u + 2], areg[(u + LA) & 3][gi], cnt_ring[(u + LA) & 3][gi]);
+                multiply(op0);
+                if (!(u & 1)) read_operands((u + 1) & 3, (u + 1) & 1, 0, op0);
+                multiply(op1);
+                // fragment s + 2: B rows into the tile fragment s - 2 has left, entries into this fragment's operand set
+                stage_b(breg[(u + 2) & 3], (u + 2) & 3);
+                scatter(areg[(u + 2) & 3], cnt_ring[(u + 2) & 3], u & 1);
+                if (u & 1) {   // one barrier per pair of fragments: tiles written in this pair are read in the next
+                    block_barrier();
+                    read_operands((u + 1) & 3, (u + 1) & 1, 0, op0);
+                }
             }
             if ((base & 31u) == 28u) {   // 32 fragments = 1024 condensed columns: second level
 #pragma unroll
-                for (int c = 0; c < NCH32; ++c) {
-                    acc2[c] += acc[c];
+                for (int gi = 0; gi < RG; ++gi)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
-                }
+                    for (int c = 0; c < NCH32; ++c) {
+                        acc2[gi][c] += acc[gi][c];
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[gi][c][v] = 0.f;
+                    }
             }
         }
     }
 
-    // ---- output: each wave's 32 rows x 32 features take a turn through LDS and leave as whole lines ----
+    // ---- output: each group's 32 rows x 32 features take a turn through LDS and leave as whole lines ----
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    float* const stage = reinterpret_cast<float*>(smem) + g * (32 * Gm::STAGE_STRIDE);
+    float* const stage = reinterpret_cast<float*>(smem) + wv * (32 * Gm::STAGE_STRIDE);
     const int n = lane & 31, hh = lane >> 5;
 #pragma unroll
-    for (int c = 0; c < NCH32; ++c) {
-        const float16_t sum = acc2[c] + acc[c];
-        __builtin_amdgcn_wave_barrier();
+    for (int gi = 0; gi < RG; ++gi)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<float4_t*>(stage + n * Gm::STAGE_STRIDE + 8 * q + 4 * hh) =
-                (float4_t){sum[4 * q], sum[4 * q + 1], sum[4 * q + 2], sum[4 * q + 3]};
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+        for (int c = 0; c < NCH32; ++c) {
+            const float16_t sum = acc2[gi][c] + acc[gi][c];
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int id = i * 64 + lane, pr = id >> 3, fp = id & 7;
-            const float4_t v = *reinterpret_cast<const float4_t*>(stage + pr * Gm::STAGE_STRIDE + 4 * fp);
-            const int f = panel + 32 * c + 4 * fp;
-            const int prow = shfl_i32(row, pr);
-            if (f >= N) continue;
-            if (dst != kNoDst) {
-                *reinterpret_cast<float4_t*>(scratch + ((size_t)dst + g * 32 + pr) * N + f) = v;   // partial sums: ordinary stores
-            } else if (prow >= 0) {
-                panel_store(out, (size_t)prow, N, f, v);
-                keep_streaming_hint();
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4_t*>(stage + n * Gm::STAGE_STRIDE + 8 * q + 4 * hh) =
+                    (float4_t){sum[4 * q], sum[4 * q + 1], sum[4 * q + 2], sum[4 * q + 3]};
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int id = i * 64 + lane, pr = id >> 3, fp = id & 7;
+                const float4_t v = *reinterpret_cast<const float4_t*>(stage + pr * Gm::STAGE_STRIDE + 4 * fp);
+                const int f = panel + 32 * c + 4 * fp;
+                const int prow = shfl_i32(row[gi], pr);
+                if (f >= N) continue;
+                if (dst != kNoDst) {
+                    *reinterpret_cast<float4_t*>(scratch + ((size_t)dst + (g0 + gi) * 32 + pr) * N + f) = v;   // partial sums: ordinary stores
+                } else if (prow >= 0) {
+                    panel_store(out, (size_t)prow, N, f, v);
+                    keep_streaming_hint();
+                }
             }
         }
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1208,7 +1270,7 @@ template <int NCH32, int NG, int R, class OUT>
 static void launch_panel_t(const DevicePlan& d, const void* B, const OUT& out, hipStream_t st, int feature0, int panels) {
     uint32_t longest = 0;
     for (int x = 0; x < 8; ++x) longest = std::max(longest, d.tile_split.start[x + 1] - d.tile_split.start[x]);
-    hipLaunchKernelGGL((rsh_panel_kernel<NCH32, NG, R, OUT>), dim3(8u * longest, (unsigned)panels), dim3(64 * NG), 0, st,
+    hipLaunchKernelGGL((rsh_panel_kernel<NCH32, NG, R, 1, OUT>), dim3(8u * longest, (unsigned)panels), dim3(64 * NG), 0, st,
                        (const uint4*)d.tile_item, d.tile_split, d.win_row, d.win_tile_off, d.panel_col0, d.tile_colid,
                        d.panel_off, d.panel_ent, (const __half*)B, out, d.scratch, d.geo.N, feature0);
 }
