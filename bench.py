@@ -28,7 +28,7 @@ ABLATIONS = {
     # Section 4.3.3: identity -> spanning-tree walk -> + 2-opt -> + relocation of isolated rows
     "reorder": [dict(reorder=0), dict(reorder=2), dict(reorder=3), dict(reorder=1)],
     # window height and fragment width (the paper fixes 16 x 8 for its MMA shape)
-    "shape": [dict(window_rows=w, tile_k=k) for w in (16, 32, 64) for k in (16, 32)],
+    "shape": [dict(window_rows=w, tile_k=k) for w in (16, 32, 64) for k in (16, 32)] + [dict(window_rows=w) for w in (128, 256)],
 }
 
 

@@ -32,6 +32,16 @@ bool hip_ok(hipError_t e) {
     return false;
 }
 
+}  // namespace
+
+namespace rsh {
+void note_hip_error() {
+    g_hip_error = hipGetErrorString(hipGetLastError());
+}
+}  // namespace rsh
+
+namespace {
+
 double ms_since(std::chrono::steady_clock::time_point t0) {
     return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
 }

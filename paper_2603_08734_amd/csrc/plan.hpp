@@ -90,6 +90,9 @@ struct Partition {
 int validate_csr(const rsh_csr_t& a);
 void column_degrees(const rsh_csr_t& a, std::vector<int32_t>& deg, int threads);
 void estimate_threshold(int64_t n_rows, int64_t nnz, int32_t* tau_nnz, int32_t* tau_inc);
+// Keeps the text of the HIP runtime's last error for rsh_last_hip_error (calling thread) and clears it.
+void note_hip_error();
+
 // Neighbour lists of Algorithm 3 step II: n_rows x knn_k row ids (-1 = no further neighbour) and affinities.
 struct KnnLists {
     std::vector<int32_t> nbr;

@@ -133,21 +133,30 @@ struct DeviceScorer {
              (a.nnz == 0 || hipMemcpy(col_idx, a.col_idx, (size_t)a.nnz * 4, hipMemcpyHostToDevice) == hipSuccess) &&
              (wv.empty() || hipMemcpy(w, wv.data(), wv.size() * 8, hipMemcpyHostToDevice) == hipSuccess) &&
              (rwv.empty() || hipMemcpy(row_w, rwv.data(), rwv.size() * 8, hipMemcpyHostToDevice) == hipSuccess);
+        if (!ok) note_hip_error();
         return ok ? RSH_OK : RSH_ERR_HIP;
     }
     // tables of `n` rows in pinned buffer set `s` -> device -> scores back into h_score[s]; asynchronous
     int submit(int s, int64_t n) {
         if (hipMemcpyAsync(rows[s], h_rows[s], (size_t)n * 4, hipMemcpyHostToDevice, stream) != hipSuccess ||
-            hipMemcpyAsync(cand[s], h_cand[s], (size_t)n * 64 * 4, hipMemcpyHostToDevice, stream) != hipSuccess)
+            hipMemcpyAsync(cand[s], h_cand[s], (size_t)n * 64 * 4, hipMemcpyHostToDevice, stream) != hipSuccess) {
+            note_hip_error();
             return RSH_ERR_HIP;
+        }
         const int rc = launch_score_pairs(row_ptr, col_idx, w, row_w, rows[s], cand[s], score[s], n, stream);
         if (rc) return rc;
         if (hipMemcpyAsync(h_score[s], score[s], (size_t)n * 64 * 8, hipMemcpyDeviceToHost, stream) != hipSuccess ||
-            hipEventRecord(done[s], stream) != hipSuccess)
+            hipEventRecord(done[s], stream) != hipSuccess) {
+            note_hip_error();
             return RSH_ERR_HIP;
+        }
         return RSH_OK;
     }
-    int wait(int s) { return hipEventSynchronize(done[s]) == hipSuccess ? RSH_OK : RSH_ERR_HIP; }
+    int wait(int s) {
+        if (hipEventSynchronize(done[s]) == hipSuccess) return RSH_OK;
+        note_hip_error();
+        return RSH_ERR_HIP;
+    }
     ~DeviceScorer() {
         if (stream) (void)hipStreamSynchronize(stream);
         for (int s = 0; s < 2; ++s) {
@@ -293,7 +302,6 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     // column; a matrix whose columns are all too frequent to serve as features) and is skipped.
     // The sample only needs the posting lists of its own feature columns, so the full index is
     // built after the test.
-    bool searched = false;
     if (o.partition == 1 && o.force_path == 0 && o.min_reuse > 1.f && o.reorder == 1 && !knn_only) {
         constexpr int64_t kSamples = 2048;
         std::vector<int64_t> takes;
@@ -307,7 +315,6 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
             for (int i = 0; i < nf; ++i) mark[(size_t)feat[i].second] = 1;
         }
         build_index(&mark);
-        searched = true;
         std::atomic<int64_t> pass{0};
         parallel_chunks(n_s, threads, [&](int64_t b, int64_t e, int) {
             RowScratch ws;
@@ -329,7 +336,6 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
         });
         if (n_s > 0 && pass.load() * 100 < n_s) return RSH_OK;   // order stays the given one, objective not evaluated
     }
-    (void)searched;
     build_index(nullptr);
 
     std::vector<int32_t> nbr((size_t)n * (size_t)K, -1);
