@@ -83,9 +83,11 @@ typedef struct {
                              row in a window (tests compare the three)                          */
     float min_reuse;      /* partition == 1: dissolve windows with nnz/|U| below this           */
     int32_t long_row_nnz; /* partition == 1: rows longer than this go to the irregular path; 0 = auto */
-    int32_t window_schedule; /* 1 (default) = windows are issued in breadth-first clusters of windows that
-                             read each other's rows (square matrices only), when that lowers the distinct
-                             columns per run of consecutive windows by a tenth; 0 = plan order       */
+    int32_t window_schedule; /* 1 (default) = on square matrices the windows are issued in an order built over
+                             "window u names a row that window v holds": breadth-first clusters, or a
+                             breadth-first numbering inside each eighth of the plan order (the run one XCD
+                             gets), whichever lowers the distinct columns per run of 1024 consecutive
+                             windows more, if by at least a tenth; 0 = plan order                      */
     int32_t hub_windows;  /* partition == 1: 1 = long rows are grouped among themselves, longest first, and a
                              group whose reuse reaches min_reuse becomes a window; 0 = all long rows go
                              to the irregular path                                                 */
@@ -130,8 +132,9 @@ typedef struct {
     int64_t rows_tile, rows_irregular;         /* rows of C each kernel writes directly or via scratch */
     int32_t tau_nnz, tau_inc;                  /* thresholds actually used                       */
     int32_t window_rows, tile_k;               /* W and K actually used                          */
-    int64_t schedule_cols_given, schedule_cols_found; /* distinct columns per run of 256 consecutive windows,
-                                                  summed, in plan order and in clustered order (0 = not tried) */
+    int64_t schedule_cols_given, schedule_cols_found; /* distinct columns per run of 1024 consecutive windows,
+                                                  summed, in plan order and in the best issue order found
+                                                  (0 = not tried)                                     */
     int64_t singleton_entries, singleton_rows; /* entries of windows in columns that one row of the window names;
                                                   window rows holding at least one such entry         */
     int64_t bytes_method;                      /* bytes one product moves under the routing as built: plan +

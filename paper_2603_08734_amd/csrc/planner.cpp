@@ -355,15 +355,24 @@ static void count_singletons(const std::vector<WinEntry>& ent, int64_t* entries,
 }
 
 // Order in which windows are issued.  Windows that run at the same time on one XCD should
-// gather overlapping B rows, so that a row fetched for one is an L2 hit for the others.  For a
-// square matrix the window holding row j is a natural neighbour of every window that reads
-// column j (a mesh or graph neighbourhood); windows are therefore collected in breadth-first
-// clusters of kClusterWindows over that relation, clusters seeded in the given order.  The
-// result is kept only if it lowers the distinct columns per run of kClusterWindows consecutive
-// windows by at least a tenth (the quantity L2 has to hold); otherwise the given order stays.
+// gather overlapping B rows, so that a row fetched for one is an L2 hit for the others, and a row
+// that several windows name should be named again before the L2 has turned over.  For a square
+// matrix the window holding row j is a natural neighbour of every window that reads column j (a
+// mesh or graph neighbourhood).  Two orders are built over that relation:
+//   * breadth-first clusters of kClusterWindows windows, clusters seeded in the given order;
+//   * a breadth-first (Cuthill-McKee style) numbering inside each eighth of the given order -- the
+//     run of windows one XCD will be handed: the level sets of a slab of a mesh are much smaller
+//     than its planes, so the rows a window shares with earlier windows were named a short while
+//     ago (a 27-point stencil on 96^3 in natural order re-reads a plane of B after two planes of
+//     other rows have passed through the L2; numbered by levels inside a 12-plane slab, after a
+//     few thousand rows).
+// Each is scored by the distinct columns per run of kInFlightWindows consecutive windows (about
+// what the waves resident on one XCD work on at a time, i.e. what its L2 has to hold); the best
+// order is kept if it lowers that by at least a tenth, otherwise the given order stays.
 static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan& plan, int64_t n_win,
                                              int64_t* cols_given, int64_t* cols_found) {
     constexpr int64_t kClusterWindows = 256;
+    constexpr int64_t kInFlightWindows = 1024;
     std::vector<int64_t> order((size_t)n_win);
     std::iota(order.begin(), order.end(), (int64_t)0);
     *cols_given = *cols_found = 0;
@@ -378,7 +387,7 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
         std::vector<int64_t> stamp((size_t)a.n_cols, -1);
         int64_t total = 0;
         for (int64_t i = 0; i < n_win; ++i) {
-            const int64_t chunk = i / kClusterWindows, w = ord[(size_t)i];
+            const int64_t chunk = i / kInFlightWindows, w = ord[(size_t)i];
             for (size_t q = (size_t)plan.win_tile_off[w] * K; q < (size_t)plan.win_tile_off[w + 1] * K; ++q) {
                 const int32_t c = plan.tile_colid[q];
                 if (stamp[(size_t)c] != chunk) {
@@ -389,36 +398,48 @@ static std::vector<int64_t> schedule_windows(const rsh_csr_t& a, const HostPlan&
         }
         return total;
     };
-    std::vector<int64_t> found;
-    found.reserve((size_t)n_win);
-    std::vector<uint8_t> state((size_t)n_win, 0);   // 0 free, 1 queued, 2 placed
+    // breadth-first numbering of the windows lo .. hi-1 (a run of the given order), seeded at the
+    // lowest free window, at most `limit` windows per tree; windows still queued when a tree is
+    // full are free again
+    std::vector<uint8_t> state((size_t)n_win);   // 0 free, 1 queued, 2 placed
     std::vector<int64_t> queue;
-    for (int64_t seed = 0; seed < n_win; ++seed) {
-        if (state[(size_t)seed] == 2) continue;
-        queue.clear();
-        queue.push_back(seed);
-        state[(size_t)seed] = 1;
-        int64_t placed = 0;
-        for (size_t head = 0; head < queue.size() && placed < kClusterWindows; ++head) {
-            const int64_t w = queue[head];
-            state[(size_t)w] = 2;
-            found.push_back(w);
-            ++placed;
-            for (size_t q = (size_t)plan.win_tile_off[w] * K; q < (size_t)plan.win_tile_off[w + 1] * K; ++q) {
-                const int32_t w2 = row_win[(size_t)plan.tile_colid[q]];
-                if (w2 >= 0 && state[(size_t)w2] == 0) {
-                    state[(size_t)w2] = 1;
-                    queue.push_back(w2);
+    auto breadth_first = [&](int64_t lo, int64_t hi, int64_t limit, std::vector<int64_t>& out) {
+        for (int64_t seed = lo; seed < hi; ++seed) {
+            if (state[(size_t)seed] == 2) continue;
+            queue.clear();
+            queue.push_back(seed);
+            state[(size_t)seed] = 1;
+            int64_t placed = 0;
+            for (size_t head = 0; head < queue.size() && placed < limit; ++head) {
+                const int64_t w = queue[head];
+                state[(size_t)w] = 2;
+                out.push_back(w);
+                ++placed;
+                for (size_t q = (size_t)plan.win_tile_off[w] * K; q < (size_t)plan.win_tile_off[w + 1] * K; ++q) {
+                    const int32_t w2 = row_win[(size_t)plan.tile_colid[q]];
+                    if (w2 >= lo && w2 < hi && state[(size_t)w2] == 0) {
+                        state[(size_t)w2] = 1;
+                        queue.push_back(w2);
+                    }
                 }
             }
+            for (int64_t w : queue)
+                if (state[(size_t)w] == 1) state[(size_t)w] = 0;
         }
-        for (int64_t w : queue)
-            if (state[(size_t)w] == 1) state[(size_t)w] = 0;   // still queued: free for later clusters
-    }
+    };
+    std::vector<int64_t> clustered, levelled;
+    clustered.reserve((size_t)n_win);
+    levelled.reserve((size_t)n_win);
+    std::fill(state.begin(), state.end(), (uint8_t)0);
+    breadth_first(0, n_win, kClusterWindows, clustered);
+    std::fill(state.begin(), state.end(), (uint8_t)0);
+    for (int x = 0; x < 8; ++x) breadth_first(n_win * x / 8, n_win * (x + 1) / 8, n_win, levelled);
     *cols_given = footprint(order);
-    *cols_found = footprint(found);
-    if ((int64_t)found.size() == n_win && *cols_found * 10 <= *cols_given * 9) return found;
-    return order;
+    const int64_t f_clustered = (int64_t)clustered.size() == n_win ? footprint(clustered) : *cols_given;
+    const int64_t f_levelled = (int64_t)levelled.size() == n_win ? footprint(levelled) : *cols_given;
+    *cols_found = std::min(f_clustered, f_levelled);
+    if (*cols_found * 10 > *cols_given * 9) return order;
+    return f_levelled <= f_clustered ? levelled : clustered;
 }
 
 // ---------------------------------------------------------------------------
