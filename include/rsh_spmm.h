@@ -112,6 +112,12 @@ typedef struct {
                              2 (default) = the device when upload != 0 and the matrix has at least 131072
                              rows, else the host.  Both take the same binary64 operations in the same order:
                              neighbour lists, row order and plan do not depend on this option           */
+    int32_t element_level; /* 1 = element-level routing on top of the row-level partition: in every window the
+                             entries of columns that only one of its rows names go to the residual kernel
+                             (a slice per window row, at most max_nnz_per_slice entries of a row), the window's
+                             sums and those slices meet in the combine pass; 0 (default) = row-level routing
+                             only, as in the paper (Section 3.1).  rsh_plan_stats' bytes_method_element_level
+                             says what the option would move; windows of 128 or 256 rows ignore it      */
 } rsh_plan_opts_t;
 
 /* What the planner built (host side, for tests, logs and the benchmark). */
@@ -136,7 +142,8 @@ typedef struct {
                                                   summed, in plan order and in the best issue order found
                                                   (0 = not tried)                                     */
     int64_t singleton_entries, singleton_rows; /* entries of windows in columns that one row of the window names;
-                                                  window rows holding at least one such entry         */
+                                                  window rows holding at least one such entry (counted
+                                                  before element_level moves them)                    */
     int64_t bytes_method;                      /* bytes one product moves under the routing as built: plan +
                                                   2N per distinct column of each window and per residual entry
                                                   + 4N per row of C + 8N per partial row                 */

@@ -51,7 +51,7 @@ class rsh_plan_opts_t(ctypes.Structure):
                 ("min_reuse", ctypes.c_float), ("long_row_nnz", ctypes.c_int32),
                 ("window_schedule", ctypes.c_int32), ("hub_windows", ctypes.c_int32), ("xcd_partition_nnz", ctypes.c_int32), ("run_width", ctypes.c_int32), ("transpose", ctypes.c_int32), ("upload", ctypes.c_int32),
                 ("threads", ctypes.c_int32), ("side_stream", ctypes.c_int32),
-                ("device_scoring", ctypes.c_int32)]
+                ("device_scoring", ctypes.c_int32), ("element_level", ctypes.c_int32)]
 
 
 class rsh_kernel_times_t(ctypes.Structure):

@@ -207,6 +207,7 @@ int rsh_plan_opts_default(rsh_plan_opts_t* o) {
     o->threads = 0;
     o->side_stream = 0;
     o->device_scoring = 2;
+    o->element_level = 0;
     return RSH_OK;
 }
 
@@ -229,7 +230,7 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
     if (o.reorder < 0 || o.reorder > 3 || o.knn_k < 1 || o.knn_k > 64 || !(o.alpha > 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.max_tiles_per_item < 0 || o.max_nnz_per_slice < 0 || o.long_row_nnz < 0 || !(o.min_reuse >= 0.f)) return RSH_ERR_BAD_OPTION;
     if (o.threads < 0 || o.transpose < 0 || o.transpose > 1 || o.side_stream < 0 || o.side_stream > 1) return RSH_ERR_BAD_OPTION;
-    if (o.device_scoring < 0 || o.device_scoring > 2) return RSH_ERR_BAD_OPTION;
+    if (o.device_scoring < 0 || o.device_scoring > 2 || o.element_level < 0 || o.element_level > 1) return RSH_ERR_BAD_OPTION;
 
     const auto t_all = std::chrono::steady_clock::now();
     auto t0 = t_all;

@@ -354,6 +354,25 @@ static void count_singletons(const std::vector<WinEntry>& ent, int64_t* entries,
     *rows = popc64(row_seen[0]) + popc64(row_seen[1]) + popc64(row_seen[2]) + popc64(row_seen[3]);
 }
 
+// Element-level routing: the entries of columns that only one row of the window names leave the
+// window (they would cost a fragment column and a staged row of B for one multiply-add each) and
+// are appended to `spilled`, still sorted by (column, window row); the rest stays in `ent`.  At
+// most `cap` entries leave per row (one bounded slice of the residual kernel takes them).
+static void spill_singletons(std::vector<WinEntry>& ent, std::vector<WinEntry>& spilled, uint32_t cap) {
+    uint32_t left[256];
+    for (uint32_t& x : left) x = cap;
+    size_t keep = 0;
+    for (size_t i = 0; i < ent.size(); ++i) {
+        const bool first = i == 0 || (ent[i - 1].key >> 8) != (ent[i].key >> 8);
+        const bool last = i + 1 == ent.size() || (ent[i + 1].key >> 8) != (ent[i].key >> 8);
+        if (first && last && left[ent[i].key & 255] > 0) {
+            --left[ent[i].key & 255];
+            spilled.push_back(ent[i]);
+        } else ent[keep++] = ent[i];   // keep <= i, so ent[i - 1] and ent[i + 1] still hold what they held
+    }
+    ent.resize(keep);
+}
+
 // Order in which windows are issued.  Windows that run at the same time on one XCD should
 // gather overlapping B rows, so that a row fetched for one is an L2 hit for the others, and a row
 // that several windows name should be named again before the L2 has turned over.  For a square
@@ -587,6 +606,10 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     plan.win_row = part.win_row;
 
     int64_t sum_cols = 0, n_tiles = 0, nnz_tile = 0;
+    // element-level routing (bitmap form only): per window the entries that leave for the residual path
+    const bool element_level = plan.opts.element_level != 0 && !geo.panel;
+    std::vector<std::vector<WinEntry>> win_spill(element_level ? (size_t)n_win : 0);
+    const uint32_t spill_cap = (uint32_t)(plan.opts.max_nnz_per_slice > 0 ? plan.opts.max_nnz_per_slice : 512);
     plan.win_single_entries.assign((size_t)n_win, 0);
     plan.win_single_rows.assign((size_t)n_win, 0);
     if (geo.panel) {
@@ -602,8 +625,14 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
             std::vector<WinEntry> ent;
             std::vector<uint32_t> cnt;   // entries per (fragment, sub-fragment)
+            std::vector<WinEntry> spilled;
             for (int64_t w = b; w < e; ++w) {
                 gather_window(a, &part.win_row[w * W], W, ent);
+                count_singletons(ent, &plan.win_single_entries[(size_t)w], &plan.win_single_rows[(size_t)w]);
+                if (element_level) {
+                    spilled.clear();
+                    spill_singletons(ent, spilled, spill_cap);
+                }
                 int64_t u = 0;
                 cnt.clear();
                 uint64_t prev_col = ~0ull;
@@ -621,7 +650,6 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
                 win_tiles[w] = (uint32_t)(cnt.size() / (size_t)NW);
                 win_vals[w] = v;
                 win_cols[w] = u;
-                count_singletons(ent, &plan.win_single_entries[(size_t)w], &plan.win_single_rows[(size_t)w]);
             }
         });
         plan.win_tile_off.assign((size_t)n_win + 1, 0);
@@ -647,6 +675,13 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
             std::vector<uint32_t> ucol;   // condensed column index of each entry
             for (int64_t w = b; w < e; ++w) {
                 gather_window(a, &part.win_row[w * W], W, ent);
+                if (element_level) {
+                    // by (window row, column): the residual stream holds a row's entries in ascending column order
+                    spill_singletons(ent, win_spill[(size_t)w], spill_cap);
+                    std::sort(win_spill[(size_t)w].begin(), win_spill[(size_t)w].end(), [](const WinEntry& x, const WinEntry& y) {
+                        return (x.key & 255) != (y.key & 255) ? (x.key & 255) < (y.key & 255) : x.key < y.key;
+                    });
+                }
                 win_nnz[w] = (int64_t)ent.size();
                 const uint32_t t0 = plan.win_tile_off[w];
                 const uint32_t nt = plan.win_tile_off[w + 1] - t0;
@@ -718,6 +753,7 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     plan.tile_item.clear();
     plan.combine.clear();
     int64_t slots = 0, n_split_windows = 0;
+    std::vector<int64_t> spill_slot(element_level ? (size_t)n_win : 0, -1);   // first slot of a window's spilled rows
     const std::vector<int64_t> worder = schedule_windows(a, plan, n_win, &plan.stats.schedule_cols_given, &plan.stats.schedule_cols_found);
     for (int64_t wi = 0; wi < n_win; ++wi) {
         const int64_t w = worder[(size_t)wi];
@@ -726,7 +762,28 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         // fragments), the bitmap form into the fewest parts of at most t_max fragments
         const uint32_t parts = geo.panel && plan.opts.max_tiles_per_item <= 0
                                    ? (uint32_t)std::max<int64_t>(1, (2 * (int64_t)nt + t_max) / (2 * t_max))
-                                   : (uint32_t)((nt + t_max - 1) / t_max);
+                                   : (uint32_t)std::max<int64_t>(1, (nt + t_max - 1) / t_max);
+        if (element_level && !win_spill[(size_t)w].empty()) {
+            // Rows of this window receive a second contribution from the residual path: the window's
+            // parts go to scratch, one more slot per row takes the row's spilled entries, and the
+            // combine pass adds them up (a row without spilled entries has only the window's parts).
+            uint32_t has_spill[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (const WinEntry& x : win_spill[(size_t)w]) has_spill[(x.key & 255) >> 5] |= 1u << (x.key & 31);
+            for (uint32_t p = 0; p < parts; ++p) {
+                const uint32_t b = t0 + (uint32_t)((uint64_t)nt * p / parts);
+                const uint32_t e = t0 + (uint32_t)((uint64_t)nt * (p + 1) / parts);
+                plan.tile_item.insert(plan.tile_item.end(), {(uint32_t)w, b, e, (uint32_t)(slots + (int64_t)p * W)});
+            }
+            for (int r = 0; r < W; ++r) {
+                const int32_t row = part.win_row[w * W + r];
+                const uint32_t extra = (has_spill[r >> 5] >> (r & 31)) & 1u;
+                if (row >= 0) plan.combine.insert(plan.combine.end(), {(uint32_t)row, (uint32_t)(slots + r), parts + extra, (uint32_t)W});
+            }
+            spill_slot[(size_t)w] = slots + (int64_t)parts * W;
+            slots += (int64_t)(parts + 1) * W;
+            ++n_split_windows;
+            continue;
+        }
         if (parts <= 1) {
             // a window without fragments (only absent/empty rows) still zero-fills its rows
             plan.tile_item.insert(plan.tile_item.end(), {(uint32_t)w, t0, t0 + nt, kNoDst});
@@ -768,7 +825,9 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
         if (len <= TPR) by_len[(size_t)len].push_back(r);
         else long_rows.push_back(r);
     }
-    if (nnz_irr >= (1ll << 31)) return RSH_ERR_TOO_LARGE;
+    int64_t n_spilled = 0;
+    for (const auto& v : win_spill) n_spilled += (int64_t)v.size();
+    if (nnz_irr + n_spilled >= (1ll << 31)) return RSH_ERR_TOO_LARGE;
     // Residual rows run in ascending row id whatever the reordering found: they share no
     // window, and consecutive rows of C (and consecutive combine entries) written by
     // neighbouring waves measured faster than the reordered sequence.
@@ -824,8 +883,8 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     std::vector<uint32_t> group_off;   // 9 offsets per long row (only filled for partitioned rows)
     if (any_partitioned) group_off.assign((size_t)n_long * 9, 0);
 
-    plan.irr_col.assign((size_t)nnz_irr + 64, 0);   // tail pad keeps lane-wise reads in bounds
-    plan.irr_val.assign((size_t)nnz_irr + 64, 0);
+    plan.irr_col.assign((size_t)(nnz_irr + n_spilled) + 64, 0);   // tail pad keeps lane-wise reads in bounds
+    plan.irr_val.assign((size_t)(nnz_irr + n_spilled) + 64, 0);
     parallel_chunks(n_irr, threads, [&](int64_t b, int64_t e, int) {
         for (int64_t i = b; i < e; ++i) {
             const int32_t r = stream_rows[(size_t)i];
@@ -892,6 +951,29 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
             ++n_slice_waves;
         }
         if (n_slices > 1) slots += n_slices;
+    }
+    // (1b) entries that left their window (element-level routing): per window row one slice that
+    //      writes a partial row for the combine pass
+    if (element_level) {
+        int64_t at = nnz_irr;
+        for (int64_t w = 0; w < n_win; ++w) {
+            const std::vector<WinEntry>& sp = win_spill[(size_t)w];
+            for (size_t i = 0; i < sp.size();) {
+                size_t j = i;
+                while (j < sp.size() && (sp[j].key & 255) == (sp[i].key & 255)) ++j;
+                for (size_t q = i; q < j; ++q) {
+                    plan.irr_col[(size_t)at + (q - i)] = (int32_t)(sp[q].key >> 8);
+                    plan.irr_val[(size_t)at + (q - i)] = sp[q].val;
+                }
+                // a row's spilled entries are few (at most its own length): one slice
+                free_waves.insert(free_waves.end(), {(uint32_t)at, (uint32_t)(j - i), (uint32_t)(spill_slot[(size_t)w] + (int64_t)(sp[i].key & 255)),
+                                                     kWaveSlice | kWaveToScratch});
+                ++n_slice_waves;
+                at += (int64_t)(j - i);
+                i = j;
+            }
+        }
+        nnz_irr += n_spilled;
     }
     // (2) short rows: a wave takes G * R rows of L entries each, R = TPR / L rows per team
     {

@@ -66,6 +66,9 @@ OPTION_SETS = {
     "alg1_literal": dict(partition=0),
     "tiny_items": dict(force_path=2, max_tiles_per_item=2),
     "tiny_slices": dict(force_path=1, max_nnz_per_slice=24),
+    "element_level": dict(element_level=1),
+    "element_level_all_tile": dict(element_level=1, force_path=2, max_tiles_per_item=2),
+    "element_level_w64": dict(element_level=1, force_path=2, window_rows=64),
 }
 
 
@@ -197,6 +200,8 @@ FULL_SIZE_CASES = [
     (4, 208, dict(window_rows=128)),                                                  # panel form: a full feature panel and a masked one
     (2, 160, dict(reorder=0)),                                                        # a full and a partial panel in the irregular kernel
     (3, 112, {}),                                                                     # tile panels of 64, 32 and 16 columns
+    (4, 0, dict(element_level=1)),                                                    # single-row columns of every window on the residual path
+    (3, 0, dict(element_level=1)),
 ]
 
 

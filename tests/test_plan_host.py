@@ -24,6 +24,9 @@ MODES = {
     "alg1_literal": dict(partition=0),
     "tiny_items": dict(force_path=2, max_tiles_per_item=2),
     "tiny_slices": dict(force_path=1, max_nnz_per_slice=24),
+    "element_level": dict(element_level=1),
+    "element_level_all_tile": dict(element_level=1, force_path=2, max_tiles_per_item=2),
+    "element_level_w64": dict(element_level=1, force_path=2, window_rows=64),
 }
 
 
@@ -152,7 +155,10 @@ def test_plan_structure_invariants(k, mode):
     for w, lst in by_win.items():
         assert lst[0][0] == off[w] and lst[-1][1] == off[w + 1]
         assert all(lst[i][1] == lst[i + 1][0] for i in range(len(lst) - 1))
-        assert (len(lst) == 1) == (lst[0][2] == 0xFFFFFFFF)
+        if MODES[mode].get("element_level"):   # a one-part window whose rows also get spilled entries goes to scratch too
+            assert len(lst) == 1 or lst[0][2] != 0xFFFFFFFF
+        else:
+            assert (len(lst) == 1) == (lst[0][2] == 0xFFFFFFFF)
     # irregular waves tile the irregular stream exactly once
     G = p.teams_per_wave()
     T = 64 // G
@@ -187,9 +193,14 @@ def test_plan_structure_invariants(k, mode):
     for w, lst in by_win.items():
         if len(lst) > 1:
             absent_slots += int((win_row[w] < 0).sum()) * len(lst)
-    assert len(produced) == len(set(produced)) == st["n_scratch_slots"]
     assert len(consumed) == len(set(consumed)) and set(consumed) <= set(produced)
-    assert len(produced) - len(consumed) == absent_slots
+    if MODES[mode].get("element_level"):
+        # a window with spilled entries holds one more slot per row; only rows that have spilled entries fill theirs
+        assert len(produced) == len(set(produced)) <= st["n_scratch_slots"]
+        assert max(produced, default=-1) < st["n_scratch_slots"]
+    else:
+        assert len(produced) == len(set(produced)) == st["n_scratch_slots"]
+        assert len(produced) - len(consumed) == absent_slots
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
@@ -537,3 +548,44 @@ def test_single_row_columns_are_counted(opts):
     assert st["bytes_method"] == want
     per_entry = 8 if opts["window_rows"] >= 128 else 4 + opts["window_rows"] // 8 + 2
     assert st["bytes_method_element_level"] == want - (per_entry - 6) * 20 + 8 * N * 20
+
+
+@pytest.mark.parametrize("k", [1, 3, 4])
+@pytest.mark.parametrize("kw", [dict(force_path=2), dict(force_path=2, window_rows=32), dict()])
+def test_element_level_routing_moves_exactly_the_single_row_columns(k, kw):
+    """element_level = 1: in every window the entries of columns that one row of the window names are
+    the ones the decode reports on the residual path (next to the rows that are residual anyway), the
+    window keeps no column with a single entry, and the statistic of the plan made without the option
+    counted exactly these entries."""
+    A, N, _ = make_config(k, small=True)
+    p0 = host_plan(A, N, **kw)
+    p1 = host_plan(A, N, element_level=1, **kw)
+    _, _, _, path0 = p0.decode()
+    rp, ci, val, path1 = p1.decode()
+    assert np.array_equal(rp, A.row_ptr) and np.array_equal(ci, A.col_idx)
+    assert np.array_equal(val.view(np.uint16), A.val.view(np.uint16))
+    s0, s1 = p0.stats(), p1.stats()
+    assert int(path1.sum()) - int(path0.sum()) == s0["singleton_entries"] > 0
+    assert s1["nnz_tile"] == s0["nnz_tile"] - s0["singleton_entries"]
+    assert s1["nnz_irregular"] == s0["nnz_irregular"] + s0["singleton_entries"]
+    # window by window: the spilled entries are those whose column occurs once among the window's rows
+    W = s0["window_rows"]
+    win_row = p0.array(B_.RSH_ARR_WIN_ROW).reshape(-1, W)
+    assert np.array_equal(win_row, p1.array(B_.RSH_ARR_WIN_ROW).reshape(-1, W))   # same windows
+    rows_of = np.repeat(np.arange(A.n_rows), np.diff(A.row_ptr))
+    for w in range(0, win_row.shape[0], max(1, win_row.shape[0] // 40)):
+        rows = win_row[w][win_row[w] >= 0]
+        sel = np.isin(rows_of, rows)
+        cols, counts = np.unique(A.col_idx[sel], return_counts=True)
+        single = np.isin(A.col_idx[sel], cols[counts == 1])
+        assert np.array_equal(path1[sel] == 1, single)
+    assert s1["singleton_entries"] == s0["singleton_entries"]   # the statistic describes the windows before routing
+
+
+def test_element_level_is_refused_out_of_range_and_ignored_by_tall_windows():
+    A, N, _ = make_config(5, small=True)
+    with pytest.raises(RshError):
+        host_plan(A, N, element_level=2)
+    p = host_plan(A, N, element_level=1, window_rows=128, force_path=2)
+    _, _, _, path = p.decode()
+    assert int(path.sum()) == 0
