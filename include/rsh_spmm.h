@@ -110,7 +110,7 @@ typedef struct {
                              0 = host threads, 1 = a kernel on the current HIP device (the host still finds the
                              candidates and picks the best knn_k; an error if the device cannot be used),
                              2 (default) = the device when upload != 0 and the matrix has at least 131072
-                             rows, else the host.  Both take the same binary64 operations in the same order:
+                             rows (the host if the device cannot take it), else the host.  Both take the same binary64 operations in the same order:
                              neighbour lists, row order and plan do not depend on this option           */
     int32_t element_level; /* 1 = element-level routing on top of the row-level partition: in every window the
                              entries of columns that only one of its rows names go to the residual kernel

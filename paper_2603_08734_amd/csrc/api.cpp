@@ -286,9 +286,16 @@ int rsh_plan_create(const rsh_csr_t* csr, int32_t N, const rsh_plan_opts_t* opts
         h.stats.ms_validate = ms_since(t0);
 
         t0 = std::chrono::steady_clock::now();
-        if (o.device_scoring == 2) o.device_scoring = (o.upload && csr->n_rows >= kDeviceScoringRows) ? 1 : 0;
+        const bool scoring_chosen_here = o.device_scoring == 2;
+        if (scoring_chosen_here) o.device_scoring = (o.upload && csr->n_rows >= kDeviceScoringRows) ? 1 : 0;
         if (o.reorder) {
             rc = rsh::reorder_rows(*csr, o, col_deg, h.order, threads, &h.stats.reorder_cost_given, &h.stats.reorder_cost_found);
+            if (rc == RSH_ERR_HIP && scoring_chosen_here && o.device_scoring == 1) {
+                // the device could not take the scoring (no room for the pattern, say): the host scorer
+                // gives the same lists; an explicit device_scoring = 1 reports the error instead
+                o.device_scoring = 0;
+                rc = rsh::reorder_rows(*csr, o, col_deg, h.order, threads, &h.stats.reorder_cost_given, &h.stats.reorder_cost_found);
+            }
             if (rc) throw rc;
         } else {
             h.order.resize((size_t)csr->n_rows);
