@@ -80,6 +80,22 @@ class rsh_plan_stats_t(ctypes.Structure):
 _lib = None
 
 
+def _preload_hip_runtime() -> None:
+    """One HIP runtime per process.  PyTorch ships a HIP runtime of its own; the device pointers and
+    streams it hands out are only good for kernels launched through that same runtime.  librsh.so
+    asks for the runtime by its soname, which the loader satisfies with whatever copy is already
+    mapped -- PyTorch's if PyTorch was imported first, the system's if not, in which case a later
+    ``import torch`` would bring a second runtime into the process.  So when PyTorch is installed its
+    copy is mapped before the library, whatever the import order."""
+    import importlib.util
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.submodule_search_locations:
+        return
+    cand = os.path.join(list(spec.submodule_search_locations)[0], "lib", "libamdhip64.so")
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
+
+
 def lib() -> ctypes.CDLL:
     """Load ``librsh.so``; it is built first when it is missing or older than one of its sources
     (and a compiler is there: a box without one runs the library it was given)."""
@@ -87,6 +103,7 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(_build.LIB) or (_build.needs_build() and os.path.exists(_build.HIPCC)):
             _build.build(force=True)
+        _preload_hip_runtime()
         L = ctypes.CDLL(_build.LIB)
         vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
         L.rsh_plan_opts_default.argtypes = [ctypes.POINTER(rsh_plan_opts_t)]
