@@ -23,6 +23,8 @@
 //   * the found order replaces the given one only if it lowers the objective by >= 3 %;
 //   * before the search, a sample of rows is tested for whether the best window around a row could
 //     pass the partition's reuse test at all; if hardly any does, the given order is kept as it is.
+//     The same sample bounds what the search could gain: if not even every row standing next to its
+//     best candidate would lower the objective by 3 %, the given order is kept without searching.
 //
 // Step II's affinities can be taken on the GPU (rsh_plan_opts_t::device_scoring): the host still
 // finds each row's candidates through the inverted index and picks the best k afterwards, the
@@ -294,6 +296,28 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
         return keep;
     };
 
+    // The objective of Section 3.4: sum of (1 - sim) over consecutive rows.  The heuristic is
+    // meant to lower it; the found order is used only when it lowers the objective by at least
+    // 3 % -- a smaller change means the given order was already as coherent (e.g. the natural
+    // order of a stencil), and permuting it would only disturb the locality it has.
+    // Summed over pieces of a fixed size, so that the value (and with it the 3 % decision and the
+    // plan) does not depend on the number of threads.
+    auto path_cost = [&](const std::vector<int32_t>* ord) {
+        constexpr int64_t kPiece = 4096;
+        const int64_t n_pieces = (n - 1 + kPiece - 1) / kPiece;
+        std::vector<double> part((size_t)n_pieces, 0.0);
+        parallel_dynamic(n_pieces, threads, 16, [&](int64_t b, int64_t e, int) {
+            for (int64_t q = b; q < e; ++q) {
+                double s = 0.0;
+                for (int64_t i = q * kPiece; i < std::min(n - 1, (q + 1) * kPiece); ++i)
+                    s += 1.0 - (ord ? sim((*ord)[(size_t)i], (*ord)[(size_t)i + 1]) : sim((int32_t)i, (int32_t)i + 1));
+                part[(size_t)q] = s;
+            }
+        });
+        double s = 0.0;
+        for (double x : part) s += x;
+        return s;
+    };
     // Is there anything to find?  Under the cost-guided partition a window only survives when its
     // rows reuse columns (stored entries / distinct columns >= min_reuse).  For a sample of rows the
     // best window the search could build around the row -- the row and its most similar candidates
@@ -302,8 +326,17 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     // column; a matrix whose columns are all too frequent to serve as features) and is skipped.
     // The sample only needs the posting lists of its own feature columns, so the full index is
     // built after the test.
-    if (o.partition == 1 && o.force_path == 0 && o.min_reuse > 1.f && o.reorder == 1 && !knn_only) {
+    //
+    // The same sample answers a second question: could the search beat the given order by the 3 %
+    // the acceptance rule asks for?  Whatever order it builds, a row's affinity to its successor is
+    // at most its affinity to its best candidate, so the found objective is at least n minus the sum
+    // of those; with the sample's mean best affinity and its mean affinity to the given successor
+    // standing in for the sums, the search is skipped when mean_best < 0.03 + 0.97 * mean_given (a
+    // mesh in its natural order: a row's successor already is as similar as anything the index
+    // finds).  The objective of the given order is still evaluated and reported.
+    if (o.reorder == 1 && !knn_only) {
         constexpr int64_t kSamples = 2048;
+        const bool reuse_test = o.partition == 1 && o.force_path == 0 && o.min_reuse > 1.f;
         std::vector<int64_t> takes;
         for (int64_t r = 0; r < n; ++r)
             if (takes_part(r) && a.row_ptr[r + 1] > a.row_ptr[r]) takes.push_back(r);
@@ -316,12 +349,16 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
         }
         build_index(&mark);
         std::atomic<int64_t> pass{0};
+        std::vector<double> best_of((size_t)n_s, 0.0), given_of((size_t)n_s, 0.0);
         parallel_chunks(n_s, threads, [&](int64_t b, int64_t e, int) {
             RowScratch ws;
             std::vector<int32_t> cols;
             for (int64_t q = b; q < e; ++q) {
                 const int64_t r = takes[(size_t)(q * (int64_t)takes.size() / n_s)];
                 const size_t got = score_row(r, (size_t)o.window_rows - 1, ws);
+                best_of[(size_t)q] = got ? -ws.scored[0].first : 0.0;
+                given_of[(size_t)q] = r + 1 < n ? sim((int32_t)r, (int32_t)r + 1) : 0.0;
+                if (!reuse_test) continue;
                 int64_t entries = a.row_ptr[r + 1] - a.row_ptr[r];
                 cols.assign(a.col_idx + a.row_ptr[r], a.col_idx + a.row_ptr[r + 1]);
                 for (size_t i = 0; i < got; ++i) {
@@ -334,7 +371,13 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
                 if ((double)entries >= (double)o.min_reuse * (double)distinct) ++pass;
             }
         });
-        if (n_s > 0 && pass.load() * 100 < n_s) return RSH_OK;   // order stays the given one, objective not evaluated
+        if (reuse_test && n_s > 0 && pass.load() * 100 < n_s) return RSH_OK;   // order stays the given one, objective not evaluated
+        double best = 0.0, given = 0.0;   // summed in sample order: independent of the thread count
+        for (int64_t q = 0; q < n_s; ++q) best += best_of[(size_t)q], given += given_of[(size_t)q];
+        if (n_s > 0 && best < 0.03 * (double)n_s + 0.97 * given) {
+            *cost_given = *cost_found = path_cost(nullptr);
+            return RSH_OK;
+        }
     }
     build_index(nullptr);
 
@@ -586,28 +629,6 @@ int reorder_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vector
     order.insert(order.end(), empties.begin(), empties.end());
     if ((int64_t)order.size() != n) return RSH_ERR_INVALID_CSR;
 
-    // The objective of Section 3.4: sum of (1 - sim) over consecutive rows.  The heuristic is
-    // meant to lower it; the found order is used only when it lowers the objective by at least
-    // 3 % -- a smaller change means the given order was already as coherent (e.g. the natural
-    // order of a stencil), and permuting it would only disturb the locality it has.
-    // Summed over pieces of a fixed size, so that the value (and with it the 3 % decision and the
-    // plan) does not depend on the number of threads.
-    auto path_cost = [&](const std::vector<int32_t>* ord) {
-        constexpr int64_t kPiece = 4096;
-        const int64_t n_pieces = (n - 1 + kPiece - 1) / kPiece;
-        std::vector<double> part((size_t)n_pieces, 0.0);
-        parallel_dynamic(n_pieces, threads, 16, [&](int64_t b, int64_t e, int) {
-            for (int64_t q = b; q < e; ++q) {
-                double s = 0.0;
-                for (int64_t i = q * kPiece; i < std::min(n - 1, (q + 1) * kPiece); ++i)
-                    s += 1.0 - (ord ? sim((*ord)[(size_t)i], (*ord)[(size_t)i + 1]) : sim((int32_t)i, (int32_t)i + 1));
-                part[(size_t)q] = s;
-            }
-        });
-        double s = 0.0;
-        for (double x : part) s += x;
-        return s;
-    };
     *cost_given = path_cost(nullptr);
     *cost_found = path_cost(&order);
     if (*cost_found > 0.97 * *cost_given) std::iota(order.begin(), order.end(), 0);
