@@ -104,13 +104,29 @@ static int64_t own_columns(const rsh_csr_t& a, int32_t row, const int32_t* other
 
 static inline int64_t row_len(const rsh_csr_t& a, int32_t r) { return a.row_ptr[r + 1] - a.row_ptr[r]; }
 
-// Distinct columns over a set of rows.
-static int64_t union_size(const rsh_csr_t& a, const int32_t* rows, int n, std::vector<int32_t>& tmp) {
-    tmp.clear();
-    for (int i = 0; i < n; ++i)
-        if (rows[i] >= 0) tmp.insert(tmp.end(), a.col_idx + a.row_ptr[rows[i]], a.col_idx + a.row_ptr[rows[i] + 1]);
-    std::sort(tmp.begin(), tmp.end());
-    return std::unique(tmp.begin(), tmp.end()) - tmp.begin();
+// Distinct columns over a set of rows.  `seen` is the calling thread's own array of n_cols stamps
+// (created empty, sized on first use) and `stamp` its running call count: a column is new to a
+// call when it does not carry the call's stamp yet -- one pass over the entries, no sort.
+struct ColumnStamps {
+    std::vector<uint32_t> seen;
+    uint32_t stamp = 0;
+};
+static int64_t union_size(const rsh_csr_t& a, const int32_t* rows, int n, ColumnStamps& cs) {
+    if (cs.seen.size() != (size_t)a.n_cols || cs.stamp == 0xffffffffu) {
+        cs.seen.assign((size_t)a.n_cols, 0u);
+        cs.stamp = 0;
+    }
+    const uint32_t stamp = ++cs.stamp;
+    int64_t distinct = 0;
+    for (int i = 0; i < n; ++i) {
+        if (rows[i] < 0) continue;
+        for (int64_t p = a.row_ptr[rows[i]]; p < a.row_ptr[rows[i] + 1]; ++p) {
+            uint32_t& s = cs.seen[(size_t)a.col_idx[p]];
+            distinct += s != stamp;
+            s = stamp;
+        }
+    }
+    return distinct;
 }
 
 // Sampled test of whether taller windows pay.  Taller windows share one staged B tile among
@@ -122,7 +138,12 @@ int choose_window_rows(const rsh_csr_t& a, const Partition& part16) {
     const int64_t n_win = (int64_t)part16.win_row.size() / kW;
     if (n_win < 64) return kW;
     constexpr int kLevels = 5, kSpan = 16;
-    const int64_t n_groups = n_win / kSpan, n_samples = std::min<int64_t>(512, n_groups);
+    // up to 512 groups, fewer when the groups are large: about four million entries are looked at
+    int64_t per_group = 0;
+    for (int i = 0; i < kSpan * kW; ++i)
+        if (part16.win_row[(size_t)i] >= 0) per_group += row_len(a, part16.win_row[(size_t)i]);
+    const int64_t n_groups = n_win / kSpan;
+    const int64_t n_samples = std::min<int64_t>(std::min<int64_t>(512, n_groups), std::max<int64_t>(8, (4ll << 20) / std::max<int64_t>(1, per_group)));
     // seen[level][c] = last (sample, unit) stamp under which column c was counted at that merge level
     std::vector<int64_t> seen[kLevels];
     for (auto& v : seen) v.assign((size_t)a.n_cols, -1);
@@ -223,7 +244,7 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
     const int64_t n_groups = ((int64_t)win_pos.size() + W - 1) / W;
     std::vector<uint8_t> keep((size_t)n_groups, 1);
     parallel_chunks(n_groups, threads, [&](int64_t b, int64_t e, int) {
-        std::vector<int32_t> tmp;
+        ColumnStamps tmp;
         int32_t rows[kMaxWindowRows];
         for (int64_t g = b; g < e; ++g) {
             int cnt = 0;
@@ -256,7 +277,7 @@ void partition_rows(const rsh_csr_t& a, const rsh_plan_opts_t& o, const std::vec
         const int64_t n_lg = ((int64_t)long_pos.size() + W - 1) / W;
         std::vector<uint8_t> keep_l((size_t)n_lg, 0);
         parallel_chunks(n_lg, threads, [&](int64_t b, int64_t e, int) {
-            std::vector<int32_t> tmp;
+            ColumnStamps tmp;
             int32_t rows[kMaxWindowRows];
             for (int64_t g = b; g < e; ++g) {
                 int cnt = 0;
@@ -479,6 +500,39 @@ static inline uint32_t panel_unit_of(uint32_t row, uint32_t u, uint32_t nt) {
     return ((row / 32) * nt + u / kPanelK) * 2 + (u % kPanelK) / 16;
 }
 
+// Condensed column index of a window's columns without sorting its entries: the distinct columns
+// are collected on first sight (per-thread stamps), sorted, and ranked.
+struct WindowColumns {
+    std::vector<uint32_t> seen, rank;   // per column: stamp of the window that saw it last; its rank there
+    std::vector<int32_t> cols;          // the window's distinct columns, ascending
+    std::vector<uint32_t> count;        // entries per condensed column
+    std::vector<uint8_t> row_of;        // window row of a column's (last) entry
+    uint32_t stamp = 0;
+    void index(const rsh_csr_t& a, const int32_t* rows, int W) {
+        if (seen.size() != (size_t)a.n_cols || stamp == 0xffffffffu) {
+            seen.assign((size_t)a.n_cols, 0u);
+            rank.assign((size_t)a.n_cols, 0u);
+            stamp = 0;
+        }
+        ++stamp;
+        cols.clear();
+        for (int r = 0; r < W; ++r) {
+            if (rows[r] < 0) continue;
+            for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p) {
+                const int32_t c = a.col_idx[p];
+                if (seen[(size_t)c] != stamp) {
+                    seen[(size_t)c] = stamp;
+                    cols.push_back(c);
+                }
+            }
+        }
+        std::sort(cols.begin(), cols.end());
+        for (size_t u = 0; u < cols.size(); ++u) rank[(size_t)cols[u]] = (uint32_t)u;
+        count.assign(cols.size(), 0u);
+        row_of.assign(cols.size(), 0);
+    }
+};
+
 static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int threads,
                               int64_t* sum_cols, int64_t* nnz_tile) {
     const int W = plan.geo.win_rows, G = plan.geo.panel_groups;
@@ -488,30 +542,41 @@ static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPla
     std::vector<uint32_t> win_tiles((size_t)n_win);
     std::vector<uint64_t> win_ent((size_t)n_win), win_real((size_t)n_win);
     std::vector<int64_t> win_cols((size_t)n_win);
-    parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
-        std::vector<WinEntry> ent;
+    parallel_dynamic(n_win, threads, 1, [&](int64_t b, int64_t e, int) {
+        WindowColumns wc;
         std::vector<uint32_t> cnt;
         for (int64_t w = b; w < e; ++w) {
-            gather_window(a, &part.win_row[w * W], W, ent);
-            int64_t u = 0;
-            uint64_t prev_col = ~0ull;
-            for (const WinEntry& x : ent)
-                if ((x.key >> 8) != prev_col) prev_col = x.key >> 8, ++u;
-            const uint32_t nt = (uint32_t)((u + K - 1) / K);
+            const int32_t* rows = &part.win_row[w * W];
+            wc.index(a, rows, W);
+            const uint32_t nt = (uint32_t)((wc.cols.size() + K - 1) / K);
             cnt.assign((size_t)nt * 2 * G, 0);
-            u = -1;
-            prev_col = ~0ull;
-            for (const WinEntry& x : ent) {
-                if ((x.key >> 8) != prev_col) prev_col = x.key >> 8, ++u;
-                ++cnt[panel_unit_of((uint32_t)(x.key & 255), (uint32_t)u, nt)];
+            uint64_t real = 0;
+            for (int r = 0; r < W; ++r) {
+                if (rows[r] < 0) continue;
+                for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p) {
+                    const uint32_t u = wc.rank[(size_t)a.col_idx[p]];
+                    ++cnt[panel_unit_of((uint32_t)r, u, nt)];
+                    ++wc.count[u];
+                    wc.row_of[u] = (uint8_t)r;
+                    ++real;
+                }
             }
             uint64_t padded = 0;
             for (uint32_t c : cnt) padded += (c + 3u) & ~3u;
-            win_cols[w] = u + 1;
+            win_cols[w] = (int64_t)wc.cols.size();
             win_tiles[w] = nt;
-            win_real[w] = ent.size();
+            win_real[w] = real;
             win_ent[w] = padded;
-            count_singletons(ent, &plan.win_single_entries[(size_t)w], &plan.win_single_rows[(size_t)w]);
+            // columns that one row of the window names (the statistic of element-level routing)
+            uint64_t row_seen[4] = {0, 0, 0, 0};
+            int64_t singles = 0;
+            for (size_t u = 0; u < wc.cols.size(); ++u)
+                if (wc.count[u] == 1) {
+                    ++singles;
+                    row_seen[wc.row_of[u] >> 6] |= 1ull << (wc.row_of[u] & 63);
+                }
+            plan.win_single_entries[(size_t)w] = singles;
+            plan.win_single_rows[(size_t)w] = popc64(row_seen[0]) + popc64(row_seen[1]) + popc64(row_seen[2]) + popc64(row_seen[3]);
         }
     });
     plan.win_tile_off.assign((size_t)n_win + 1, 0);
@@ -535,59 +600,61 @@ static int pack_panel_windows(const rsh_csr_t& a, const Partition& part, HostPla
     plan.tile_val.clear();
     // pass 2: fill
     std::vector<uint32_t> win_max_unit((size_t)n_win, 0);
-    parallel_chunks(n_win, threads, [&](int64_t b, int64_t e, int) {
-        std::vector<WinEntry> ent;
-        std::vector<uint32_t> unit_of, start, fill;
+    parallel_dynamic(n_win, threads, 1, [&](int64_t b, int64_t e, int) {
+        WindowColumns wc;
+        std::vector<uint32_t> start, fill, half;
         for (int64_t w = b; w < e; ++w) {
-            gather_window(a, &part.win_row[w * W], W, ent);
             const uint32_t t0 = plan.win_tile_off[w], nt = plan.win_tile_off[w + 1] - t0;
             if (nt == 0) continue;
+            const int32_t* rows = &part.win_row[w * W];
+            wc.index(a, rows, W);
             const size_t nu = (size_t)nt * 2 * G;
-            unit_of.resize(ent.size());
-            start.assign(nu + 1, 0);
-            int64_t u = -1;
-            uint64_t prev_col = ~0ull;
-            for (size_t i = 0; i < ent.size(); ++i) {
-                const uint64_t c = ent[i].key >> 8;
-                if (c != prev_col) {
-                    prev_col = c;
-                    ++u;
-                    plan.tile_colid[(size_t)t0 * K + (size_t)u] = (int32_t)c;
-                }
-                unit_of[i] = panel_unit_of((uint32_t)(ent[i].key & 255), (uint32_t)u, nt);
-                ++start[unit_of[i] + 1];
-            }
-            const int64_t n_u = u + 1;
+            const int64_t n_u = (int64_t)wc.cols.size();
+            for (int64_t u = 0; u < n_u; ++u) plan.tile_colid[(size_t)t0 * K + (size_t)u] = wc.cols[(size_t)u];
             for (int64_t k = n_u; k < (int64_t)nt * K; ++k)   // padding columns repeat the last valid one
-                plan.tile_colid[(size_t)t0 * K + (size_t)k] = plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)];
+                plan.tile_colid[(size_t)t0 * K + (size_t)k] = wc.cols[(size_t)(n_u - 1)];
             // one run of consecutive columns that fills whole fragments: the kernel computes column ids
-            if (n_u == (int64_t)nt * K && plan.tile_colid[(size_t)t0 * K + (size_t)(n_u - 1)] - plan.tile_colid[(size_t)t0 * K] == n_u - 1)
-                plan.panel_col0[(size_t)w] = plan.tile_colid[(size_t)t0 * K];
+            if (n_u == (int64_t)nt * K && wc.cols[(size_t)(n_u - 1)] - wc.cols[0] == n_u - 1) plan.panel_col0[(size_t)w] = wc.cols[0];
+            // Entries come row by row, columns ascending; a cell's address orders a unit by (half of
+            // the K step, row, column): counting the two halves of every unit apart puts each entry
+            // straight into its final place.
+            half.assign(2 * nu, 0);
+            for (int r = 0; r < W; ++r) {
+                if (rows[r] < 0) continue;
+                for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p) {
+                    const uint32_t u = wc.rank[(size_t)a.col_idx[p]];
+                    ++half[2 * panel_unit_of((uint32_t)r, u, nt) + ((u % 16) / 8)];
+                }
+            }
+            start.assign(nu + 1, 0);
             uint32_t most = 0;
-            for (size_t q = 1; q <= nu; ++q) {   // start[q] = padded entries of units before q
-                const uint32_t padded = (start[q] + 3u) & ~3u;
+            for (size_t q = 0; q < nu; ++q) {   // start[q] = padded entries of units before q
+                const uint32_t padded = (half[2 * q] + half[2 * q + 1] + 3u) & ~3u;
                 most = std::max(most, padded);
-                start[q] = start[q - 1] + padded;
+                start[q + 1] = start[q] + padded;
             }
             win_max_unit[(size_t)w] = most;
             const size_t ub = (size_t)t0 * 2 * G;
             for (size_t q = 0; q < nu; ++q) plan.panel_off[ub + q] = (uint32_t)(win_ent_off[w] + start[q]);
-            // entries arrive sorted by (column, row); inside a unit they are stored by cell address
             uint32_t* out = &plan.panel_ent[(size_t)win_ent_off[w]];
-            fill.assign(start.begin(), start.end() - 1);
-            u = -1;
-            prev_col = ~0ull;
-            for (size_t i = 0; i < ent.size(); ++i) {
-                if ((ent[i].key >> 8) != prev_col) prev_col = ent[i].key >> 8, ++u;
-                const uint32_t k = (uint32_t)u % K, r = (uint32_t)(ent[i].key & 255);
-                const uint32_t lane = (r % 32) + 32 * ((k % 16) / 8), addr = (lane * 8 + k % 8) * 2;
-                out[fill[unit_of[i]]++] = (addr << 16) | ent[i].val;
+            fill.resize(2 * nu);
+            for (size_t q = 0; q < nu; ++q) {
+                fill[2 * q] = start[q];
+                fill[2 * q + 1] = start[q] + half[2 * q];
+            }
+            for (int r = 0; r < W; ++r) {
+                if (rows[r] < 0) continue;
+                for (int64_t p = a.row_ptr[rows[r]]; p < a.row_ptr[rows[r] + 1]; ++p) {
+                    const uint32_t u = wc.rank[(size_t)a.col_idx[p]], k = u % K;
+                    const uint32_t lane = ((uint32_t)r % 32) + 32 * ((k % 16) / 8), addr = (lane * 8 + k % 8) * 2;
+                    out[fill[2 * panel_unit_of((uint32_t)r, u, nt) + ((k % 16) / 8)]++] = (addr << 16) | a.val_f16[p];
+                }
             }
             for (size_t q = 0; q < nu; ++q) {
-                std::sort(out + start[q], out + fill[q]);
                 // padding: address 1024 * (2 - h) + 4 * j lands in the wave's spare words behind its two tiles
                 const uint32_t h = (uint32_t)(q & 1);
-                for (uint32_t j = 0; fill[q] < start[q + 1]; ++j) out[fill[q]++] = (1024u * (2u - h) + 4u * j) << 16;
+                uint32_t at = fill[2 * q + 1];
+                for (uint32_t j = 0; at < start[q + 1]; ++j) out[at++] = (1024u * (2u - h) + 4u * j) << 16;
             }
         }
     });
