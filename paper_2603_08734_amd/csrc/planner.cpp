@@ -922,17 +922,21 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
     bool any_partitioned = false;
     if (xp_min > 0) {
         std::vector<uint32_t> cnt((size_t)a.n_cols, 0);
-        for (int64_t i = 0; i < n_long; ++i) {
-            const int32_t r = long_rows[(size_t)i];
-            if (row_len(a, r) < xp_min) continue;
-            any_partitioned = true;
-            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) ++cnt[(size_t)a.col_idx[p]];
-        }
+        for (int64_t i = 0; i < n_long && !any_partitioned; ++i) any_partitioned = row_len(a, long_rows[(size_t)i]) >= xp_min;
+        if (any_partitioned)   // entries per column over the rows that will be cut (counts: the order of the additions does not matter)
+            parallel_dynamic(n_long, threads, 256, [&](int64_t b, int64_t e, int) {
+                for (int64_t i = b; i < e; ++i) {
+                    const int32_t r = long_rows[(size_t)i];
+                    if (row_len(a, r) < xp_min) continue;
+                    for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p)
+                        __atomic_fetch_add(&cnt[(size_t)a.col_idx[p]], 1u, __ATOMIC_RELAXED);
+                }
+            });
         if (any_partitioned) {
             std::vector<int32_t> used;
             for (int64_t c = 0; c < a.n_cols; ++c)
                 if (cnt[(size_t)c]) used.push_back((int32_t)c);
-            std::sort(used.begin(), used.end(), [&](int32_t x, int32_t y) {
+            parallel_sort(used.begin(), used.end(), threads, [&](int32_t x, int32_t y) {
                 return cnt[(size_t)x] != cnt[(size_t)y] ? cnt[(size_t)x] > cnt[(size_t)y] : x < y;
             });
             col_group.assign((size_t)a.n_cols, 0);
@@ -952,7 +956,8 @@ int pack_plan(const rsh_csr_t& a, const Partition& part, HostPlan& plan, int thr
 
     plan.irr_col.assign((size_t)(nnz_irr + n_spilled) + 64, 0);   // tail pad keeps lane-wise reads in bounds
     plan.irr_val.assign((size_t)(nnz_irr + n_spilled) + 64, 0);
-    parallel_chunks(n_irr, threads, [&](int64_t b, int64_t e, int) {
+    // dynamic pieces: the long rows stand first in the stream, equal shares of rows would not be equal work
+    parallel_dynamic(n_irr, threads, 1024, [&](int64_t b, int64_t e, int) {
         for (int64_t i = b; i < e; ++i) {
             const int32_t r = stream_rows[(size_t)i];
             const int64_t len = row_len(a, r);
